@@ -1,0 +1,134 @@
+/*
+ * csrk — FP32 CSR sparse kernels for AMD Instinct MI355X (gfx950):
+ *   SPMM     O = S . B                       (paper eq. (2), Algorithm 2)
+ *   SDDMM    P = S (.) (A . B^T) on S's pattern  (paper eq. (1), Algorithm 1)
+ *   FusedMM  O = (S (.) (A . B^T)) . C       (paper eq. (3), Algorithm 3)
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every pointer is a DEVICE pointer owned by the caller and valid on the
+ *    device that is current when the call is made.  Nothing is copied to or
+ *    from the host.
+ *  - S is M x K in compressed sparse row form exactly as in the paper's section
+ *    "Matrix Storage Layout" (Fig. 1): `rowptr` has M+1 int32 entries, 0-based,
+ *    non-decreasing, rowptr[0] = 0 and rowptr[M] = nnz; `colidx` has nnz int32
+ *    column indices in [0, K); `vals` has nnz FP32 values in the same order.
+ *    Entries of a row may be in any order and may repeat (SPMM/FusedMM add
+ *    repeated entries up, SDDMM yields one result per stored entry); explicitly
+ *    stored zeros are ordinary entries.  The library reads nnz from rowptr[M] on
+ *    the device.  Index contents are not validated by the compute calls: an
+ *    out-of-range index or a decreasing rowptr is undefined behaviour (use
+ *    csrk_validate_csr first when inputs are untrusted).
+ *  - Dense matrices are FP32, row-major and contiguous (leading dimension = row
+ *    length).
+ *  - Calls are asynchronous: work is enqueued on `stream` and the call returns
+ *    without synchronising.  Inputs must stay valid and unchanged, and outputs
+ *    untouched, until the stream has passed the enqueued work.
+ *  - Outputs are overwritten (there is no alpha/beta; Algorithm 2 starts from a
+ *    zero row).  Rows of S with no entries give zero rows of O.  M == 0, N == 0,
+ *    D == 0 or nnz == 0 are valid: with D == 0 every dot product is empty (0).
+ *  - O must not overlap any input.  P may be the same array as vals (the
+ *    paper's SDDMM overwrites the values of the sparse matrix in place).
+ *  - SPMM and FusedMM use a per-device scratch area owned by the library for
+ *    partial rows; it is allocated (hipMalloc, which synchronises) the first time
+ *    it is needed or has to grow, and kept until csrk_release_workspace or process
+ *    exit.  Two calls in flight at once on different streams of one device would
+ *    share it and race: serialise such calls on one stream.  Results do not
+ *    depend on timing: partial rows are combined in a fixed order.
+ *  - Return value: CSRK_OK or an error code; csrk_last_error() then gives a
+ *    message for the calling thread.  On error nothing has been enqueued.
+ *  - Any N >= 1 and D >= 1 work.  Widths that are multiples of 4 with 16-byte
+ *    aligned dense pointers take the fast (128-bit access) kernels.
+ */
+#ifndef CSRK_H
+#define CSRK_H
+
+#include <stdint.h>
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int csrk_status;
+#define CSRK_OK            0
+#define CSRK_INVALID_ARG   1   /* negative size, null pointer where one is required, bad alignment */
+#define CSRK_UNSUPPORTED   2   /* a size beyond what the kernels' 32-bit indexing covers */
+#define CSRK_HIP_ERROR     3   /* a HIP runtime call failed; message has the HIP error string */
+#define CSRK_WORKSPACE     4   /* the scratch area could not be allocated */
+
+/*
+ * SPMM, paper eq. (2) / Algorithm 2:
+ *   O[i, :] = sum over stored entries j of row i of  vals[j] * B[colidx[j], :]
+ * S is M x K (rowptr/colidx/vals), B is K x N, O is M x N (overwritten).
+ * vals must not be NULL.
+ */
+csrk_status spmm_csr(int M, int K, int N,
+                     const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                     const float *B, float *O, hipStream_t stream);
+
+/*
+ * SDDMM, paper eq. (1) / Algorithm 1, with the sampled product scaled by S's
+ * stored values:
+ *   P[j] = vals[j] * <A[i, :], B[colidx[j], :]>   for every stored entry j of row i
+ * A is M x D, B is K x D (used as B^T), P has nnz entries in the order of
+ * colidx.  vals == NULL means an all-ones pattern, which is the paper's I_A.
+ * P may alias vals.
+ */
+csrk_status sddmm_csr(int M, int K, int D,
+                      const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                      const float *A, const float *B, float *P, hipStream_t stream);
+
+/*
+ * FusedMM, paper eq. (3) / Algorithm 3: SDDMM followed by SPMM with the sampled
+ * scores kept on chip (never written to device memory):
+ *   O[i, :] = sum_j ( vals[j] * <A[i, :], B[colidx[j], :]> ) * C[colidx[j], :]
+ * A is M x D, B is K x D, C is K x N, O is M x N (overwritten).  The paper has
+ * D == N; here the dot length D and the output width N are independent.
+ * vals == NULL means an all-ones pattern.
+ */
+csrk_status fusedmm_csr(int M, int K, int D, int N,
+                        const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *A, const float *B, const float *C,
+                        float *O, hipStream_t stream);
+
+/*
+ * Debug helper for untrusted inputs (the paper's storage rules, Fig. 1): checks
+ * on the device that rowptr[0] == 0, rowptr is non-decreasing and every colidx
+ * is in [0, K).  Synchronises `stream`.  *problems receives a bit mask:
+ * 1 rowptr[0] != 0, 2 rowptr decreases somewhere, 4 a column index is out of
+ * range; *sorted receives 1 if the columns of every row are strictly ascending
+ * (only meaningful when *problems == 0).  Either pointer may be NULL (host pointers).
+ */
+csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t *colidx,
+                              hipStream_t stream, int *problems, int *sorted);
+
+/*
+ * Benchmark aid (not part of the paper's method; it mirrors the paper's practice of
+ * timing each kernel on its own, section "Experiments").  csrk_profile_enable(n)
+ * with n > 0 creates n pairs of HIP events; from then on every spmm_csr / sddmm_csr /
+ * fusedmm_csr call on this thread's current device records one pair on the call's
+ * stream, immediately before and after its main kernel (the combine pass of partial
+ * rows is outside the pair), until the pairs are used up.  csrk_profile_enable(0)
+ * destroys the events and switches recording off.
+ * csrk_profile_collect waits for the recorded pairs, writes up to `capacity`
+ * elapsed times in milliseconds to ms[] and the operation of each to kinds[]
+ * (1 SPMM, 2 SDDMM, 3 FusedMM) in call order, stores the number written in *count
+ * and resets the recorder.  ms, kinds and count are host pointers.
+ */
+csrk_status csrk_profile_enable(int max_records);
+csrk_status csrk_profile_collect(float *ms, int *kinds, int capacity, int *count);
+
+/* Frees the calling device's scratch area (synchronises the device). */
+csrk_status csrk_release_workspace(void);
+
+/* Message of the last error on the calling thread ("" if none). Host string owned by the library. */
+const char *csrk_last_error(void);
+
+/* Library version string, e.g. "csrk 0.1 gfx950". */
+const char *csrk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSRK_H */

@@ -1,0 +1,171 @@
+"""Python binding of the csrk C-ABI (include/csrk.h): argument marshalling only.
+
+Every function takes torch CUDA tensors (torch is used for device memory and
+streams, nothing else), checks dtype / shape / contiguity / device, and passes raw
+device pointers plus the current HIP stream to the library.  All arithmetic runs in
+the library's HIP kernels.  If `libcsrk.so` is missing or cannot be loaded the import
+of a function from here raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcsrk.so")
+
+CSRK_OK = 0
+
+_lib = None
+
+
+class CsrkError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"csrk error {code}: {msg}")
+        self.code = code
+
+
+def load(build_if_missing: bool = True):
+    """Load libcsrk.so (building it with hipcc first only if the file is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2311_00368_amd.build`")
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    i, p = ctypes.c_int, ctypes.c_void_p
+    lib.spmm_csr.argtypes = [i, i, i, p, p, p, p, p, p]
+    lib.sddmm_csr.argtypes = [i, i, i, p, p, p, p, p, p, p]
+    lib.fusedmm_csr.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p]
+    lib.csrk_validate_csr.argtypes = [i, i, p, p, p, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.csrk_release_workspace.argtypes = []
+    lib.csrk_profile_enable.argtypes = [i]
+    lib.csrk_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i,
+                                         ctypes.POINTER(ctypes.c_int)]
+    for f in (lib.spmm_csr, lib.sddmm_csr, lib.fusedmm_csr, lib.csrk_validate_csr, lib.csrk_release_workspace,
+              lib.csrk_profile_enable, lib.csrk_profile_collect):
+        f.restype = ctypes.c_int
+    lib.csrk_last_error.restype = ctypes.c_char_p
+    lib.csrk_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(code: int):
+    if code != CSRK_OK:
+        raise CsrkError(code, load().csrk_last_error().decode())
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype, shape=None, device=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a CUDA tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if device is not None and t.device != device:
+        raise ValueError(f"{name} is on {t.device}, expected {device}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _csr_ptrs(M: int, rowptr, colidx, vals, need_vals: bool):
+    dev = rowptr.device
+    rp = _dev_ptr(rowptr, "rowptr", torch.int32, (M + 1,))
+    nnz = colidx.numel()
+    ci = _dev_ptr(colidx, "colidx", torch.int32, (nnz,), dev)
+    if vals is None and need_vals:
+        raise ValueError("vals is required")
+    va = _dev_ptr(vals, "vals", torch.float32, (nnz,), dev)
+    return dev, nnz, rp, ci, va
+
+
+def csrk_version() -> str:
+    return load().csrk_version().decode()
+
+
+def csrk_last_error() -> str:
+    return load().csrk_last_error().decode()
+
+
+def spmm_csr(M: int, K: int, N: int, rowptr, colidx, vals, B, O=None) -> torch.Tensor:
+    """O = S.B on the current stream; returns O (allocated M x N if not given)."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, True)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.spmm_csr(M, K, N, rp, ci, va, _dev_ptr(B, "B", torch.float32, (K, N), dev),
+                            _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+def sddmm_csr(M: int, K: int, D: int, rowptr, colidx, vals, A, B, P=None) -> torch.Tensor:
+    """P = S (.) (A.B^T) on S's pattern (vals=None: all-ones pattern); returns P (nnz floats).
+    P may be `vals` itself for the in-place form."""
+    lib = load()
+    dev, nnz, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if P is None:
+        P = torch.empty((nnz,), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.sddmm_csr(M, K, D, rp, ci, va, _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                             _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                             _dev_ptr(P, "P", torch.float32, (nnz,), dev), _stream(dev)))
+    return P
+
+
+def fusedmm_csr(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O=None) -> torch.Tensor:
+    """O = (S (.) (A.B^T)).C on the current stream; returns O (M x N)."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.fusedmm_csr(M, K, D, N, rp, ci, va, _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                               _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                               _dev_ptr(C, "C", torch.float32, (K, N), dev),
+                               _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+def csrk_validate_csr(M: int, K: int, rowptr, colidx) -> Tuple[int, bool]:
+    """Device-side structural check; returns (problem bit mask, columns strictly ascending)."""
+    lib = load()
+    dev = rowptr.device
+    rp = _dev_ptr(rowptr, "rowptr", torch.int32, (M + 1,))
+    ci = _dev_ptr(colidx, "colidx", torch.int32, None, dev)
+    problems, is_sorted = ctypes.c_int(0), ctypes.c_int(0)
+    with torch.cuda.device(dev):
+        _check(lib.csrk_validate_csr(M, K, rp, ci, _stream(dev), ctypes.byref(problems), ctypes.byref(is_sorted)))
+    return problems.value, bool(is_sorted.value)
+
+
+def csrk_release_workspace() -> None:
+    _check(load().csrk_release_workspace())
+
+
+def csrk_profile_enable(max_records: int) -> None:
+    _check(load().csrk_profile_enable(max_records))
+
+
+def csrk_profile_collect(capacity: int = 4096):
+    """Returns [(kind, milliseconds), ...] for the recorded main-kernel launches, in call order
+    (kind: 1 SPMM, 2 SDDMM, 3 FusedMM)."""
+    ms = (ctypes.c_float * capacity)()
+    kinds = (ctypes.c_int * capacity)()
+    n = ctypes.c_int(0)
+    _check(load().csrk_profile_collect(ms, kinds, capacity, ctypes.byref(n)))
+    return [(kinds[t], ms[t]) for t in range(n.value)]

@@ -1,0 +1,409 @@
+// C-ABI of the csrk library (declared in include/csrk.h): argument checks, kernel
+// selection by dense width and alignment, per-device scratch for partial rows, launches.
+#include "../../include/csrk.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "kernels_nnzsplit.hpp"
+
+namespace {
+
+using namespace csrk;
+
+thread_local char g_err[512] = "";
+
+csrk_status fail(csrk_status code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define CSRK_HIP(call)                                                                          \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(CSRK_HIP_ERROR, "%s failed: %s", #call, hipGetErrorString(e_));         \
+    } while (0)
+
+constexpr int kMaxDevices = 64;
+
+struct DeviceState {
+    bool init = false;
+    int workers = 0;        // wavefronts the equal-nonzero split is cut into
+    float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way
+    int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
+    size_t head_floats = 0;
+};
+
+DeviceState g_dev[kMaxDevices];
+std::mutex g_mu;
+
+// optional per-call event pairs around the main kernels (csrk_profile_enable)
+struct Recorder {
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> kind;
+    int used = 0;
+};
+Recorder g_rec;
+
+struct ScopedRecord {
+    int slot = -1;
+    hipStream_t st;
+    ScopedRecord(int kind, hipStream_t s) : st(s) {
+        if (g_rec.used < (int)g_rec.start.size()) {
+            slot = g_rec.used++;
+            g_rec.kind[slot] = kind;
+            (void)hipEventRecord(g_rec.start[slot], st);
+        }
+    }
+    void end() {
+        if (slot >= 0) (void)hipEventRecord(g_rec.stop[slot], st);
+        slot = -1;
+    }
+};
+
+int env_int(const char *name, int dflt) {
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    const long v = strtol(s, nullptr, 10);
+    return v > 0 ? (int)v : dflt;
+}
+
+csrk_status device_state(DeviceState **out) {
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CSRK_UNSUPPORTED, "device ordinal %d not supported", dev);
+    DeviceState &d = g_dev[dev];
+    if (!d.init) {
+        int cus = 0;
+        CSRK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        // 8 wavefronts per SIMD, 4 SIMDs per CU: every CU gets a full complement of shares
+        int workers = env_int("CSRK_WORKERS", cus * 32);
+        workers = (workers + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
+        d.workers = workers;
+        d.init = true;
+    }
+    *out = &d;
+    return CSRK_OK;
+}
+
+// scratch for `width` columns of partial rows; grows, never shrinks
+csrk_status ensure_scratch(DeviceState &d, int width) {
+    const size_t need = (size_t)d.workers * (size_t)width;
+    if (!d.head_row) {
+        if (hipMalloc((void **)&d.head_row, sizeof(int32_t) * ((size_t)d.workers + 16)) != hipSuccess) {
+            d.head_row = nullptr;
+            return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", sizeof(int32_t) * ((size_t)d.workers + 16));
+        }
+    }
+    if (need > d.head_floats) {
+        if (d.head) {
+            CSRK_HIP(hipDeviceSynchronize());
+            CSRK_HIP(hipFree(d.head));
+            d.head = nullptr;
+            d.head_floats = 0;
+        }
+        if (hipMalloc((void **)&d.head, need * sizeof(float)) != hipSuccess) {
+            d.head = nullptr;
+            return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", need * sizeof(float));
+        }
+        d.head_floats = need;
+    }
+    return CSRK_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+csrk_status check_dims(const char *fn, int M, int K, long long w1, long long w2) {
+    if (M < 0 || K < 0 || w1 < 0 || w2 < 0) return fail(CSRK_INVALID_ARG, "%s: negative dimension", fn);
+    // element offsets into dense operands are formed in 64 bits, row/column numbers in 32
+    if ((long long)M >= (1ll << 31) - 1 || (long long)K >= (1ll << 31) - 1 || w1 >= (1ll << 24) || w2 >= (1ll << 24))
+        return fail(CSRK_UNSUPPORTED, "%s: dimension too large", fn);
+    return CSRK_OK;
+}
+
+// --- kernel selection ---------------------------------------------------------------
+// A dense width W is covered by groups of LG lanes holding VEC floats each (T tiles per
+// lane).  Fast path: W % 4 == 0 and 16-byte aligned operands -> 128-bit accesses.
+struct WidthCfg {
+    int vec, lg, t;
+};
+
+WidthCfg out_width_cfg(int N, bool vec4) {
+    if (vec4) {
+        if (N <= 64) return {4, 16, 1};
+        if (N <= 128) return {4, 32, 1};
+        if (N <= 256) return {4, 64, 1};
+        return {4, 64, 2};
+    }
+    return {1, 64, 1};
+}
+
+WidthCfg dot_width_cfg(int D, bool vec4) {
+    if (vec4) {
+        if (D <= 64) return {4, 16, 1};
+        if (D <= 128) return {4, 32, 1};
+        if (D <= 256) return {4, 64, 1};
+        return {4, 64, 0};
+    }
+    return {1, 64, 0};
+}
+
+template <int VEC, int LG, int T>
+void launch_spmm(dim3 grid, hipStream_t st, int M, int N, const int32_t *rp, const int32_t *ci, const float *v,
+                 const float *B, float *O, float *head, int32_t *head_row) {
+    hipLaunchKernelGGL((spmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, N, rp, ci, v, B, O,
+                       head, head_row);
+}
+
+template <int VEC, int LG, int T>
+void launch_sddmm(dim3 grid, hipStream_t st, int M, int D, const int32_t *rp, const int32_t *ci, const float *v,
+                  const float *A, const float *B, float *P) {
+    hipLaunchKernelGGL((sddmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, D, rp, ci, v, A, B,
+                       P);
+}
+
+template <int VD, int LD, int TD, int VN, int LN, int TN>
+void launch_fused(dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp, const int32_t *ci,
+                  const float *v, const float *A, const float *B, const float *C, float *O, float *head,
+                  int32_t *head_row) {
+    hipLaunchKernelGGL((fusedmm_nnzsplit_kernel<VD, LD, TD, VN, LN, TN>), grid, dim3(kBlockThreads), 0, st, M, D, N,
+                       rp, ci, v, A, B, C, O, head, head_row);
+}
+
+template <int VD, int LD, int TD>
+bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp,
+                    const int32_t *ci, const float *v, const float *A, const float *B, const float *C, float *O,
+                    float *head, int32_t *head_row) {
+#define CSRK_FUSED_CASE(VN, LN, TN)                                                                         \
+    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                        \
+        launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row);     \
+        return true;                                                                                        \
+    }
+    CSRK_FUSED_CASE(4, 16, 1)
+    CSRK_FUSED_CASE(4, 32, 1)
+    CSRK_FUSED_CASE(4, 64, 1)
+    CSRK_FUSED_CASE(4, 64, 2)
+    CSRK_FUSED_CASE(1, 64, 1)
+#undef CSRK_FUSED_CASE
+    return false;
+}
+
+void launch_combine(DeviceState &d, hipStream_t st, int N, float *O) {
+    const int ytiles = (N + kBlockThreads - 1) / kBlockThreads;
+    hipLaunchKernelGGL(combine_heads_kernel, dim3(d.workers, ytiles < 8 ? ytiles : 8), dim3(kBlockThreads), 0, st, N,
+                       d.workers, O, d.head, d.head_row);
+}
+
+// --- validation kernels -------------------------------------------------------------
+__global__ void validate_rowptr_kernel(int M, const int32_t *rowptr, int32_t *flags) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0 && rowptr[0] != 0) atomicOr(flags, 1);
+    if (i < M && rowptr[i + 1] < rowptr[i]) atomicOr(flags, 2);
+}
+
+__global__ void validate_colidx_kernel(int M, int K, const int32_t *rowptr, const int32_t *colidx, int32_t *flags) {
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int r = wave; r < M; r += nwaves) {
+        const int rs = rowptr[r], re = rowptr[r + 1];
+        for (int j = rs + lane; j < re; j += 64) {
+            const int k = colidx[j];
+            if (k < 0 || k >= K) atomicOr(flags, 4);
+            if (j > rs && colidx[j - 1] >= k) atomicOr(flags + 1, 1);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *csrk_last_error(void) { return g_err; }
+
+const char *csrk_version(void) { return "csrk 0.1 gfx950"; }
+
+csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                     const float *B, float *O, hipStream_t stream) {
+    if (csrk_status s = check_dims("spmm_csr", M, K, N, 0)) return s;
+    if (M == 0 || N == 0) return CSRK_OK;
+    if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr: rowptr and O must not be NULL");
+    if (!vals) return fail(CSRK_INVALID_ARG, "spmm_csr: vals must not be NULL");
+    if (K > 0 && (!colidx || !B)) return fail(CSRK_INVALID_ARG, "spmm_csr: colidx and B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    if (csrk_status s = ensure_scratch(*d, N)) return s;
+    const bool vec4 = (N % 4 == 0) && aligned16(B) && aligned16(O) && aligned16(d->head);
+    const WidthCfg c = out_width_cfg(N, vec4);
+    const int tile = c.vec * c.lg * c.t;
+    const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
+    ScopedRecord rec(1, stream);
+#define CSRK_SPMM_CASE(V, L, T)                                                                           \
+    if (c.vec == V && c.lg == L && c.t == T)                                                              \
+        launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row);
+    CSRK_SPMM_CASE(4, 16, 1)
+    CSRK_SPMM_CASE(4, 32, 1)
+    CSRK_SPMM_CASE(4, 64, 1)
+    CSRK_SPMM_CASE(4, 64, 2)
+    CSRK_SPMM_CASE(1, 64, 1)
+#undef CSRK_SPMM_CASE
+    rec.end();
+    CSRK_HIP(hipGetLastError());
+    launch_combine(*d, stream, N, O);
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                      const float *A, const float *B, float *P, hipStream_t stream) {
+    if (csrk_status s = check_dims("sddmm_csr", M, K, D, 0)) return s;
+    if (M == 0 || K == 0) return CSRK_OK;
+    if (!rowptr || !colidx || !P) return fail(CSRK_INVALID_ARG, "sddmm_csr: rowptr, colidx and P must not be NULL");
+    if (D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "sddmm_csr: A and B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    const bool vec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
+    const WidthCfg c = dot_width_cfg(D, vec4);
+    const dim3 grid(d->workers / kWavesPerBlock);
+    ScopedRecord rec(2, stream);
+#define CSRK_SDDMM_CASE(V, L, T)                                                  \
+    if (c.vec == V && c.lg == L && c.t == T)                                      \
+        launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P);
+    CSRK_SDDMM_CASE(4, 16, 1)
+    CSRK_SDDMM_CASE(4, 32, 1)
+    CSRK_SDDMM_CASE(4, 64, 1)
+    CSRK_SDDMM_CASE(4, 64, 0)
+    CSRK_SDDMM_CASE(1, 64, 0)
+#undef CSRK_SDDMM_CASE
+    rec.end();
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *A, const float *B, const float *C, float *O, hipStream_t stream) {
+    if (csrk_status s = check_dims("fusedmm_csr", M, K, D, N)) return s;
+    if (M == 0 || N == 0) return CSRK_OK;
+    if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr: rowptr and O must not be NULL");
+    if (K > 0 && (!colidx || !C)) return fail(CSRK_INVALID_ARG, "fusedmm_csr: colidx and C must not be NULL");
+    if (K > 0 && D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "fusedmm_csr: A and B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    if (csrk_status s = ensure_scratch(*d, N)) return s;
+    const bool dvec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
+    const bool nvec4 = (N % 4 == 0) && aligned16(C) && aligned16(O) && aligned16(d->head);
+    const WidthCfg dc = dot_width_cfg(D, dvec4);
+    const WidthCfg nc = out_width_cfg(N, nvec4);
+    const int tile = nc.vec * nc.lg * nc.t;
+    const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
+    bool done = false;
+    ScopedRecord rec(3, stream);
+#define CSRK_DOT_CASE(V, L, T)                                                                            \
+    if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                  \
+        done = launch_fused_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head, \
+                                       d->head_row);
+    CSRK_DOT_CASE(4, 16, 1)
+    CSRK_DOT_CASE(4, 32, 1)
+    CSRK_DOT_CASE(4, 64, 1)
+    CSRK_DOT_CASE(4, 64, 0)
+    CSRK_DOT_CASE(1, 64, 0)
+#undef CSRK_DOT_CASE
+    rec.end();
+    if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
+    CSRK_HIP(hipGetLastError());
+    launch_combine(*d, stream, N, O);
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t *colidx, hipStream_t stream,
+                              int *problems, int *sorted) {
+    if (M < 0 || K < 0) return fail(CSRK_INVALID_ARG, "csrk_validate_csr: negative dimension");
+    if (!rowptr) return fail(CSRK_INVALID_ARG, "csrk_validate_csr: rowptr must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    if (csrk_status s = ensure_scratch(*d, 1)) return s;
+    int32_t *flags = d->head_row + d->workers;    // two spare words behind the worker table
+    int32_t host[2] = {0, 0};
+    CSRK_HIP(hipMemcpyAsync(flags, host, sizeof(host), hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(validate_rowptr_kernel, dim3(M / 256 + 1), dim3(256), 0, stream, M, rowptr, flags);
+    CSRK_HIP(hipGetLastError());
+    CSRK_HIP(hipMemcpyAsync(host, flags, sizeof(host), hipMemcpyDeviceToHost, stream));
+    CSRK_HIP(hipStreamSynchronize(stream));
+    if (host[0] == 0 && M > 0 && colidx) {       // only walk colidx under a sane rowptr
+        hipLaunchKernelGGL(validate_colidx_kernel, dim3(1024), dim3(256), 0, stream, M, K, rowptr, colidx, flags);
+        CSRK_HIP(hipGetLastError());
+        CSRK_HIP(hipMemcpyAsync(host, flags, sizeof(host), hipMemcpyDeviceToHost, stream));
+        CSRK_HIP(hipStreamSynchronize(stream));
+    }
+    if (problems) *problems = host[0];
+    if (sorted) *sorted = host[1] == 0;
+    return CSRK_OK;
+}
+
+csrk_status csrk_profile_enable(int max_records) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (hipEvent_t e : g_rec.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_rec.stop) (void)hipEventDestroy(e);
+    g_rec.start.clear();
+    g_rec.stop.clear();
+    g_rec.kind.clear();
+    g_rec.used = 0;
+    if (max_records < 0) return fail(CSRK_INVALID_ARG, "csrk_profile_enable: negative count");
+    for (int i = 0; i < max_records; ++i) {
+        hipEvent_t a, b;
+        CSRK_HIP(hipEventCreate(&a));
+        CSRK_HIP(hipEventCreate(&b));
+        g_rec.start.push_back(a);
+        g_rec.stop.push_back(b);
+        g_rec.kind.push_back(0);
+    }
+    return CSRK_OK;
+}
+
+csrk_status csrk_profile_collect(float *ms, int *kinds, int capacity, int *count) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!count || capacity < 0 || (capacity > 0 && (!ms || !kinds)))
+        return fail(CSRK_INVALID_ARG, "csrk_profile_collect: bad arguments");
+    int n = 0;
+    for (int i = 0; i < g_rec.used && n < capacity; ++i) {
+        CSRK_HIP(hipEventSynchronize(g_rec.stop[i]));
+        CSRK_HIP(hipEventElapsedTime(&ms[n], g_rec.start[i], g_rec.stop[i]));
+        kinds[n] = g_rec.kind[i];
+        ++n;
+    }
+    *count = n;
+    g_rec.used = 0;
+    return CSRK_OK;
+}
+
+csrk_status csrk_release_workspace(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CSRK_OK;
+    DeviceState &d = g_dev[dev];
+    CSRK_HIP(hipDeviceSynchronize());
+    if (d.head) CSRK_HIP(hipFree(d.head));
+    if (d.head_row) CSRK_HIP(hipFree(d.head_row));
+    d.head = nullptr;
+    d.head_row = nullptr;
+    d.head_floats = 0;
+    return CSRK_OK;
+}
+
+}  // extern "C"

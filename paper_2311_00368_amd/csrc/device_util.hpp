@@ -1,0 +1,111 @@
+// Device-side helpers shared by the gfx950 kernels: wave64 lane utilities, DPP
+// reductions, vector loads, the equal-nonzero work partition and the wave-wide
+// search that maps a nonzero position to its row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace csrk {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ float readlane_f(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over groups of LG consecutive lanes (LG a power of two, <= 64); every lane of
+// a group ends up with the group's sum.  The first four steps stay inside a row of 16
+// lanes and use DPP (quad permutes, half-row mirror, row mirror); wider groups finish
+// with cross-row exchanges.
+template <int LG>
+__device__ __forceinline__ float group_sum(float v) {
+    if (LG >= 2) v += dpp_f<0xB1>(v);    // quad_perm [1,0,3,2]
+    if (LG >= 4) v += dpp_f<0x4E>(v);    // quad_perm [2,3,0,1]
+    if (LG >= 8) v += dpp_f<0x141>(v);   // row_half_mirror
+    if (LG >= 16) v += dpp_f<0x140>(v);  // row_mirror
+    if (LG >= 32) v += __shfl_xor(v, 16);
+    if (LG >= 64) v += __shfl_xor(v, 32);
+    return v;
+}
+
+// VEC consecutive floats; VEC == 4 is one 128-bit access (address must be 16-byte aligned).
+template <int VEC>
+__device__ __forceinline__ void load_vec(const float *p, float (&d)[VEC]) {
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) d[i] = p[i];
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *p, const float (&d)[VEC]) {
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(d[0], d[1], d[2], d[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) p[i] = d[i];
+    }
+}
+
+// First r in [0, M) with rowptr[r] >= x, or M if there is none.  All 64 lanes of the
+// wave probe at once, so a search over M rows takes ceil(log64 M) rounds.
+__device__ __forceinline__ int wave_lower_bound(const int32_t *rowptr, int M, int x) {
+    const int lane = lane_id();
+    int a = 0, b = M;
+    while (b > a) {
+        const int step = (b - a + kWave - 1) / kWave;
+        const long long idx = (long long)a + (long long)lane * step;
+        const bool ge = (idx < b) ? (rowptr[idx] >= x) : true;
+        const unsigned long long m = __ballot(ge);
+        const int f = m ? __builtin_ctzll(m) : kWave;
+        const int na = (f > 0) ? a + (f - 1) * step + 1 : a;
+        const long long nb = (long long)a + (long long)f * step;
+        b = (int)(nb < b ? nb : b);
+        a = na;
+        if (f == 0) b = a;
+    }
+    return uniform(a);
+}
+
+// Equal-nonzero partition: worker w of W takes the stored entries [lo, hi), a share
+// rounded up to whole chunks of 64 so chunk loads stay aligned.  Workers past the last
+// entry are idle; the last active worker also owns the trailing rows that have no
+// entries.  With nnz == 0 worker 0 owns every row.
+struct Share {
+    int lo, hi;     // this worker's entries
+    int nnz;
+    bool active;    // has entries or owns rows
+    bool last;      // last active worker
+};
+
+__device__ __forceinline__ Share make_share(const int32_t *rowptr, int M, int w, int W) {
+    Share s;
+    s.nnz = rowptr[M];
+    long long per = ((long long)s.nnz + W - 1) / W;
+    per = (per + kWave - 1) / kWave * kWave;
+    if (per == 0) per = kWave;
+    const long long wl = s.nnz > 0 ? (s.nnz - 1) / per : 0;
+    const long long lo = (long long)w * per;
+    s.active = (long long)w <= wl;
+    s.last = (long long)w == wl;
+    s.lo = s.active ? (int)lo : s.nnz;
+    const long long hi = lo + per;
+    s.hi = (int)(hi < s.nnz ? hi : s.nnz);
+    if (!s.active) s.hi = s.nnz;
+    return s;
+}
+
+}  // namespace csrk

@@ -1,0 +1,415 @@
+// Row-segment kernels with an equal-nonzero work split (the general path).
+//
+// Each wavefront ("worker") takes an equal share of S's stored entries, whatever the
+// row lengths are, finds the row its share starts in by a wave-wide search of rowptr
+// and walks the rows it touches.  This is the load balancing for skewed row lengths:
+// a row longer than a share is cut into segments handled by consecutive workers.
+//
+//  - SPMM / FusedMM: a worker writes the rows that START inside its share straight to
+//    O (if such a row continues into later shares this is its first partial sum), and
+//    puts the partial sum of the row that was already running when its share began
+//    (its "head") into a scratch row; `combine_heads_kernel` then adds the heads to
+//    O in worker order, so the result does not depend on timing.
+//  - SDDMM: outputs are per stored entry, segments are disjoint, no combine.
+//
+// Inside a segment the column indices and values are streamed in coalesced chunks of
+// 64 (one per lane), the next chunk being loaded while the current one is consumed.
+// A group of LG lanes covers the dense width with VEC floats per lane, so 64/LG
+// entries are processed side by side; their dense rows are gathered with one
+// (128-bit when VEC == 4) load per lane.
+//
+// Paper correspondence: the chunked index stream with look-ahead is the role of the
+// VLC-sized blocks and prefetches in the paper's kernels (section "ESIMD
+// Implementation"); the per-row arithmetic is Algorithms 1-3.
+#pragma once
+#include "device_util.hpp"
+
+namespace csrk {
+
+constexpr int kBlockThreads = 256;
+constexpr int kWavesPerBlock = kBlockThreads / kWave;
+
+// f(t) for t = t0, t0+stride, ... < t1, in blocks of U statically unrolled calls (so the
+// U gathers of a block are all in flight together) and a one-at-a-time remainder.
+template <int U, typename F>
+__device__ __forceinline__ void for_unrolled(int t0, int t1, int stride, F &&f) {
+    int t = t0;
+    for (; t + U * stride <= t1; t += U * stride) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) f(t + u * stride);
+    }
+    for (; t < t1; t += stride) f(t);
+}
+
+// ---------------------------------------------------------------------------------
+// SPMM segment: acc[t][v] += sum_{j in [s0,s1)} vals[j] * Bmat[colidx[j], n + t*TW + v]
+// ---------------------------------------------------------------------------------
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void spmm_segment(int s0, int s1, const int32_t *__restrict__ colidx,
+                                             const float *__restrict__ vals,
+                                             const float *__restrict__ Bmat, int N, int n,
+                                             float (&acc)[T][VEC]) {
+    constexpr int NPAR = kWave / LG;
+    constexpr int TW = LG * VEC;
+    const int lane = lane_id();
+    const int g = lane / LG;
+    if (s1 <= s0) return;
+    int base = s0 & ~(kWave - 1);
+    int j = base + lane;
+    bool ok = j >= s0 && j < s1;
+    int kc = ok ? colidx[j] : 0;
+    float vc = ok ? vals[j] : 0.f;
+    for (; base < s1; base += kWave) {
+        // look-ahead: next chunk of the index/value stream
+        const int jn = base + kWave + lane;
+        const bool okn = jn < s1;
+        const int kn = okn ? colidx[jn] : 0;
+        const float vn = okn ? vals[jn] : 0.f;
+        const int t0 = s0 > base ? s0 - base : 0;
+        const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
+        if constexpr (NPAR == 1) {
+            for_unrolled<8>(t0, t1, 1, [&](int t) {
+                const int k = __builtin_amdgcn_readlane(kc, t);
+                const float s = readlane_f(vc, t);
+                const float *brow = Bmat + (size_t)k * N + n;
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) {
+                    if (n + tt * TW < N) {
+                        float b[VEC];
+                        load_vec<VEC>(brow + tt * TW, b);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(s, b[v], acc[tt][v]);
+                    }
+                }
+            });
+        } else {
+            for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
+                const int idx = t + g;
+                const int k = __shfl(kc, idx);
+                const float s = __shfl(vc, idx);
+                if (idx >= t0 && idx < t1) {
+                    const float *brow = Bmat + (size_t)k * N + n;
+#pragma unroll
+                    for (int tt = 0; tt < T; ++tt) {
+                        if (n + tt * TW < N) {
+                            float b[VEC];
+                            load_vec<VEC>(brow + tt * TW, b);
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(s, b[v], acc[tt][v]);
+                        }
+                    }
+                }
+            });
+        }
+        kc = kn;
+        vc = vn;
+    }
+}
+
+// Sum the NPAR side-by-side partial rows of a wave into lanes [0, LG).
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void fold_groups(float (&acc)[T][VEC]) {
+#pragma unroll
+    for (int off = LG; off < kWave; off <<= 1)
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[tt][v] += __shfl_xor(acc[tt][v], off);
+}
+
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void store_row(float *dst, int N, int n, const float (&acc)[T][VEC]) {
+    constexpr int TW = LG * VEC;
+    if (lane_id() < LG) {
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt)
+            if (n + tt * TW < N) store_vec<VEC>(dst + n + tt * TW, acc[tt]);
+    }
+}
+
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
+    int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O,
+    float *__restrict__ head, int32_t *__restrict__ head_row) {
+    constexpr int TW = LG * VEC;
+    const int lane = lane_id();
+    const int W = gridDim.x * kWavesPerBlock;
+    const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int n = blockIdx.y * (TW * T) + (lane % LG) * VEC;
+    const Share sh = make_share(rowptr, M, w, W);
+    if (!sh.active) {
+        if (blockIdx.y == 0 && lane == 0) head_row[w] = -1;
+        return;
+    }
+    int r = wave_lower_bound(rowptr, M, sh.lo);
+    int hr = -1;
+    if (sh.lo < sh.nnz) {
+        const int start = uniform(rowptr[r]);      // r <= M and rowptr[M] = nnz
+        if (start != sh.lo) {                      // share begins inside row r-1
+            hr = r - 1;
+            float acc[T][VEC] = {};
+            spmm_segment<VEC, LG, T>(sh.lo, start < sh.hi ? start : sh.hi, colidx, vals, Bmat, N, n, acc);
+            fold_groups<VEC, LG, T>(acc);
+            store_row<VEC, LG, T>(head + (size_t)w * N, N, n, acc);
+        }
+    }
+    if (blockIdx.y == 0 && lane == 0) head_row[w] = hr;
+    for (; r < M; ++r) {
+        const int rs = uniform(rowptr[r]);
+        if (!sh.last && rs >= sh.hi) break;
+        const int re = uniform(rowptr[r + 1]);
+        float acc[T][VEC] = {};
+        spmm_segment<VEC, LG, T>(rs, re < sh.hi ? re : sh.hi, colidx, vals, Bmat, N, n, acc);
+        fold_groups<VEC, LG, T>(acc);
+        store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
+    }
+}
+
+// O[r, :] += head[w, :] + head[w+1, :] + ... for the run of workers whose head is row r.
+// One thread per output column; only the first worker of a run does the adding, in
+// worker order, so sums are reproducible.
+__global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int W, float *__restrict__ O,
+                                                                       const float *__restrict__ head,
+                                                                       const int32_t *__restrict__ head_row) {
+    const int w = blockIdx.x;
+    const int r = head_row[w];
+    if (r < 0) return;
+    if (w > 0 && head_row[w - 1] == r) return;
+    int wend = w + 1;
+    while (wend < W && head_row[wend] == r) ++wend;
+    for (int n = blockIdx.y * blockDim.x + threadIdx.x; n < N; n += gridDim.y * blockDim.x) {
+        float s = O[(size_t)r * N + n];
+        for (int ww = w; ww < wend; ++ww) s += head[(size_t)ww * N + n];
+        O[(size_t)r * N + n] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// SDDMM chunk: dot products of one row of A with the gathered rows of Bmat for the
+// entries of one chunk; results land in `slot[0..64)` (LDS, one slot array per wave)
+// ---------------------------------------------------------------------------------
+// T > 0: the A row sits in registers (`a`, T tiles of LG*VEC columns).  T == 0: any D,
+// tiles are walked at run time and the A row is re-read from memory (it stays in L1).
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float *__restrict__ Bmat, int D,
+                                            int d, const float *__restrict__ arow,
+                                            const float (&a)[T > 0 ? T : 1][VEC], float *slot) {
+    constexpr int NPAR = kWave / LG;
+    constexpr int TW = LG * VEC;
+    const int lane = lane_id();
+    const int g = lane / LG;
+    for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
+        const int idx = t + g;
+        const int k = (NPAR == 1) ? __builtin_amdgcn_readlane(kc, t) : __shfl(kc, idx);
+        const bool act = idx >= t0 && idx < t1;
+        float part = 0.f;
+        if (act) {
+            const float *brow = Bmat + (size_t)k * D + d;
+            if constexpr (T > 0) {
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) {
+                    if (d + tt * TW < D) {
+                        float b[VEC];
+                        load_vec<VEC>(brow + tt * TW, b);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) part = fmaf(a[tt][v], b[v], part);
+                    }
+                }
+            } else {
+                for (int dd = 0; d + dd < D; dd += TW) {
+                    float b[VEC], av[VEC];
+                    load_vec<VEC>(brow + dd, b);
+                    load_vec<VEC>(arow + d + dd, av);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) part = fmaf(av[v], b[v], part);
+                }
+            }
+        }
+        part = group_sum<LG>(part);
+        if (act && (lane % LG) == 0) slot[idx] = part;
+    });
+}
+
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void load_a_row(const float *__restrict__ arow, int D, int d,
+                                           float (&a)[T > 0 ? T : 1][VEC]) {
+    constexpr int TW = LG * VEC;
+    if constexpr (T > 0) {
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt) {
+            if (d + tt * TW < D) {
+                load_vec<VEC>(arow + d + tt * TW, a[tt]);
+            } else {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) a[tt][v] = 0.f;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) a[0][v] = 0.f;
+    }
+}
+
+// P may alias vals, so neither is __restrict__.
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
+    int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P) {
+    __shared__ float slots[kWavesPerBlock][kWave];
+    const int lane = lane_id();
+    const int W = gridDim.x * kWavesPerBlock;
+    const int wv = threadIdx.x >> 6;
+    const int w = uniform(blockIdx.x * kWavesPerBlock + wv);
+    const int d = (lane % LG) * VEC;
+    const Share sh = make_share(rowptr, M, w, W);
+    if (!sh.active || sh.lo >= sh.nnz) return;
+    float *slot = slots[wv];
+    // row containing entry lo: the last row that starts at or before lo
+    int r = wave_lower_bound(rowptr, M, sh.lo);
+    if (uniform(rowptr[r]) != sh.lo) --r;
+    for (; r < M; ++r) {
+        const int rs = uniform(rowptr[r]);
+        if (rs >= sh.hi) break;
+        const int re = uniform(rowptr[r + 1]);
+        const int s0 = rs > sh.lo ? rs : sh.lo;
+        const int s1 = re < sh.hi ? re : sh.hi;
+        if (s1 <= s0) continue;
+        const float *arow = A + (size_t)r * D;
+        float a[T > 0 ? T : 1][VEC];
+        load_a_row<VEC, LG, T>(arow, D, d, a);
+        for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
+            const int j = base + lane;
+            const bool ok = j >= s0 && j < s1;
+            const int kc = ok ? colidx[j] : 0;
+            const float vc = (ok && vals) ? vals[j] : 1.f;
+            const int t0 = s0 > base ? s0 - base : 0;
+            const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
+            sddmm_chunk<VEC, LG, T>(kc, t0, t1, Bmat, D, d, arow, a, slot);
+            __builtin_amdgcn_wave_barrier();
+            if (ok) P[j] = vc * slot[lane];
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// FusedMM: per chunk, the SDDMM stage leaves the 64 scores in LDS slots, each lane
+// picks up "its" score (scaled by vals) into a register, and the SPMM stage consumes
+// them from there; scores never reach device memory (Algorithm 3's `arow`).
+// Dot stage uses (VD, LD, TD) over D, the accumulate stage (VN, LN, TN) over N.
+// ---------------------------------------------------------------------------------
+template <int VN, int LN, int TN>
+__device__ __forceinline__ void saxpy_chunk(int kc, float sc, int t0, int t1, const float *__restrict__ Cmat,
+                                            int N, int n, float (&acc)[TN][VN]) {
+    constexpr int NPAR = kWave / LN;
+    constexpr int TW = LN * VN;
+    const int g = lane_id() / LN;
+    if constexpr (NPAR == 1) {
+        for_unrolled<8>(t0, t1, 1, [&](int t) {
+            const int k = __builtin_amdgcn_readlane(kc, t);
+            const float s = readlane_f(sc, t);
+            const float *crow = Cmat + (size_t)k * N + n;
+#pragma unroll
+            for (int tt = 0; tt < TN; ++tt) {
+                if (n + tt * TW < N) {
+                    float c[VN];
+                    load_vec<VN>(crow + tt * TW, c);
+#pragma unroll
+                    for (int v = 0; v < VN; ++v) acc[tt][v] = fmaf(s, c[v], acc[tt][v]);
+                }
+            }
+        });
+    } else {
+        for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
+            const int idx = t + g;
+            const int k = __shfl(kc, idx);
+            const float s = __shfl(sc, idx);
+            if (idx >= t0 && idx < t1) {
+                const float *crow = Cmat + (size_t)k * N + n;
+#pragma unroll
+                for (int tt = 0; tt < TN; ++tt) {
+                    if (n + tt * TW < N) {
+                        float c[VN];
+                        load_vec<VN>(crow + tt * TW, c);
+#pragma unroll
+                        for (int v = 0; v < VN; ++v) acc[tt][v] = fmaf(s, c[v], acc[tt][v]);
+                    }
+                }
+            }
+        });
+    }
+}
+
+template <int VD, int LD, int TD, int VN, int LN, int TN>
+__device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int32_t *__restrict__ colidx,
+                                              const float *__restrict__ vals, const float *__restrict__ A,
+                                              const float *__restrict__ Bmat, const float *__restrict__ Cmat,
+                                              int D, int N, int d, int n, float *slot, float (&acc)[TN][VN]) {
+    if (s1 <= s0) return;
+    const int lane = lane_id();
+    const float *arow = A + (size_t)row * D;
+    float a[TD > 0 ? TD : 1][VD];
+    load_a_row<VD, LD, TD>(arow, D, d, a);
+    for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
+        const int j = base + lane;
+        const bool ok = j >= s0 && j < s1;
+        const int kc = ok ? colidx[j] : 0;
+        const float vc = (ok && vals) ? vals[j] : 1.f;
+        const int t0 = s0 > base ? s0 - base : 0;
+        const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
+        sddmm_chunk<VD, LD, TD>(kc, t0, t1, Bmat, D, d, arow, a, slot);
+        __builtin_amdgcn_wave_barrier();
+        const float sc = ok ? vc * slot[lane] : 0.f;
+        __builtin_amdgcn_wave_barrier();
+        saxpy_chunk<VN, LN, TN>(kc, sc, t0, t1, Cmat, N, n, acc);
+    }
+}
+
+template <int VD, int LD, int TD, int VN, int LN, int TN>
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
+    int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
+    const float *__restrict__ Cmat, float *__restrict__ O, float *__restrict__ head,
+    int32_t *__restrict__ head_row) {
+    __shared__ float slots[kWavesPerBlock][kWave];
+    constexpr int TWN = LN * VN;
+    const int lane = lane_id();
+    const int W = gridDim.x * kWavesPerBlock;
+    const int wv = threadIdx.x >> 6;
+    const int w = uniform(blockIdx.x * kWavesPerBlock + wv);
+    const int d = (lane % LD) * VD;
+    const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
+    float *slot = slots[wv];
+    const Share sh = make_share(rowptr, M, w, W);
+    if (!sh.active) {
+        if (blockIdx.y == 0 && lane == 0) head_row[w] = -1;
+        return;
+    }
+    int r = wave_lower_bound(rowptr, M, sh.lo);
+    int hr = -1;
+    if (sh.lo < sh.nnz) {
+        const int start = uniform(rowptr[r]);
+        if (start != sh.lo) {
+            hr = r - 1;
+            float acc[TN][VN] = {};
+            fused_segment<VD, LD, TD, VN, LN, TN>(hr, sh.lo, start < sh.hi ? start : sh.hi, colidx, vals, A, Bmat,
+                                                  Cmat, D, N, d, n, slot, acc);
+            fold_groups<VN, LN, TN>(acc);
+            store_row<VN, LN, TN>(head + (size_t)w * N, N, n, acc);
+        }
+    }
+    if (blockIdx.y == 0 && lane == 0) head_row[w] = hr;
+    for (; r < M; ++r) {
+        const int rs = uniform(rowptr[r]);
+        if (!sh.last && rs >= sh.hi) break;
+        const int re = uniform(rowptr[r + 1]);
+        float acc[TN][VN] = {};
+        fused_segment<VD, LD, TD, VN, LN, TN>(r, rs, re < sh.hi ? re : sh.hi, colidx, vals, A, Bmat, Cmat, D, N, d,
+                                              n, slot, acc);
+        fold_groups<VN, LN, TN>(acc);
+        store_row<VN, LN, TN>(O + (size_t)r * N, N, n, acc);
+    }
+}
+
+}  // namespace csrk
