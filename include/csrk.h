@@ -16,7 +16,8 @@
  *    Entries of a row may be in any order and may repeat (SPMM/FusedMM add
  *    repeated entries up, SDDMM yields one result per stored entry); explicitly
  *    stored zeros are ordinary entries.  The library reads nnz from rowptr[M] on
- *    the device.  Index contents are not validated by the compute calls: an
+ *    the device; colidx, vals and P are never dereferenced when it is 0, so they
+ *    may be NULL then.  Index contents are not validated by the compute calls: an
  *    out-of-range index or a decreasing rowptr is undefined behaviour (use
  *    csrk_validate_csr first when inputs are untrusted).
  *  - Dense matrices are FP32, row-major and contiguous (leading dimension = row
@@ -61,7 +62,7 @@ typedef int csrk_status;
  * SPMM, paper eq. (2) / Algorithm 2:
  *   O[i, :] = sum over stored entries j of row i of  vals[j] * B[colidx[j], :]
  * S is M x K (rowptr/colidx/vals), B is K x N, O is M x N (overwritten).
- * vals must not be NULL.
+ * vals == NULL means every stored entry is 1 (the paper's all-ones matrix I_A).
  */
 csrk_status spmm_csr(int M, int K, int N,
                      const int32_t *rowptr, const int32_t *colidx, const float *vals,

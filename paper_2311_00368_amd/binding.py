@@ -104,7 +104,7 @@ def csrk_last_error() -> str:
 def spmm_csr(M: int, K: int, N: int, rowptr, colidx, vals, B, O=None) -> torch.Tensor:
     """O = S.B on the current stream; returns O (allocated M x N if not given)."""
     lib = load()
-    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, True)
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
     if O is None:
         O = torch.empty((M, N), dtype=torch.float32, device=dev)
     with torch.cuda.device(dev):

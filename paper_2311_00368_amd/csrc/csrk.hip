@@ -238,8 +238,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     if (csrk_status s = check_dims("spmm_csr", M, K, N, 0)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr: rowptr and O must not be NULL");
-    if (!vals) return fail(CSRK_INVALID_ARG, "spmm_csr: vals must not be NULL");
-    if (K > 0 && (!colidx || !B)) return fail(CSRK_INVALID_ARG, "spmm_csr: colidx and B must not be NULL");
+    if (K > 0 && !B) return fail(CSRK_INVALID_ARG, "spmm_csr: B must not be NULL");
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;
     if (csrk_status s = device_state(&d)) return s;
@@ -269,7 +268,7 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
                       const float *A, const float *B, float *P, hipStream_t stream) {
     if (csrk_status s = check_dims("sddmm_csr", M, K, D, 0)) return s;
     if (M == 0 || K == 0) return CSRK_OK;
-    if (!rowptr || !colidx || !P) return fail(CSRK_INVALID_ARG, "sddmm_csr: rowptr, colidx and P must not be NULL");
+    if (!rowptr) return fail(CSRK_INVALID_ARG, "sddmm_csr: rowptr must not be NULL");
     if (D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "sddmm_csr: A and B must not be NULL");
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;
@@ -297,7 +296,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     if (csrk_status s = check_dims("fusedmm_csr", M, K, D, N)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr: rowptr and O must not be NULL");
-    if (K > 0 && (!colidx || !C)) return fail(CSRK_INVALID_ARG, "fusedmm_csr: colidx and C must not be NULL");
+    if (K > 0 && !C) return fail(CSRK_INVALID_ARG, "fusedmm_csr: C must not be NULL");
     if (K > 0 && D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "fusedmm_csr: A and B must not be NULL");
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;

@@ -58,13 +58,13 @@ __device__ __forceinline__ void spmm_segment(int s0, int s1, const int32_t *__re
     int j = base + lane;
     bool ok = j >= s0 && j < s1;
     int kc = ok ? colidx[j] : 0;
-    float vc = ok ? vals[j] : 0.f;
+    float vc = ok ? (vals ? vals[j] : 1.f) : 0.f;
     for (; base < s1; base += kWave) {
         // look-ahead: next chunk of the index/value stream
         const int jn = base + kWave + lane;
         const bool okn = jn < s1;
         const int kn = okn ? colidx[jn] : 0;
-        const float vn = okn ? vals[jn] : 0.f;
+        const float vn = okn ? (vals ? vals[jn] : 1.f) : 0.f;
         const int t0 = s0 > base ? s0 - base : 0;
         const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
         if constexpr (NPAR == 1) {

@@ -202,6 +202,7 @@ def test_empty_dimensions_and_errors(csrk):
     assert lib.spmm_csr(-1, 5, 4, None, None, None, None, None, None) == 1
     assert b"negative" in lib.csrk_last_error()
     assert lib.spmm_csr(3, 5, 4, None, None, None, None, None, None) == 1
+    assert b"NULL" in lib.csrk_last_error()
     assert lib.sddmm_csr(3, 5, 1 << 25, None, None, None, None, None, None, None) == 2
 
 
