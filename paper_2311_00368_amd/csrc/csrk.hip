@@ -11,6 +11,7 @@
 #include <mutex>
 #include <vector>
 
+#include "kernels_ktile.hpp"
 #include "kernels_nnzsplit.hpp"
 
 namespace {
@@ -38,6 +39,7 @@ constexpr int kMaxDevices = 64;
 
 struct DeviceState {
     bool init = false;
+    int cus = 0;
     int workers = 0;        // wavefronts the equal-nonzero split is cut into
     float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way
     int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
@@ -59,7 +61,7 @@ struct ScopedRecord {
     int slot = -1;
     hipStream_t st;
     ScopedRecord(int kind, hipStream_t s) : st(s) {
-        if (g_rec.used < (int)g_rec.start.size()) {
+        if (kind != 0 && g_rec.used < (int)g_rec.start.size()) {
             slot = g_rec.used++;
             g_rec.kind[slot] = kind;
             (void)hipEventRecord(g_rec.start[slot], st);
@@ -90,6 +92,7 @@ csrk_status device_state(DeviceState **out) {
         int workers = env_int("CSRK_WORKERS", cus * 32);
         workers = (workers + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
         d.workers = workers;
+        d.cus = cus;
         d.init = true;
     }
     *out = &d;
@@ -160,9 +163,9 @@ WidthCfg dot_width_cfg(int D, bool vec4) {
 
 template <int VEC, int LG, int T>
 void launch_spmm(dim3 grid, hipStream_t st, int M, int N, const int32_t *rp, const int32_t *ci, const float *v,
-                 const float *B, float *O, float *head, int32_t *head_row) {
+                 const float *B, float *O, float *head, int32_t *head_row, const int32_t *gate) {
     hipLaunchKernelGGL((spmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, N, rp, ci, v, B, O,
-                       head, head_row);
+                       head, head_row, gate);
 }
 
 template <int VEC, int LG, int T>
@@ -175,19 +178,19 @@ void launch_sddmm(dim3 grid, hipStream_t st, int M, int D, const int32_t *rp, co
 template <int VD, int LD, int TD, int VN, int LN, int TN>
 void launch_fused(dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp, const int32_t *ci,
                   const float *v, const float *A, const float *B, const float *C, float *O, float *head,
-                  int32_t *head_row) {
+                  int32_t *head_row, const int32_t *gate) {
     hipLaunchKernelGGL((fusedmm_nnzsplit_kernel<VD, LD, TD, VN, LN, TN>), grid, dim3(kBlockThreads), 0, st, M, D, N,
-                       rp, ci, v, A, B, C, O, head, head_row);
+                       rp, ci, v, A, B, C, O, head, head_row, gate);
 }
 
 template <int VD, int LD, int TD>
 bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp,
                     const int32_t *ci, const float *v, const float *A, const float *B, const float *C, float *O,
-                    float *head, int32_t *head_row) {
-#define CSRK_FUSED_CASE(VN, LN, TN)                                                                         \
-    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                        \
-        launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row);     \
-        return true;                                                                                        \
+                    float *head, int32_t *head_row, const int32_t *gate) {
+#define CSRK_FUSED_CASE(VN, LN, TN)                                                                           \
+    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                          \
+        launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row, gate); \
+        return true;                                                                                          \
     }
     CSRK_FUSED_CASE(4, 16, 1)
     CSRK_FUSED_CASE(4, 32, 1)
@@ -198,10 +201,56 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
     return false;
 }
 
-void launch_combine(DeviceState &d, hipStream_t st, int N, float *O) {
+void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32_t *gate) {
     const int ytiles = (N + kBlockThreads - 1) / kBlockThreads;
     hipLaunchKernelGGL(combine_heads_kernel, dim3(d.workers, ytiles < 8 ? ytiles : 8), dim3(kBlockThreads), 0, st, N,
-                       d.workers, O, d.head, d.head_row);
+                       d.workers, O, d.head, d.head_row, gate);
+}
+
+// --- LDS-tiled path ---------------------------------------------------------------------
+// Host-side eligibility (shapes only); the device-side analysis has the last word.
+constexpr int kTileRows = 4;          // rows of S per wavefront
+constexpr float kTileMinDensity = 0.02f;
+
+int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
+
+bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
+    const int mode = env_int("CSRK_KTILE", 1);       // 1 auto, 2 force where the kernel can run, 3 off
+    if (mode == 3) return false;
+    if (N % 4 != 0 || N > 512 || N <= 128) return mode == 2 && N % 4 == 0 && N <= 512;
+    if (mode == 2) return true;
+    // enough row blocks to occupy the CUs, and a dense operand too big to live in one XCD's L2
+    return (long long)M >= (long long)d.cus * kTileWaves * kTileRows / 2 && (long long)K * N * 4 >= (8ll << 20);
+}
+
+csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, const int32_t *ci) {
+    int32_t *flags = tile_flags(d);
+    hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(64), 0, st, flags);
+    hipLaunchKernelGGL(analyze_kernel, dim3(d.cus * 8), dim3(256), 0, st, M, K, rp, ci, kTileMinDensity, flags);
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+template <int T, int KT, bool FUSED>
+csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                         const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                         float *O) {
+    using L = KTileLds<T, KT, kTileRows, FUSED>;
+    static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
+    static_assert(KT % 16 == 0, "the staging loops copy whole multiples of 16 rows");
+    auto kern = ktile_kernel<T, KT, kTileRows, FUSED>;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (!attr_set[dev]) {
+        CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
+        attr_set[dev] = true;
+    }
+    const int rb = kTileWaves * kTileRows;
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v, A, B,
+                       C, O, tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
 }
 
 // --- validation kernels -------------------------------------------------------------
@@ -247,10 +296,22 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const WidthCfg c = out_width_cfg(N, vec4);
     const int tile = c.vec * c.lg * c.t;
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
-    ScopedRecord rec(1, stream);
+    const int32_t *gate = nullptr;
+    if (vec4 && ktile_shape_ok(*d, M, K, N)) {
+        // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
+        // unless the analysis found S unsuitable (unsorted columns or too sparse)
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+        gate = tile_flags(*d);
+        ScopedRecord rec(1, stream);
+        csrk_status s = N <= 256 ? launch_ktile<1, 128, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O)
+                                 : launch_ktile<2, 64, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
+        rec.end();
+        if (s) return s;
+    }
+    ScopedRecord rec(gate ? 0 : 1, stream);
 #define CSRK_SPMM_CASE(V, L, T)                                                                           \
     if (c.vec == V && c.lg == L && c.t == T)                                                              \
-        launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row);
+        launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row, gate);
     CSRK_SPMM_CASE(4, 16, 1)
     CSRK_SPMM_CASE(4, 32, 1)
     CSRK_SPMM_CASE(4, 64, 1)
@@ -259,7 +320,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
 #undef CSRK_SPMM_CASE
     rec.end();
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O);
+    launch_combine(*d, stream, N, O, gate);
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
@@ -309,11 +370,21 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int tile = nc.vec * nc.lg * nc.t;
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     bool done = false;
-    ScopedRecord rec(3, stream);
+    const int32_t *gate = nullptr;
+    if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+        gate = tile_flags(*d);
+        ScopedRecord rec(3, stream);
+        csrk_status s = N <= 256 ? launch_ktile<1, 96, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
+                                 : launch_ktile<2, 64, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+        rec.end();
+        if (s) return s;
+    }
+    ScopedRecord rec(gate ? 0 : 3, stream);
 #define CSRK_DOT_CASE(V, L, T)                                                                            \
     if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                  \
         done = launch_fused_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head, \
-                                       d->head_row);
+                                       d->head_row, gate);
     CSRK_DOT_CASE(4, 16, 1)
     CSRK_DOT_CASE(4, 32, 1)
     CSRK_DOT_CASE(4, 64, 1)
@@ -323,7 +394,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     rec.end();
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O);
+    launch_combine(*d, stream, N, O, gate);
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }

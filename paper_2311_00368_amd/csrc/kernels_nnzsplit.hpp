@@ -23,6 +23,7 @@
 // Implementation"); the per-row arithmetic is Algorithms 1-3.
 #pragma once
 #include "device_util.hpp"
+#include "kernels_ktile.hpp"
 
 namespace csrk {
 
@@ -131,8 +132,9 @@ template <int VEC, int LG, int T>
 __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
     int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O,
-    float *__restrict__ head, int32_t *__restrict__ head_row) {
+    float *__restrict__ head, int32_t *__restrict__ head_row, const int32_t *__restrict__ gate) {
     constexpr int TW = LG * VEC;
+    if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
     const int lane = lane_id();
     const int W = gridDim.x * kWavesPerBlock;
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
@@ -171,7 +173,9 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
 // worker order, so sums are reproducible.
 __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int W, float *__restrict__ O,
                                                                        const float *__restrict__ head,
-                                                                       const int32_t *__restrict__ head_row) {
+                                                                       const int32_t *__restrict__ head_row,
+                                                                       const int32_t *__restrict__ gate) {
+    if (gate && ktile_ok(gate)) return;
     const int w = blockIdx.x;
     const int r = head_row[w];
     if (r < 0) return;
@@ -371,9 +375,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, float *__restrict__ head,
-    int32_t *__restrict__ head_row) {
+    int32_t *__restrict__ head_row, const int32_t *__restrict__ gate) {
     __shared__ float slots[kWavesPerBlock][kWave];
     constexpr int TWN = LN * VN;
+    if (gate && ktile_ok(gate)) return;
     const int lane = lane_id();
     const int W = gridDim.x * kWavesPerBlock;
     const int wv = threadIdx.x >> 6;

@@ -1,0 +1,93 @@
+"""The LDS-tiled SPMM / FusedMM kernels against the CPU oracle.
+
+By default the library picks these kernels only for large shapes; CSRK_KTILE=2 makes it take
+them wherever the kernel can run at all (output width a multiple of 4 up to 512, dot length a
+multiple of 4 up to 64), so small and ragged cases reach them too.  Patterns the kernels cannot
+take (columns not ascending, or too sparse) must fall back to the general kernels on the device
+and still give the right answer."""
+import os
+
+import numpy as np
+import pytest
+
+import helpers
+from paper_2311_00368_amd import inputs
+from test_gpu_parity import csrk, dev, run_fused, run_spmm  # noqa: F401  (csrk is a fixture)
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def force_ktile():
+    old = os.environ.get("CSRK_KTILE")
+    os.environ["CSRK_KTILE"] = "2"
+    yield
+    if old is None:
+        os.environ.pop("CSRK_KTILE", None)
+    else:
+        os.environ["CSRK_KTILE"] = old
+
+
+@pytest.mark.parametrize("M,K,N", [(64, 64, 256), (100, 257, 512), (333, 417, 4), (1000, 129, 260), (65, 1000, 128),
+                                   (2048, 2048, 512), (130, 70, 500)])
+@pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
+def test_spmm_ktile(csrk, M, K, N, p):
+    rng = np.random.default_rng(M + K + N)
+    rp, ci = inputs.bernoulli_csr(N, M, K, p)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, B)
+
+
+@pytest.mark.parametrize("M,K,D,N", [(64, 64, 64, 256), (100, 257, 64, 512), (333, 417, 4, 4), (1000, 129, 32, 260),
+                                     (2048, 2048, 64, 512), (130, 70, 60, 500), (70, 300, 16, 64)])
+@pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
+def test_fusedmm_ktile(csrk, M, K, D, N, p):
+    rng = np.random.default_rng(M + K + N + D)
+    rp, ci = inputs.bernoulli_csr(N + D, M, K, p)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_fused(csrk, M, K, D, N, rp, ci, None, A, B, C)
+
+
+def test_edge_patterns_ktile(csrk):
+    # includes unsorted and duplicated columns, empty rows, one full row: the device-side
+    # analysis must route each to a kernel that handles it
+    rng = np.random.default_rng(77)
+    for name, M, K, rp, ci in helpers.edge_patterns(rng):
+        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+        for D, N in [(64, 64), (64, 512), (8, 256)]:
+            A = rng.normal(size=(M, D)).astype(np.float32)
+            B = rng.normal(size=(K, D)).astype(np.float32)
+            C = rng.normal(size=(K, N)).astype(np.float32)
+            run_spmm(csrk, M, K, N, rp, ci, v, C)
+            run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
+def test_sorted_with_duplicates_and_dense_rows_ktile(csrk):
+    rng = np.random.default_rng(5)
+    K, N, D = 700, 512, 64
+    rows = []
+    for i in range(150):
+        n = int(rng.integers(0, 3 * K))
+        rows.append(sorted(rng.integers(0, K, size=n).tolist()))      # ascending, many repeats, rows > 64 per tile
+    rp, ci = helpers.csr_from_rows(rows, K)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(150, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_spmm(csrk, 150, K, N, rp, ci, v, C)
+    run_fused(csrk, 150, K, D, N, rp, ci, v, A, B, C)
+
+
+def test_skewed_rows_ktile(csrk):
+    w = inputs.workload("fused8k_skew", scale=0.25)
+    f = w.ops["fusedmm"]
+    rng = np.random.default_rng(1)
+    C = rng.normal(size=(w.K, 256)).astype(np.float32)
+    run_spmm(csrk, w.M, w.K, 256, w.rowptr, w.colidx, w.vals, C)
+    run_fused(csrk, w.M, w.K, 64, 256, w.rowptr, w.colidx, w.vals, f["A"], f["B"], C)
