@@ -238,7 +238,7 @@ csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, in
     using L = KTileLds<T, KT, kTileRows, FUSED>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert(KT % 16 == 0, "the staging loops copy whole multiples of 16 rows");
-    auto kern = ktile_kernel<T, KT, kTileRows, FUSED>;
+    auto kern = ktile_kernel<T, KT, kTileRows, FUSED, !FUSED>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));

@@ -16,17 +16,32 @@
 // found without any precomputed pointers: the wavefront keeps a cursor per row and a
 // 64-entry look-ahead chunk of (colidx, vals) in registers; because columns ascend
 // within a row, the entries of the current tile are a prefix of the chunk, whose
-// length is a ballot + popcount.  The chunk for the next tile is requested before the
-// multiply-adds of the current one start.
+// length is a ballot + popcount.
+//
+// Instruction budget (the kernel is bound by VALU issue, not by LDS or HBM):
+//  - The chunk is parked in a small per-wavefront LDS slot as (column, value) pairs
+//    and each entry is fetched back with one 64-bit read whose address is the same in
+//    every lane (an LDS broadcast).  That puts column and value in VGPRs of all lanes
+//    with no VALU work; v_readlane_b32 would cost two 8-cycle VALU slots per entry,
+//    a third of the kernel's time when measured.
+//  - Per entry that leaves one address computation plus the 4*T multiply-adds.
+//  - Entries go in batches of 4: pair reads, then all row reads, then the multiply-adds,
+//    so LDS latency overlaps.
+//  - The look-ahead chunks are reloaded in one place, after the tile's arithmetic, and
+//    the next tile of the dense operand is requested into registers right after the
+//    tile barrier: no vector-memory wait ever sits inside the arithmetic.
 //
 // Requirements (checked on the device by analyze_kernel, else the general kernels run):
 // columns of every row non-decreasing; S dense enough for the LDS copy to pay.
 //
 // FusedMM adds a dot stage per segment: 4 entries at a time, 16 lanes x 4 floats over
-// D <= 64, rows of the first dense operand B also staged in LDS, DPP reduction, scores
-// parked in a 64-float LDS slot per wavefront and picked up one per lane, exactly as in
-// the general kernel.  Scores never leave the CU (Algorithm 3's `arow`).
+// D <= 64, rows of the first dense operand B also staged in LDS, DPP reduction; the
+// finished score (times the stored value) overwrites the value half of the entry's
+// pair in the LDS slot, from where the accumulate stage broadcasts it.  Scores never
+// leave the CU (Algorithm 3's `arow`).
 #pragma once
+#include <type_traits>
+
 #include "device_util.hpp"
 
 namespace csrk {
@@ -66,11 +81,14 @@ struct KTileLds {
     static constexpr int kRowFloats = T * 256;
     static constexpr int kCFloats = KT * kRowFloats;
     static constexpr int kDFloats = FUSED ? KT * 64 : 0;
-    static constexpr int kSlotFloats = FUSED ? kTileWaves * kWave : 0;
-    static constexpr int kBytes = (kCFloats + kDFloats + kSlotFloats) * 4;
+    // (column, value) pairs: SPMM keeps two 64-entry slots per wavefront so that the next
+    // row's chunk is written while the current row is consumed; FusedMM has one
+    static constexpr int kSlots = FUSED ? 1 : 2;
+    static constexpr int kEntFloats = kTileWaves * kSlots * kWave * 2;
+    static constexpr int kBytes = (kCFloats + kDFloats + kEntFloats) * 4;
 };
 
-template <int T, int KT, int ROWS, bool FUSED>
+template <int T, int KT, int ROWS, bool FUSED, bool PREFETCH>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
@@ -78,12 +96,13 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     using L = KTileLds<T, KT, ROWS, FUSED>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
-    float *ct = lds;                        // KT x (T*256)
-    float *bt = lds + L::kCFloats;          // KT x 64        (FUSED)
-    float *slots = bt + L::kDFloats;        // 16 x 64        (FUSED)
-
+    constexpr int kRowBytes = L::kRowFloats * 4;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
+    float *ct = lds;                        // KT x (T*256) floats
+    float *bt = lds + L::kCFloats;          // KT x 64 floats (FUSED)
+    int2 *ent = reinterpret_cast<int2 *>(bt + L::kDFloats) + wave * (L::kSlots * kWave);
+
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
     const int d = (lane & 15) * 4;          // FUSED: this lane's slice of the dot length
@@ -116,73 +135,147 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         }
     }
 
+    // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
     const int n4 = N >> 2;                  // float4s per dense row
-    for (int k0 = 0; k0 < K; k0 += KT) {
-        __syncthreads();                    // previous tile fully consumed
-        // ---- stage C[k0:k0+KT, 0:N] (and B[k0:k0+KT, 0:D]) in LDS
-        {
-            const float4 *src = reinterpret_cast<const float4 *>(Cmat);
-            float4 *dst = reinterpret_cast<float4 *>(ct);
-            constexpr int kRow4 = T * 64;
+    constexpr int kRow4 = T * 64;
+    constexpr int kPer = KT * kRow4 / kTileThreads;
+    constexpr int kPerB = FUSED ? (KT * 16 + kTileThreads - 1) / kTileThreads : 1;
+    float4 stage[kPer];
+    float4 stageb[kPerB];
+    auto issue = [&](int k0) {
+        const float4 *src = reinterpret_cast<const float4 *>(Cmat);
 #pragma unroll
-            for (int i = 0; i < KT * kRow4 / kTileThreads; ++i) {
+        for (int i = 0; i < kPer; ++i) {
+            const int e = i * kTileThreads + threadIdx.x;
+            const int kk = e / kRow4, c4 = e % kRow4;
+            stage[i] = (k0 + kk < K && c4 < n4) ? src[(size_t)(k0 + kk) * n4 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if constexpr (FUSED) {
+            const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
+            const int d4 = D >> 2;
+#pragma unroll
+            for (int i = 0; i < kPerB; ++i) {
                 const int e = i * kTileThreads + threadIdx.x;
-                const int kk = e / kRow4, c4 = e % kRow4;
-                if (k0 + kk < K && c4 < n4) dst[e] = src[(size_t)(k0 + kk) * n4 + c4];
-            }
-            if constexpr (FUSED) {
-                const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
-                float4 *dstb = reinterpret_cast<float4 *>(bt);
-                const int d4 = D >> 2;
-#pragma unroll
-                for (int i = 0; i < (KT * 16 + kTileThreads - 1) / kTileThreads; ++i) {
-                    const int e = i * kTileThreads + threadIdx.x;
-                    const int kk = e >> 4, c4 = e & 15;
-                    if (e < KT * 16 && k0 + kk < K && c4 < d4) dstb[e] = srcb[(size_t)(k0 + kk) * d4 + c4];
-                }
+                const int kk = e >> 4, c4 = e & 15;
+                stageb[i] = (e < KT * 16 && k0 + kk < K && c4 < d4) ? srcb[(size_t)(k0 + kk) * d4 + c4]
+                                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         }
+    };
+    auto commit = [&]() {
+        float4 *dst = reinterpret_cast<float4 *>(ct);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        if constexpr (FUSED) {
+            float4 *dstb = reinterpret_cast<float4 *>(bt);
+#pragma unroll
+            for (int i = 0; i < kPerB; ++i) {
+                const int e = i * kTileThreads + threadIdx.x;
+                if (e < KT * 16) dstb[e] = stageb[i];
+            }
+        }
+    };
+
+    if constexpr (PREFETCH) issue(0);
+    for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();                    // previous tile fully consumed
+        if constexpr (!PREFETCH) issue(k0);
+        commit();
         __syncthreads();
+        if constexpr (PREFETCH) {
+            if (k0 + KT < K) issue(k0 + KT);   // lands while this tile is being worked on
+        }
         const int kend = k0 + KT;
+        const int lb = n * 4 - k0 * kRowBytes;  // lane's byte offset in a tile row, minus the tile origin
+        int cnts[ROWS];
+        if constexpr (!FUSED) ent[lane] = make_int2(kc[0], __builtin_bit_cast(int, vc[0]));
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            while (true) {
-                // entries of this tile = leading lanes of the chunk with column < kend
-                const int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
-                if (cnt == 0) break;
-                // request the chunk that follows before doing the arithmetic
-                const int npos = pos[r] + cnt;
-                const int jn = npos + lane;
-                const bool okn = jn < end[r];
-                const int kn = okn ? colidx[jn] : 0x7fffffff;
-                const float vn = okn ? (vals ? vals[jn] : 1.f) : 0.f;
-                float sc = vc[r];
-                if constexpr (FUSED) {
-                    float *slot = slots + wave * kWave;
+            // entries of this tile = leading lanes of the chunk with column < kend
+            const int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
+            cnts[r] = cnt;
+            int2 *e;
+            if constexpr (FUSED) {
+                e = ent;
+                if (cnt > 0) {
+                    e[lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+                    // dot stage: group g of 16 lanes handles entry t+g
                     for (int t = 0; t < cnt; t += 4) {
                         const int idx = t + g;
-                        const int kk = __shfl(kc[r], idx) - k0;
+                        const bool on = idx < cnt;
+                        const int2 kv = e[on ? idx : 0];
                         float part = 0.f;
-                        if (idx < cnt && d < D) {
+                        if (on && d < D) {
                             float b[4];
-                            load_vec<4>(bt + kk * 64 + d, b);
+                            load_vec<4>(bt + (kv.x - k0) * 64 + d, b);
                             part = a[r][0] * b[0];
                             part = fmaf(a[r][1], b[1], part);
                             part = fmaf(a[r][2], b[2], part);
                             part = fmaf(a[r][3], b[3], part);
                         }
                         part = group_sum<16>(part);
-                        if (idx < cnt && (lane & 15) == 0) slot[idx] = part;
+                        if (on && (lane & 15) == 0)
+                            reinterpret_cast<int *>(e)[2 * idx + 1] =
+                                __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
                     }
-                    __builtin_amdgcn_wave_barrier();
-                    sc = lane < cnt ? vc[r] * slot[lane] : 0.f;
-                    __builtin_amdgcn_wave_barrier();
                 }
-                const int kcur = kc[r];
-                auto step = [&](int t) {
-                    const int kk = __builtin_amdgcn_readlane(kcur, t) - k0;
-                    const float s = readlane_f(sc, t);
-                    const float *crow = ct + kk * L::kRowFloats + n;
+            } else {
+                if (r + 1 < ROWS)
+                    ent[((r + 1) & 1) * kWave + lane] = make_int2(kc[r + 1], __builtin_bit_cast(int, vc[r + 1]));
+                e = ent + (r & 1) * kWave;
+            }
+            auto batch = [&](int t, auto count) {
+                constexpr int CNT = decltype(count)::value;
+                float c[CNT][T][4];
+                int2 ks[CNT];
+#pragma unroll
+                for (int u = 0; u < CNT; ++u) ks[u] = e[t + u];    // same address in all lanes: broadcast
+#pragma unroll
+                for (int u = 0; u < CNT; ++u) {
+                    const char *crow = reinterpret_cast<const char *>(ct) + (ks[u].x * kRowBytes + lb);
+#pragma unroll
+                    for (int tt = 0; tt < T; ++tt)
+                        load_vec<4>(reinterpret_cast<const float *>(crow + tt * 1024), c[u][tt]);
+                }
+#pragma unroll
+                for (int u = 0; u < CNT; ++u) {
+                    const float sv = __builtin_bit_cast(float, ks[u].y);
+#pragma unroll
+                    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(sv, c[u][tt][v], acc[r][tt][v]);
+                }
+            };
+            int t = 0;
+            for (; t + 4 <= cnt; t += 4) batch(t, std::integral_constant<int, 4>{});
+            switch (cnt - t) {
+                case 3: batch(t, std::integral_constant<int, 3>{}); break;
+                case 2: batch(t, std::integral_constant<int, 2>{}); break;
+                case 1: batch(t, std::integral_constant<int, 1>{}); break;
+                default: break;
+            }
+            pos[r] += cnt;
+            if (cnt == kWave) {
+                // rare (a row with 64 or more entries inside one tile): finish the tile's
+                // entries of this row one at a time straight from memory
+                while (pos[r] < end[r]) {
+                    const int k = uniform(colidx[pos[r]]);
+                    if (k >= kend) break;
+                    float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
+                    if constexpr (FUSED) {
+                        float part = 0.f;
+                        if (g == 0 && d < D) {
+                            float b[4];
+                            load_vec<4>(bt + (k - k0) * 64 + d, b);
+                            part = a[r][0] * b[0];
+                            part = fmaf(a[r][1], b[1], part);
+                            part = fmaf(a[r][2], b[2], part);
+                            part = fmaf(a[r][3], b[3], part);
+                        }
+                        part = group_sum<16>(part);
+                        s *= readlane_f(part, 0);
+                    }
+                    const float *crow = ct + (k - k0) * L::kRowFloats + n;
 #pragma unroll
                     for (int tt = 0; tt < T; ++tt) {
                         float c[4];
@@ -190,19 +283,18 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 #pragma unroll
                         for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
                     }
-                };
-                int t = 0;
-                for (; t + 4 <= cnt; t += 4) {
-                    step(t);
-                    step(t + 1);
-                    step(t + 2);
-                    step(t + 3);
+                    ++pos[r];
                 }
-                for (; t < cnt; ++t) step(t);
-                pos[r] = npos;
-                kc[r] = kn;
-                vc[r] = vn;
-                if (cnt < kWave) break;
+            }
+        }
+        // look-ahead chunks for the next tile, all requested here, after the arithmetic
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (cnts[r] > 0) {
+                const int jn = pos[r] + lane;
+                const bool okn = jn < end[r];
+                kc[r] = okn ? colidx[jn] : 0x7fffffff;
+                vc[r] = okn ? (vals ? vals[jn] : 1.f) : 0.f;
             }
         }
     }
