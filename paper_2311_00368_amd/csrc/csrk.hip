@@ -170,9 +170,9 @@ void launch_spmm(dim3 grid, hipStream_t st, int M, int N, const int32_t *rp, con
 
 template <int VEC, int LG, int T>
 void launch_sddmm(dim3 grid, hipStream_t st, int M, int D, const int32_t *rp, const int32_t *ci, const float *v,
-                  const float *A, const float *B, float *P) {
+                  const float *A, const float *B, float *P, const int32_t *gate) {
     hipLaunchKernelGGL((sddmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, D, rp, ci, v, A, B,
-                       P);
+                       P, gate);
 }
 
 template <int VD, int LD, int TD, int VN, int LN, int TN>
@@ -221,6 +221,43 @@ bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     if (mode == 2) return true;
     // enough row blocks to occupy the CUs, and a dense operand too big to live in one XCD's L2
     return (long long)M >= (long long)d.cus * kTileWaves * kTileRows / 2 && (long long)K * N * 4 >= (8ll << 20);
+}
+
+bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
+    const int mode = env_int("CSRK_KTILE", 1);
+    if (mode == 3 || D % 4 != 0 || D > 128 || D < 4) return false;
+    if (mode == 2) return true;
+    return (long long)M >= (long long)d.cus * kTileWaves && (long long)K * D * 4 >= (1ll << 20);
+}
+
+template <int DMAX, int ROWS>
+csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
+                               const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
+    using L = SddmmTileLds<DMAX>;
+    static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
+    auto kern = sddmm_ktile_kernel<DMAX, ROWS>;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (!attr_set[dev]) {
+        CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
+        attr_set[dev] = true;
+    }
+    const int rb = kTileWaves * ROWS;
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, rp, ci, v, A, B, P,
+                       tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+template <int DMAX>
+csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
+                                    const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
+    // rows per wavefront: as many as still leave every CU a workgroup
+    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
+    if (blocks1 >= 4ll * d.cus) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
+    if (blocks1 >= 2ll * d.cus) return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
+    return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
 }
 
 csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, const int32_t *ci) {
@@ -337,10 +374,21 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     const bool vec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const WidthCfg c = dot_width_cfg(D, vec4);
     const dim3 grid(d->workers / kWavesPerBlock);
-    ScopedRecord rec(2, stream);
-#define CSRK_SDDMM_CASE(V, L, T)                                                  \
-    if (c.vec == V && c.lg == L && c.t == T)                                      \
-        launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P);
+    const int32_t *gate = nullptr;
+    if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
+        if (csrk_status s = ensure_scratch(*d, 1)) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+        gate = tile_flags(*d);
+        ScopedRecord rec(2, stream);
+        csrk_status s = D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
+                                : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
+        rec.end();
+        if (s) return s;
+    }
+    ScopedRecord rec(gate ? 0 : 2, stream);
+#define CSRK_SDDMM_CASE(V, L, T)                                                        \
+    if (c.vec == V && c.lg == L && c.t == T)                                            \
+        launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate);
     CSRK_SDDMM_CASE(4, 16, 1)
     CSRK_SDDMM_CASE(4, 32, 1)
     CSRK_SDDMM_CASE(4, 64, 1)

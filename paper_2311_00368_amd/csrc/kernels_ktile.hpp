@@ -309,4 +309,101 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// LDS-tiled SDDMM.  Lanes are ENTRIES here, not columns: a wavefront takes a chunk of 64
+// stored entries of one row, lane j walks the dot length for its own entry, reading its
+// row of B from the LDS tile 128 bits at a time (rows padded by 4 floats so that the 64
+// row starts spread over the banks) while the row of A, the same for all lanes, sits in
+// scalar registers.  No cross-lane reduction, results leave as one coalesced 256-byte
+// store per chunk (Algorithm 1's loop nest with the two loops swapped between lanes and
+// time).  Nothing is carried from tile to tile except the per-row cursor and look-ahead
+// chunk, found exactly as in ktile_kernel.  P may alias vals: each lane reads its value
+// before writing its result.
+// ---------------------------------------------------------------------------------------
+template <int DMAX>
+struct SddmmTileLds {
+    static constexpr int kStride = DMAX + 4;                              // floats per LDS row
+    static constexpr int kKT = (150 * 1024 / (kStride * 4)) / 64 * 64;    // tile height
+    static constexpr int kBytes = kKT * kStride * 4;
+};
+
+template <int DMAX, int ROWS>
+__global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
+    int M, int K, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
+    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, const int32_t *__restrict__ flags) {
+    using L = SddmmTileLds<DMAX>;
+    constexpr int KT = L::kKT;
+    constexpr int kStride = L::kStride;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if (!ktile_ok(flags)) return;
+    const int lane = lane_id();
+    const int wave = uniform(threadIdx.x >> 6);
+    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const int d4n = D >> 2;                 // float4s per row of A / B
+
+    int pos[ROWS], end[ROWS], kc[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = row0 + r;
+        pos[r] = row < M ? uniform(rowptr[row]) : 0;
+        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        const int j = pos[r] + lane;
+        kc[r] = j < end[r] ? colidx[j] : 0x7fffffff;
+    }
+
+    for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();
+        // stage B[k0:k0+KT, 0:D] with padded rows
+        {
+            const float4 *src = reinterpret_cast<const float4 *>(Bmat) + (size_t)k0 * d4n;
+            const int rows_here = K - k0 < KT ? K - k0 : KT;
+            const int total4 = rows_here * d4n;
+            for (int e = threadIdx.x; e < total4; e += kTileThreads) {
+                const int kk = e / d4n, c4 = e - kk * d4n;
+                *reinterpret_cast<float4 *>(lds + kk * kStride + c4 * 4) = src[e];
+            }
+        }
+        __syncthreads();
+        const int kend = k0 + KT;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const int row = row0 + r;
+            int kcur = kc[r];
+            int cnt = __builtin_popcountll(__ballot(kcur < kend));
+            const bool any = cnt > 0;
+            while (cnt > 0) {
+                const int j = pos[r] + lane;
+                const bool in = lane < cnt;
+                // speculative look-ahead: the chunk that follows if this one lies wholly in the tile
+                const int jn = j + kWave;
+                const int knext = jn < end[r] ? colidx[jn] : 0x7fffffff;
+                const float v = (in && vals) ? vals[j] : 1.f;
+                const float *brow = lds + (in ? kcur - k0 : 0) * kStride;
+                const float *arow = A + (size_t)row * D;
+                float dot = 0.f;
+#pragma unroll 4
+                for (int c4 = 0; c4 < d4n; ++c4) {
+                    const float4 b = *reinterpret_cast<const float4 *>(brow + c4 * 4);
+                    const float4 av = *reinterpret_cast<const float4 *>(arow + c4 * 4);   // uniform address
+                    dot = fmaf(av.x, b.x, dot);
+                    dot = fmaf(av.y, b.y, dot);
+                    dot = fmaf(av.z, b.z, dot);
+                    dot = fmaf(av.w, b.w, dot);
+                }
+                if (in) P[j] = v * dot;
+                pos[r] += cnt;
+                if (cnt < kWave) break;
+                kcur = knext;
+                cnt = __builtin_popcountll(__ballot(kcur < kend));
+            }
+            // look-ahead chunk for the next tile
+            if (any) {
+                const int j = pos[r] + lane;
+                kc[r] = j < end[r] ? colidx[j] : 0x7fffffff;
+            }
+        }
+    }
+}
+
 }  // namespace csrk

@@ -259,8 +259,10 @@ __device__ __forceinline__ void load_a_row(const float *__restrict__ arow, int D
 template <int VEC, int LG, int T>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P) {
+    const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P,
+    const int32_t *__restrict__ gate) {
     __shared__ float slots[kWavesPerBlock][kWave];
+    if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
     const int lane = lane_id();
     const int W = gridDim.x * kWavesPerBlock;
     const int wv = threadIdx.x >> 6;

@@ -12,7 +12,7 @@ import pytest
 
 import helpers
 from paper_2311_00368_amd import inputs
-from test_gpu_parity import csrk, dev, run_fused, run_spmm  # noqa: F401  (csrk is a fixture)
+from test_gpu_parity import csrk, dev, run_fused, run_sddmm, run_spmm  # noqa: F401  (csrk is a fixture)
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -54,6 +54,20 @@ def test_fusedmm_ktile(csrk, M, K, D, N, p):
     run_fused(csrk, M, K, D, N, rp, ci, None, A, B, C)
 
 
+@pytest.mark.parametrize("M,K,D", [(64, 64, 64), (100, 257, 128), (333, 417, 4), (1000, 1300, 32), (65, 3000, 100),
+                                   (2048, 2048, 64), (130, 70, 60), (4096, 600, 128)])
+@pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
+def test_sddmm_ktile(csrk, M, K, D, p):
+    rng = np.random.default_rng(M + K + D)
+    rp, ci = inputs.bernoulli_csr(D, M, K, p)
+    v = rng.uniform(0, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_sddmm(csrk, M, K, D, rp, ci, None, A, B)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
+
+
 def test_edge_patterns_ktile(csrk):
     # includes unsorted and duplicated columns, empty rows, one full row: the device-side
     # analysis must route each to a kernel that handles it
@@ -66,6 +80,8 @@ def test_edge_patterns_ktile(csrk):
             C = rng.normal(size=(K, N)).astype(np.float32)
             run_spmm(csrk, M, K, N, rp, ci, v, C)
             run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+            if len(ci):
+                run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
 
 
 def test_sorted_with_duplicates_and_dense_rows_ktile(csrk):
@@ -82,6 +98,7 @@ def test_sorted_with_duplicates_and_dense_rows_ktile(csrk):
     C = rng.normal(size=(K, N)).astype(np.float32)
     run_spmm(csrk, 150, K, N, rp, ci, v, C)
     run_fused(csrk, 150, K, D, N, rp, ci, v, A, B, C)
+    run_sddmm(csrk, 150, K, D, rp, ci, v, A, B)
 
 
 def test_skewed_rows_ktile(csrk):
@@ -91,3 +108,4 @@ def test_skewed_rows_ktile(csrk):
     C = rng.normal(size=(w.K, 256)).astype(np.float32)
     run_spmm(csrk, w.M, w.K, 256, w.rowptr, w.colidx, w.vals, C)
     run_fused(csrk, w.M, w.K, 64, 256, w.rowptr, w.colidx, w.vals, f["A"], f["B"], C)
+    run_sddmm(csrk, w.M, w.K, 64, w.rowptr, w.colidx, w.vals, f["A"], f["B"])
