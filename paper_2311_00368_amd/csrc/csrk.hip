@@ -209,7 +209,12 @@ void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32
 
 // --- LDS-tiled path ---------------------------------------------------------------------
 // Host-side eligibility (shapes only); the device-side analysis has the last word.
-constexpr int kTileRows = 4;          // rows of S per wavefront
+// rows of S per wavefront in the LDS-tiled SPMM/FusedMM kernels: 4 when that still gives every CU
+// a workgroup (M >= 64 * CUs), else 2, else 1
+int tile_rows_for(const DeviceState &d, int M) {
+    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
+    return blocks1 >= 4ll * d.cus ? 4 : blocks1 >= 2ll * d.cus ? 2 : 1;
+}
 constexpr float kTileMinDensity = 0.02f;
 
 int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
@@ -220,7 +225,8 @@ bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     if (N % 4 != 0 || N > 512 || N <= 128) return mode == 2 && N % 4 == 0 && N <= 512;
     if (mode == 2) return true;
     // enough row blocks to occupy the CUs, and a dense operand too big to live in one XCD's L2
-    return (long long)M >= (long long)d.cus * kTileWaves * kTileRows / 2 && (long long)K * N * 4 >= (8ll << 20);
+    const long long min_dense_bytes = (long long)env_int("CSRK_KTILE_MIN_MB", 8) << 20;
+    return (long long)M >= (long long)d.cus * kTileWaves / 2 && (long long)K * N * 4 >= min_dense_bytes;
 }
 
 bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
@@ -268,14 +274,15 @@ csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const 
     return CSRK_OK;
 }
 
-template <int T, int KT, bool FUSED>
-csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                         const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                         float *O) {
-    using L = KTileLds<T, KT, kTileRows, FUSED>;
+template <int T, int KT, int ROWS, bool FUSED>
+csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                              const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                              float *O) {
+    using L = KTileLds<T, KT, ROWS, FUSED>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert(KT % 16 == 0, "the staging loops copy whole multiples of 16 rows");
-    auto kern = ktile_kernel<T, KT, kTileRows, FUSED, !FUSED>;
+    // the register prefetch of the next tile needs 8 more float4 per thread than FusedMM can spare
+    auto kern = ktile_kernel<T, KT, ROWS, FUSED, !FUSED>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -283,11 +290,22 @@ csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, in
         CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
         attr_set[dev] = true;
     }
-    const int rb = kTileWaves * kTileRows;
+    const int rb = kTileWaves * ROWS;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v, A, B,
                        C, O, tile_flags(d));
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
+}
+
+template <int T, int KT, bool FUSED>
+csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                         const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                         float *O) {
+    switch (tile_rows_for(d, M)) {
+        case 4: return launch_ktile_rows<T, KT, 4, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 2: return launch_ktile_rows<T, KT, 2, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        default: return launch_ktile_rows<T, KT, 1, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    }
 }
 
 // --- validation kernels -------------------------------------------------------------

@@ -199,24 +199,43 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                 e = ent;
                 if (cnt > 0) {
                     e[lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
-                    // dot stage: group g of 16 lanes handles entry t+g
-                    for (int t = 0; t < cnt; t += 4) {
-                        const int idx = t + g;
-                        const bool on = idx < cnt;
-                        const int2 kv = e[on ? idx : 0];
-                        float part = 0.f;
-                        if (on && d < D) {
-                            float b[4];
-                            load_vec<4>(bt + (kv.x - k0) * 64 + d, b);
-                            part = a[r][0] * b[0];
-                            part = fmaf(a[r][1], b[1], part);
-                            part = fmaf(a[r][2], b[2], part);
-                            part = fmaf(a[r][3], b[3], part);
+                    // dot stage: 16 entries per round, group g of 16 lanes takes entries
+                    // t+g, t+4+g, t+8+g, t+12+g; all pair reads, then all row reads, then the
+                    // arithmetic and the four DPP reductions, so LDS latency is paid once a round
+                    for (int t = 0; t < cnt; t += 16) {
+                        int2 kv[4];
+                        float b[4][4];
+                        float part[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int idx = t + 4 * u + g;
+                            kv[u] = e[idx < cnt ? idx : 0];
                         }
-                        part = group_sum<16>(part);
-                        if (on && (lane & 15) == 0)
-                            reinterpret_cast<int *>(e)[2 * idx + 1] =
-                                __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int idx = t + 4 * u + g;
+                            if (idx < cnt && d < D) {
+                                load_vec<4>(bt + (kv[u].x - k0) * 64 + d, b[u]);
+                            } else {
+                                b[u][0] = b[u][1] = b[u][2] = b[u][3] = 0.f;
+                            }
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            part[u] = a[r][0] * b[u][0];
+                            part[u] = fmaf(a[r][1], b[u][1], part[u]);
+                            part[u] = fmaf(a[r][2], b[u][2], part[u]);
+                            part[u] = fmaf(a[r][3], b[u][3], part[u]);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) part[u] = group_sum<16>(part[u]);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int idx = t + 4 * u + g;
+                            if (idx < cnt && (lane & 15) == 0)
+                                reinterpret_cast<int *>(e)[2 * idx + 1] =
+                                    __builtin_bit_cast(int, __builtin_bit_cast(float, kv[u].y) * part[u]);
+                        }
                     }
                 }
             } else {
