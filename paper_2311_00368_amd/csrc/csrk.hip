@@ -280,7 +280,7 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
                               float *O) {
     using L = KTileLds<T, KT, ROWS, FUSED>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
-    static_assert(KT % 16 == 0, "the staging loops copy whole multiples of 16 rows");
+    static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
     // the register prefetch of the next tile needs 8 more float4 per thread than FusedMM can spare
     auto kern = ktile_kernel<T, KT, ROWS, FUSED, !FUSED>;
     static bool attr_set[kMaxDevices] = {};
@@ -442,7 +442,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
         gate = tile_flags(*d);
         ScopedRecord rec(3, stream);
         csrk_status s = N <= 256 ? launch_ktile<1, 96, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
-                                 : launch_ktile<2, 64, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+                                 : launch_ktile<2, 56, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         rec.end();
         if (s) return s;
     }

@@ -34,8 +34,9 @@
 // Requirements (checked on the device by analyze_kernel, else the general kernels run):
 // columns of every row non-decreasing; S dense enough for the LDS copy to pay.
 //
-// FusedMM adds a dot stage per segment: 4 entries at a time, 16 lanes x 4 floats over
-// D <= 64, rows of the first dense operand B also staged in LDS, DPP reduction; the
+// FusedMM adds a dot stage per segment: 16 entries at a time, 4 lanes x 16 floats over
+// D <= 64; the tile's rows of the first dense operand B (padded to 68 floats) and the
+// block's rows of A are staged in LDS too; two quad-permute DPP adds reduce; the
 // finished score (times the stored value) overwrites the value half of the entry's
 // pair in the LDS slot, from where the accumulate stage broadcasts it.  Scores never
 // leave the CU (Algorithm 3's `arow`).
@@ -80,12 +81,14 @@ template <int T, int KT, int ROWS, bool FUSED>
 struct KTileLds {
     static constexpr int kRowFloats = T * 256;
     static constexpr int kCFloats = KT * kRowFloats;
-    static constexpr int kDFloats = FUSED ? KT * 64 : 0;
+    static constexpr int kDStride = 68;     // FUSED: floats per staged row of B (64 + 4 so row starts spread over banks)
+    static constexpr int kDFloats = FUSED ? KT * kDStride : 0;
+    static constexpr int kAFloats = FUSED ? kTileWaves * ROWS * 64 : 0;   // FUSED: the block's rows of A
     // (column, value) pairs: SPMM keeps two 64-entry slots per wavefront so that the next
     // row's chunk is written while the current row is consumed; FusedMM has one
     static constexpr int kSlots = FUSED ? 1 : 2;
     static constexpr int kEntFloats = kTileWaves * kSlots * kWave * 2;
-    static constexpr int kBytes = (kCFloats + kDFloats + kEntFloats) * 4;
+    static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
 };
 
 template <int T, int KT, int ROWS, bool FUSED, bool PREFETCH>
@@ -100,18 +103,18 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;                        // KT x (T*256) floats
-    float *bt = lds + L::kCFloats;          // KT x 64 floats (FUSED)
-    int2 *ent = reinterpret_cast<int2 *>(bt + L::kDFloats) + wave * (L::kSlots * kWave);
+    float *bt = lds + L::kCFloats;          // KT x 68 floats (FUSED)
+    float *at = bt + L::kDFloats;           // 16*ROWS x 64 floats (FUSED): rows of A of this block, zero-padded
+    int2 *ent = reinterpret_cast<int2 *>(at + L::kAFloats) + wave * (L::kSlots * kWave);
 
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
-    const int d = (lane & 15) * 4;          // FUSED: this lane's slice of the dot length
-    const int g = lane >> 4;                // FUSED: which of 4 side-by-side entries
+    const int q16 = (lane & 3) * 16;        // FUSED: this lane's 16-float slice of the dot length
+    const int ei = lane >> 2;               // FUSED: which of 16 side-by-side entries
 
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
-    float a[FUSED ? ROWS : 1][4];
     float acc[ROWS][T][4];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -126,12 +129,13 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         for (int t = 0; t < T; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][t][v] = 0.f;
-        if constexpr (FUSED) {
-            if (row < M && d < D) {
-                load_vec<4>(A + (size_t)row * D + d, a[r]);
-            } else {
-                a[r][0] = a[r][1] = a[r][2] = a[r][3] = 0.f;
-            }
+    }
+    if constexpr (FUSED) {
+        // the block's rows of A, padded with zeros to 64 columns and to whole rows
+        const int brow0 = blockIdx.x * (kTileWaves * ROWS);
+        for (int e = threadIdx.x; e < kTileWaves * ROWS * 64; e += kTileThreads) {
+            const int rr = e >> 6, cc = e & 63;
+            at[e] = (brow0 + rr < M && cc < D) ? A[(size_t)(brow0 + rr) * D + cc] : 0.f;
         }
     }
 
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 #pragma unroll
             for (int i = 0; i < kPerB; ++i) {
                 const int e = i * kTileThreads + threadIdx.x;
-                if (e < KT * 16) dstb[e] = stageb[i];
+                if (e < KT * 16) dstb[(e >> 4) * (L::kDStride / 4) + (e & 15)] = stageb[i];
             }
         }
     };
@@ -199,43 +203,29 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                 e = ent;
                 if (cnt > 0) {
                     e[lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
-                    // dot stage: 16 entries per round, group g of 16 lanes takes entries
-                    // t+g, t+4+g, t+8+g, t+12+g; all pair reads, then all row reads, then the
-                    // arithmetic and the four DPP reductions, so LDS latency is paid once a round
+                    // dot stage: 16 entries per round; lane (ei, q) = (lane / 4, lane % 4) takes
+                    // columns 16q..16q+15 of entry t+ei, so a quad of lanes covers the dot length
+                    // and two quad-permute DPP adds finish it
+                    float av[4][4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) load_vec<4>(at + (wave * ROWS + r) * 64 + q16 + 4 * i, av[i]);
                     for (int t = 0; t < cnt; t += 16) {
-                        int2 kv[4];
+                        const int idx = t + ei;
+                        const bool on = idx < cnt;
+                        const int2 kv = e[on ? idx : 0];
+                        const float *brow = bt + (kv.x - k0) * L::kDStride + q16;
                         float b[4][4];
-                        float part[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int idx = t + 4 * u + g;
-                            kv[u] = e[idx < cnt ? idx : 0];
-                        }
+                        for (int i = 0; i < 4; ++i) load_vec<4>(brow + 4 * i, b[i]);
+                        float part = 0.f;
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int idx = t + 4 * u + g;
-                            if (idx < cnt && d < D) {
-                                load_vec<4>(bt + (kv[u].x - k0) * 64 + d, b[u]);
-                            } else {
-                                b[u][0] = b[u][1] = b[u][2] = b[u][3] = 0.f;
-                            }
-                        }
+                        for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            part[u] = a[r][0] * b[u][0];
-                            part[u] = fmaf(a[r][1], b[u][1], part[u]);
-                            part[u] = fmaf(a[r][2], b[u][2], part[u]);
-                            part[u] = fmaf(a[r][3], b[u][3], part[u]);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) part[u] = group_sum<16>(part[u]);
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const int idx = t + 4 * u + g;
-                            if (idx < cnt && (lane & 15) == 0)
-                                reinterpret_cast<int *>(e)[2 * idx + 1] =
-                                    __builtin_bit_cast(int, __builtin_bit_cast(float, kv[u].y) * part[u]);
-                        }
+                            for (int v = 0; v < 4; ++v) part = fmaf(av[i][v], b[i][v], part);
+                        part = group_sum<4>(part);
+                        if (on && (lane & 3) == 0)
+                            reinterpret_cast<int *>(e)[2 * idx + 1] =
+                                __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
                     }
                 }
             } else {
@@ -283,15 +273,15 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                     float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
                     if constexpr (FUSED) {
                         float part = 0.f;
-                        if (g == 0 && d < D) {
-                            float b[4];
-                            load_vec<4>(bt + (k - k0) * 64 + d, b);
-                            part = a[r][0] * b[0];
-                            part = fmaf(a[r][1], b[1], part);
-                            part = fmaf(a[r][2], b[2], part);
-                            part = fmaf(a[r][3], b[3], part);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            float av[4], b[4];
+                            load_vec<4>(at + (wave * ROWS + r) * 64 + q16 + 4 * i, av);
+                            load_vec<4>(bt + (k - k0) * L::kDStride + q16 + 4 * i, b);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) part = fmaf(av[v], b[v], part);
                         }
-                        part = group_sum<16>(part);
+                        part = group_sum<4>(part);
                         s *= readlane_f(part, 0);
                     }
                     const float *crow = ct + (k - k0) * L::kRowFloats + n;
