@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink M,K (debug only; invalid as a result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle's timed sample (0 = auto)")
+    ap.add_argument("--no-fusion-report", action="store_true")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB before the timed region: "
                          "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -166,6 +167,36 @@ def main():
         "device": torch.cuda.get_device_name(0),
         "input_gen_s": round(t_gen, 2),
     }
+
+    if "fusedmm" in w.ops and not args.no_fusion_report:
+        # the paper's central claim is the gain from fusing: time SDDMM -> SPMM through a materialised
+        # score array against the fused call, same operands (outside the timed region above)
+        o = w.ops["fusedmm"]
+        Pu = torch.empty((nnz,), dtype=torch.float32, device="cuda")
+        Ou = torch.empty((w.M, o["N"]), dtype=torch.float32, device="cuda")
+
+        def unfused():
+            binding.sddmm_csr(w.M, w.K, o["D"], rp, ci, v, Af, Bf, Pu)
+            binding.spmm_csr(w.M, w.K, o["N"], rp, ci, Pu, Cf, Ou)
+
+        def fused():
+            binding.fusedmm_csr(w.M, w.K, o["D"], o["N"], rp, ci, v, Af, Bf, Cf, Of)
+
+        def time_ms(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        tu, tf = time_ms(unfused), time_ms(fused)
+        result["fusion"] = {"unfused_sddmm_then_spmm_ms": round(tu, 4), "fused_ms": round(tf, 4),
+                            "fused_speedup": round(tu / tf, 3),
+                            "max_abs_diff": float((Ou - Of).abs().max().item())}
 
     if not args.no_cpu_baseline:
         import oracle

@@ -190,7 +190,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             if (k0 + KT < K) issue(k0 + KT);   // lands while this tile is being worked on
         }
         const int kend = k0 + KT;
-        const int lb = n * 4 - k0 * kRowBytes;  // lane's byte offset in a tile row, minus the tile origin
+        // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
+        // large column numbers wrap instead of overflowing (the sum below is always a small offset)
+        const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
         int cnts[ROWS];
         if constexpr (!FUSED) ent[lane] = make_int2(kc[0], __builtin_bit_cast(int, vc[0]));
 #pragma unroll
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                 for (int u = 0; u < CNT; ++u) ks[u] = e[t + u];    // same address in all lanes: broadcast
 #pragma unroll
                 for (int u = 0; u < CNT; ++u) {
-                    const char *crow = reinterpret_cast<const char *>(ct) + (ks[u].x * kRowBytes + lb);
+                    const char *crow = reinterpret_cast<const char *>(ct) + ((unsigned)ks[u].x * (unsigned)kRowBytes + lb);
 #pragma unroll
                     for (int tt = 0; tt < T; ++tt)
                         load_vec<4>(reinterpret_cast<const float *>(crow + tt * 1024), c[u][tt]);
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
                 const float *brow = lds + (in ? kcur - k0 : 0) * kStride;
                 const float *arow = A + (size_t)row * D;
                 float dot = 0.f;
-#pragma unroll 4
+#pragma unroll 8
                 for (int c4 = 0; c4 < d4n; ++c4) {
                     const float4 b = *reinterpret_cast<const float4 *>(brow + c4 * 4);
                     const float4 av = *reinterpret_cast<const float4 *>(arow + c4 * 4);   // uniform address
