@@ -146,13 +146,29 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     constexpr int kPerB = FUSED ? (KT * 16 + kTileThreads - 1) / kTileThreads : 1;
     float4 stage[kPer];
     float4 stageb[kPerB];
+    // Thread t copies float4 number (t % kRow4) of tile rows t / kRow4, + kStep, + 2 kStep, ...: its
+    // offset inside a tile never changes, so a tile costs this thread kPer loads off a uniform
+    // base pointer with no address arithmetic in vector registers.
+    constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
+    const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
+    const bool my_col = my_c4 < n4;
+    const size_t my_off = (size_t)my_kk * n4 + my_c4;
+    const size_t step_off = (size_t)kStep * n4;
     auto issue = [&](int k0) {
-        const float4 *src = reinterpret_cast<const float4 *>(Cmat);
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        if (k0 + KT <= K) {
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const int e = i * kTileThreads + threadIdx.x;
-            const int kk = e / kRow4, c4 = e % kRow4;
-            stage[i] = (k0 + kk < K && c4 < n4) ? src[(size_t)(k0 + kk) * n4 + c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = 0; i < kPer; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (my_col) {
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
+            }
+        } else {                                      // last, partial tile
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+            }
         }
         if constexpr (FUSED) {
             const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
@@ -161,8 +177,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             for (int i = 0; i < kPerB; ++i) {
                 const int e = i * kTileThreads + threadIdx.x;
                 const int kk = e >> 4, c4 = e & 15;
-                stageb[i] = (e < KT * 16 && k0 + kk < K && c4 < d4) ? srcb[(size_t)(k0 + kk) * d4 + c4]
-                                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+                stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < KT * 16 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
             }
         }
     };
@@ -302,10 +318,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (cnts[r] > 0) {
-                const int jn = pos[r] + lane;
-                const bool okn = jn < end[r];
-                kc[r] = okn ? colidx[jn] : 0x7fffffff;
-                vc[r] = okn ? (vals ? vals[jn] : 1.f) : 0.f;
+                const bool okn = lane < end[r] - pos[r];
+                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
+                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
             }
         }
     }
