@@ -31,8 +31,14 @@
 //    the next tile of the dense operand is requested into registers right after the
 //    tile barrier: no vector-memory wait ever sits inside the arithmetic.
 //
-// Requirements (checked on the device by analyze_kernel, else the general kernels run):
-// columns of every row non-decreasing; S dense enough for the LDS copy to pay.
+// Requirements: columns of every row non-decreasing; S dense enough for the LDS copy to
+// pay.  Density is read off rowptr[M] by a one-thread kernel beforehand.  Ordering is
+// verified by the tiled kernels themselves at no extra memory traffic: every look-ahead
+// chunk they load is compared lane against neighbouring lane (one DPP shift and a
+// compare), and chunks overlap, so every adjacent pair of a row passes through the check.
+// A kernel that meets a descending pair raises flags[0]; its output is then unspecified
+// (never out of bounds: the cursors only move inside the row and LDS reads cannot fault)
+// and the general kernels, which are launched right behind it, redo the whole call.
 //
 // FusedMM adds a dot stage per segment: 16 entries at a time, 4 lanes x 16 floats over
 // D <= 64; the tile's rows of the first dense operand B (padded to 68 floats) and the
@@ -53,28 +59,20 @@ constexpr int kTileWaves = kTileThreads / kWave;
 // flags[0] != 0: some row has descending columns.  flags[1] != 0: dense enough.
 __device__ __forceinline__ bool ktile_ok(const int32_t *flags) { return flags[0] == 0 && flags[1] != 0; }
 
-__global__ void reset_flags_kernel(int32_t *flags) {
-    if (threadIdx.x < 4) flags[threadIdx.x] = 0;
+// The per-call row analysis that has to precede the tiled kernels: clears the ordering flag and
+// records whether nnz = rowptr[M] reaches `min_density` of M*K.
+__global__ void reset_flags_kernel(int M, int K, const int32_t *__restrict__ rowptr, float min_density,
+                                   int32_t *flags) {
+    if (threadIdx.x == 0) {
+        flags[0] = 0;
+        flags[1] = (double)rowptr[M] >= (double)min_density * (double)M * (double)K ? 1 : 0;
+    }
 }
 
-// One pass over colidx: are all rows ascending?  Also records whether nnz reaches
-// `min_density` of M*K.  (The row analysis step of the hot path.)
-__global__ __launch_bounds__(256) void analyze_kernel(int M, int K, const int32_t *__restrict__ rowptr,
-                                                      const int32_t *__restrict__ colidx, float min_density,
-                                                      int32_t *__restrict__ flags) {
-    const int lane = lane_id();
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    if (wave == 0 && lane == 0) {
-        const double nnz = (double)rowptr[M];
-        if (nnz >= (double)min_density * (double)M * (double)K) flags[1] = 1;
-    }
-    bool bad = false;
-    for (int r = wave; r < M; r += nwaves) {
-        const int rs = rowptr[r], re = rowptr[r + 1];
-        for (int j = rs + 1 + lane; j < re; j += kWave) bad |= colidx[j - 1] > colidx[j];
-    }
-    if (__ballot(bad) != 0 && lane == 0) flags[0] = 1;
+// Lanes whose column is smaller than the column in the lane before them (lane 0 compares with itself).
+__device__ __forceinline__ unsigned long long descending_lanes(int k) {
+    const int prev = __builtin_amdgcn_update_dpp(k, k, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+    return __ballot(prev > k);
 }
 
 template <int T, int KT, int ROWS, bool FUSED>
@@ -95,7 +93,7 @@ template <int T, int KT, int ROWS, bool FUSED, bool PREFETCH>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, const int32_t *__restrict__ flags) {
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
     using L = KTileLds<T, KT, ROWS, FUSED>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
@@ -116,6 +114,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int kc[ROWS];
     float vc[ROWS];
     float acc[ROWS][T][4];
+    unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
@@ -216,6 +215,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             // entries of this tile = leading lanes of the chunk with column < kend
             const int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
             cnts[r] = cnt;
+            // order check on the chunk, here where it is first used (not where it was requested,
+            // which would make the request a wait)
+            bad |= descending_lanes(kc[r]);
             int2 *e;
             if constexpr (FUSED) {
                 e = ent;
@@ -285,8 +287,11 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             if (cnt == kWave) {
                 // rare (a row with 64 or more entries inside one tile): finish the tile's
                 // entries of this row one at a time straight from memory
+                int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
                 while (pos[r] < end[r]) {
                     const int k = uniform(colidx[pos[r]]);
+                    if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
+                    lastk = k;
                     if (k >= kend) break;
                     float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
                     if constexpr (FUSED) {
@@ -324,6 +329,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             }
         }
     }
+    if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
@@ -357,7 +363,7 @@ struct SddmmTileLds {
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     int M, int K, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
-    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, const int32_t *__restrict__ flags) {
+    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags) {
     using L = SddmmTileLds<DMAX>;
     constexpr int KT = L::kKT;
     constexpr int kStride = L::kStride;
@@ -369,6 +375,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const int d4n = D >> 2;                 // float4s per row of A / B
 
     int pos[ROWS], end[ROWS], kc[ROWS];
+    unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
@@ -397,6 +404,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
             const int row = row0 + r;
             int kcur = kc[r];
             int cnt = __builtin_popcountll(__ballot(kcur < kend));
+            bad |= descending_lanes(kcur);      // checked where first used, not where requested
             const bool any = cnt > 0;
             while (cnt > 0) {
                 const int j = pos[r] + lane;
@@ -420,6 +428,10 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
                 if (in) P[j] = v * dot;
                 pos[r] += cnt;
                 if (cnt < kWave) break;
+                // the whole chunk lay in the tile: the speculative chunk is the next one; check it
+                // and the pair that straddles the two
+                bad |= descending_lanes(knext);
+                if (__builtin_amdgcn_readlane(kcur, kWave - 1) > __builtin_amdgcn_readlane(knext, 0)) bad |= 1;
                 kcur = knext;
                 cnt = __builtin_popcountll(__ballot(kcur < kend));
             }
@@ -430,6 +442,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
             }
         }
     }
+    if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernel behind this one redoes the call
 }
 
 }  // namespace csrk

@@ -109,3 +109,35 @@ def test_skewed_rows_ktile(csrk):
     run_spmm(csrk, w.M, w.K, 256, w.rowptr, w.colidx, w.vals, C)
     run_fused(csrk, w.M, w.K, 64, 256, w.rowptr, w.colidx, w.vals, f["A"], f["B"], C)
     run_sddmm(csrk, w.M, w.K, 64, w.rowptr, w.colidx, w.vals, f["A"], f["B"])
+
+
+@pytest.mark.parametrize("swap_at", [0, 1, 62, 63, 64, 65, 126, 127, 128, 191, 500, -2])
+def test_one_descending_pair_anywhere_is_noticed(csrk, swap_at):
+    # The tiled kernels check column order themselves while streaming; a single swapped pair of
+    # neighbours, wherever it sits relative to the 64-entry chunks, must send the call to the
+    # general kernels (the result must still match the oracle).
+    rng = np.random.default_rng(1000 + swap_at)
+    M, K, D, N = 70, 1500, 64, 512
+    rows = []
+    for i in range(M):
+        L = int(rng.integers(5, 1400))
+        rows.append(sorted(rng.permutation(K)[:L].tolist()))
+    victim = int(rng.integers(0, M))
+    rows[victim] = sorted(rng.permutation(K)[:1300].tolist())      # long row: many chunks, > 64 entries in a tile
+    p = swap_at if swap_at >= 0 else len(rows[victim]) + swap_at
+    rows[victim][p], rows[victim][p + 1] = rows[victim][p + 1], rows[victim][p]
+    rp, ci = helpers.csr_from_rows(rows, K)
+    assert csrk.csrk_validate_csr(M, K, dev(rp), dev(ci)) == (0, False)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    # and the same pattern put back in order goes through the tiled kernels
+    rows[victim] = sorted(rows[victim])
+    rp, ci = helpers.csr_from_rows(rows, K)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
