@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large16k")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink M,K (debug only; invalid as a result)")
+    ap.add_argument("--shape", default="", help="with --workload custom: M,K,density,N,D (e.g. 8192,8192,0.3,128,128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle's timed sample (0 = auto)")
     ap.add_argument("--no-fusion-report", action="store_true")
@@ -77,7 +78,11 @@ def main():
     torch.cuda.set_device(0)
 
     t_gen = time.time()
-    w = inputs.workload(args.workload, scale=args.scale)
+    if args.workload == "custom":
+        m_, k_, p_, n_, d_ = args.shape.split(",")
+        w = inputs.custom_workload(int(m_), int(k_), float(p_), int(n_), int(d_))
+    else:
+        w = inputs.workload(args.workload, scale=args.scale)
     t_gen = time.time() - t_gen
     nnz = w.nnz
     dev = lambda a: torch.from_numpy(a).cuda()

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "kernels_ktile.hpp"
+#include "kernels_ktile_narrow.hpp"
 #include "kernels_nnzsplit.hpp"
 
 namespace {
@@ -57,11 +58,16 @@ struct Recorder {
 };
 Recorder g_rec;
 
-struct ScopedRecord {
+// One event pair per call: begin() before the first kernel that may do the call's arithmetic (the
+// tiled kernel if one is tried, else the general kernel), end() after the last (the general kernel),
+// so the pair always contains the kernel that did the work plus at most one that stood down.
+struct CallRecord {
     int slot = -1;
+    int kind;
     hipStream_t st;
-    ScopedRecord(int kind, hipStream_t s) : st(s) {
-        if (kind != 0 && g_rec.used < (int)g_rec.start.size()) {
+    CallRecord(int k, hipStream_t s) : kind(k), st(s) {}
+    void begin() {
+        if (slot < 0 && g_rec.used < (int)g_rec.start.size()) {
             slot = g_rec.used++;
             g_rec.kind[slot] = kind;
             (void)hipEventRecord(g_rec.start[slot], st);
@@ -69,7 +75,7 @@ struct ScopedRecord {
     }
     void end() {
         if (slot >= 0) (void)hipEventRecord(g_rec.stop[slot], st);
-        slot = -1;
+        slot = -2;
     }
 };
 
@@ -143,6 +149,7 @@ struct WidthCfg {
 
 WidthCfg out_width_cfg(int N, bool vec4) {
     if (vec4) {
+        if (N <= 32) return {4, 8, 1};
         if (N <= 64) return {4, 16, 1};
         if (N <= 128) return {4, 32, 1};
         if (N <= 256) return {4, 64, 1};
@@ -153,6 +160,7 @@ WidthCfg out_width_cfg(int N, bool vec4) {
 
 WidthCfg dot_width_cfg(int D, bool vec4) {
     if (vec4) {
+        if (D <= 32) return {4, 8, 1};
         if (D <= 64) return {4, 16, 1};
         if (D <= 128) return {4, 32, 1};
         if (D <= 256) return {4, 64, 1};
@@ -192,6 +200,7 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
         launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row, gate); \
         return true;                                                                                          \
     }
+    CSRK_FUSED_CASE(4, 8, 1)
     CSRK_FUSED_CASE(4, 16, 1)
     CSRK_FUSED_CASE(4, 32, 1)
     CSRK_FUSED_CASE(4, 64, 1)
@@ -215,9 +224,15 @@ int tile_rows_for(const DeviceState &d, int M) {
     const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
     return blocks1 >= 4ll * d.cus ? 4 : blocks1 >= 2ll * d.cus ? 2 : 1;
 }
-constexpr float kTileMinDensity = 0.02f;
+constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
+constexpr float kNarrowMinDensity = 0.18f;    // narrow-output tiled kernels (measured cross-over with the general path)
 
 int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
+
+// CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
+// (a negative threshold tells the analysis kernel so)
+float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
+float narrow_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kNarrowMinDensity; }
 
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     const int mode = env_int("CSRK_KTILE", 1);       // 1 auto, 2 force where the kernel can run, 3 off
@@ -266,12 +281,73 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
 }
 
-csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, const int32_t *ci) {
+csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, float min_density) {
     int32_t *flags = tile_flags(d);
-    (void)ci;   // column order is verified inside the tiled kernels themselves
-    hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(64), 0, st, M, K, rp, kTileMinDensity, flags);
+    // column order is verified inside the tiled kernels themselves
+    hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, st, M, K, rp, min_density, flags);
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
+}
+
+// narrow outputs (N <= 128): G entries side by side per wavefront
+bool narrow_shape_ok(const DeviceState &d, int M, int N) {
+    const int mode = env_int("CSRK_KTILE", 1);
+    if (mode == 3 || N % 4 != 0 || N > 128 || N < 4) return false;
+    if (mode == 2) return true;
+    return (long long)M >= (long long)d.cus * kTileWaves / 2;
+}
+
+template <int G, int ROWS, bool FUSED, int DMAX>
+csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                               const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                               float *O) {
+    // 128-row tiles, except where FusedMM's staging of 128-long rows of A and B would not leave room
+    constexpr int KT = (FUSED && DMAX == 128 && G == 2) ? 96 : 128;
+    using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
+    static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
+    auto kern = ktile_narrow_kernel<G, KT, ROWS, FUSED, DMAX>;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (!attr_set[dev]) {
+        CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
+        attr_set[dev] = true;
+    }
+    const int rb = kTileWaves * ROWS;
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v, A, B,
+                       C, O, tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+template <int G, bool FUSED, int DMAX>
+csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                            const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                            float *O) {
+    // two workgroups share a CU, so aim for at least two per CU before giving a wavefront more rows
+    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
+    if (blocks1 >= 8ll * d.cus)
+        return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    if (blocks1 >= 4ll * d.cus)
+        return launch_narrow_rows<G, 2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    return launch_narrow_rows<G, 1, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+}
+
+template <bool FUSED, int DMAX>
+csrk_status launch_narrow_d(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                            const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                            float *O) {
+    if (N > 64) return launch_narrow_g<2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    if (N > 32) return launch_narrow_g<4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    return launch_narrow_g<8, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+}
+
+template <bool FUSED>
+csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                          const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                          float *O) {
+    if (FUSED && D > 64) return launch_narrow_d<FUSED, 128>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    return launch_narrow_d<FUSED, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
 }
 
 template <int T, int KT, int ROWS, bool FUSED>
@@ -281,8 +357,8 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     using L = KTileLds<T, KT, ROWS, FUSED>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
-    // the register prefetch of the next tile needs 8 more float4 per thread than FusedMM can spare
-    auto kern = ktile_kernel<T, KT, ROWS, FUSED, !FUSED>;
+    // the register prefetch of the next tile needs more registers than the 512-wide FusedMM can spare
+    auto kern = ktile_kernel<T, KT, ROWS, FUSED, (!FUSED || T == 1)>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -352,21 +428,28 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int tile = c.vec * c.lg * c.t;
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     const int32_t *gate = nullptr;
-    if (vec4 && ktile_shape_ok(*d, M, K, N)) {
-        // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
-        // unless the analysis found S unsuitable (unsorted columns or too sparse)
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+    CallRecord rec(1, stream);
+    if (vec4 && narrow_shape_ok(*d, M, N)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density())) return s;
         gate = tile_flags(*d);
-        ScopedRecord rec(1, stream);
+        rec.begin();
+        csrk_status s = launch_narrow<false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
+        if (s) return s;
+    } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
+        // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
+        // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
+        gate = tile_flags(*d);
+        rec.begin();
         csrk_status s = N <= 256 ? launch_ktile<1, 128, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O)
                                  : launch_ktile<2, 64, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
-        rec.end();
         if (s) return s;
     }
-    ScopedRecord rec(gate ? 0 : 1, stream);
+    rec.begin();
 #define CSRK_SPMM_CASE(V, L, T)                                                                           \
     if (c.vec == V && c.lg == L && c.t == T)                                                              \
         launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row, gate);
+    CSRK_SPMM_CASE(4, 8, 1)
     CSRK_SPMM_CASE(4, 16, 1)
     CSRK_SPMM_CASE(4, 32, 1)
     CSRK_SPMM_CASE(4, 64, 1)
@@ -393,20 +476,21 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     const WidthCfg c = dot_width_cfg(D, vec4);
     const dim3 grid(d->workers / kWavesPerBlock);
     const int32_t *gate = nullptr;
+    CallRecord rec(2, stream);
     if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
         gate = tile_flags(*d);
-        ScopedRecord rec(2, stream);
+        rec.begin();
         csrk_status s = D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                                 : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
-        rec.end();
         if (s) return s;
     }
-    ScopedRecord rec(gate ? 0 : 2, stream);
+    rec.begin();
 #define CSRK_SDDMM_CASE(V, L, T)                                                        \
     if (c.vec == V && c.lg == L && c.t == T)                                            \
         launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate);
+    CSRK_SDDMM_CASE(4, 8, 1)
     CSRK_SDDMM_CASE(4, 16, 1)
     CSRK_SDDMM_CASE(4, 32, 1)
     CSRK_SDDMM_CASE(4, 64, 1)
@@ -437,20 +521,27 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     bool done = false;
     const int32_t *gate = nullptr;
-    if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, colidx)) return s;
+    CallRecord rec(3, stream);
+    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density())) return s;
         gate = tile_flags(*d);
-        ScopedRecord rec(3, stream);
+        rec.begin();
+        csrk_status s = launch_narrow<true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+        if (s) return s;
+    } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
+        gate = tile_flags(*d);
+        rec.begin();
         csrk_status s = N <= 256 ? launch_ktile<1, 96, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
                                  : launch_ktile<2, 56, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
-        rec.end();
         if (s) return s;
     }
-    ScopedRecord rec(gate ? 0 : 3, stream);
+    rec.begin();
 #define CSRK_DOT_CASE(V, L, T)                                                                            \
     if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                  \
         done = launch_fused_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head, \
                                        d->head_row, gate);
+    CSRK_DOT_CASE(4, 8, 1)
     CSRK_DOT_CASE(4, 16, 1)
     CSRK_DOT_CASE(4, 32, 1)
     CSRK_DOT_CASE(4, 64, 1)

@@ -59,13 +59,35 @@ constexpr int kTileWaves = kTileThreads / kWave;
 // flags[0] != 0: some row has descending columns.  flags[1] != 0: dense enough.
 __device__ __forceinline__ bool ktile_ok(const int32_t *flags) { return flags[0] == 0 && flags[1] != 0; }
 
-// The per-call row analysis that has to precede the tiled kernels: clears the ordering flag and
-// records whether nnz = rowptr[M] reaches `min_density` of M*K.
-__global__ void reset_flags_kernel(int M, int K, const int32_t *__restrict__ rowptr, float min_density,
-                                   int32_t *flags) {
+// The per-call row analysis that has to precede the tiled kernels (one workgroup): clears the
+// ordering flag and decides from rowptr alone whether the tiled kernels suit S: nnz = rowptr[M]
+// must reach `min_density` of M*K, and no row may be much longer than the mean row (the tiled
+// kernels give every wavefront a fixed set of rows and synchronise per tile, so skewed row
+// lengths are left to the equal-nonzero split of the general kernels).  A negative `min_density`
+// switches both criteria off (used by tests to reach the tiled kernels with any pattern).
+__global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const int32_t *__restrict__ rowptr,
+                                                          float min_density, int32_t *flags) {
+    __shared__ int wave_max[16];
+    int longest = 0;
+    for (int r = threadIdx.x; r < M; r += blockDim.x) {
+        const int len = rowptr[r + 1] - rowptr[r];
+        longest = len > longest ? len : longest;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const int o = __shfl_xor(longest, off);
+        longest = o > longest ? o : longest;
+    }
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = longest;
+    __syncthreads();
     if (threadIdx.x == 0) {
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) longest = wave_max[w] > longest ? wave_max[w] : longest;
+        const double nnz = (double)rowptr[M];
+        const double mean = M > 0 ? nnz / (double)M : 0.0;
+        const bool dense = nnz >= (double)min_density * (double)M * (double)K;
+        const bool even = (double)longest <= 2.0 * mean + 64.0;
         flags[0] = 0;
-        flags[1] = (double)rowptr[M] >= (double)min_density * (double)M * (double)K ? 1 : 0;
+        flags[1] = ((dense && even) || min_density < 0.f) ? 1 : 0;
     }
 }
 

@@ -1,0 +1,258 @@
+// LDS-tiled SPMM / FusedMM for narrow outputs (N <= 128): the paper's own widths, 32 and 128.
+//
+// Same scheme as ktile_kernel (a workgroup of 16 wavefronts owns 16*ROWS rows of S, sweeps K in
+// tiles staged in LDS, finds each row's entries of a tile as a prefix of a 64-entry look-ahead
+// chunk, fetches (column, scale) pairs back by LDS broadcast), with the lanes laid out for a
+// narrow dense row: the wavefront is cut into G groups of 64/G lanes, a group covers the
+// 256/G-column row with one 128-bit read per lane, and the G groups work on G different
+// entries at once.  Each group accumulates its own partial row; the G partial rows are added
+// once, at the very end.  A tile is 128 rows (64 KB at 128 columns, 32 KB at 64, 16 KB at
+// 32), so that two workgroups fit a CU and cover each other's staging phases; the staging
+// therefore goes straight through registers without a look-ahead of its own.
+//
+// A segment longer than the chunk (more than 64 entries of a row inside one tile: dense or
+// very long rows) continues chunk by chunk with blocking loads; that path is correct for any
+// length but only the first 64 entries of a segment run at full speed.
+#pragma once
+#include <type_traits>
+
+#include "device_util.hpp"
+#include "kernels_ktile.hpp"
+
+namespace csrk {
+
+// DMAX (FusedMM only): 64 or 128, the dot length the staging areas and the dot stage are laid out
+// for; D <= DMAX, shorter rows are zero-padded.
+template <int G, int KT, int ROWS, bool FUSED, int DMAX>
+struct NarrowLds {
+    static constexpr int kRowFloats = 256 / G;
+    static constexpr int kCFloats = KT * kRowFloats;
+    static constexpr int kDStride = DMAX + 4;
+    static constexpr int kDFloats = FUSED ? KT * kDStride : 0;
+    static constexpr int kAFloats = FUSED ? kTileWaves * ROWS * DMAX : 0;
+    static constexpr int kEntFloats = kTileWaves * 2 * kWave * 2;
+    static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
+};
+
+template <int G, int KT, int ROWS, bool FUSED, int DMAX>
+__global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
+    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
+    constexpr int LN = kWave / G;           // lanes per entry
+    constexpr int LQ = DMAX / 16;           // FUSED dot stage: lanes per entry (16 floats each)
+    constexpr int ER = kWave / LQ;          // FUSED dot stage: entries per round
+    constexpr int kD4 = DMAX / 4;           // float4s per staged row of A / B
+    constexpr int kRowBytes = L::kRowFloats * 4;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if (!ktile_ok(flags)) return;
+    const int lane = lane_id();
+    const int wave = uniform(threadIdx.x >> 6);
+    float *ct = lds;
+    float *bt = lds + L::kCFloats;
+    float *at = bt + L::kDFloats;
+    int2 *ent = reinterpret_cast<int2 *>(at + L::kAFloats) + wave * (2 * kWave);
+
+    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const int g = lane / LN;                // which of the G side-by-side entries
+    const int n = (lane % LN) * 4;          // this lane's first column
+    const int q16 = (lane % LQ) * 16;       // FUSED dot stage: 16-float slice of the dot length
+    const int ei = lane / LQ;               // FUSED dot stage: which of ER side-by-side entries
+
+    int pos[ROWS], end[ROWS];
+    int kc[ROWS];
+    float vc[ROWS];
+    float acc[ROWS][4];
+    unsigned long long bad = 0;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = row0 + r;
+        pos[r] = row < M ? uniform(rowptr[row]) : 0;
+        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        const int j = pos[r] + lane;
+        const bool ok = j < end[r];
+        kc[r] = ok ? colidx[j] : 0x7fffffff;
+        vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+        acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.f;
+    }
+    if constexpr (FUSED) {
+        const int brow0 = blockIdx.x * (kTileWaves * ROWS);
+        for (int e = threadIdx.x; e < kTileWaves * ROWS * DMAX; e += kTileThreads) {
+            const int rr = e / DMAX, cc = e % DMAX;
+            at[e] = (brow0 + rr < M && cc < D) ? A[(size_t)(brow0 + rr) * D + cc] : 0.f;
+        }
+    }
+
+    const int n4 = N >> 2;
+    constexpr int kRow4 = 64 / G;                       // float4s per tile row
+    constexpr int kStep = kTileThreads / kRow4;         // tile rows per round of loads
+    constexpr int kPer = KT / kStep;
+    static_assert(KT % kStep == 0, "tile height must be a whole number of load rounds");
+    constexpr int kPerB = FUSED ? (KT * kD4 + kTileThreads - 1) / kTileThreads : 1;
+    const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
+    const bool my_col = my_c4 < n4;
+    const size_t my_off = (size_t)my_kk * n4 + my_c4;
+    const size_t step_off = (size_t)kStep * n4;
+
+    for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();
+        {   // stage C[k0:k0+KT, 0:N] (and B[k0:k0+KT, 0:D]) in LDS
+            const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;
+            float4 stage[kPer];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+            }
+            float4 stageb[kPerB];
+            if constexpr (FUSED) {
+                const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
+                const int d4 = D >> 2;
+#pragma unroll
+                for (int i = 0; i < kPerB; ++i) {
+                    const int e = i * kTileThreads + threadIdx.x;
+                    const int kk = e / kD4, c4 = e % kD4;
+                    stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
+                }
+            }
+            float4 *dst = reinterpret_cast<float4 *>(ct);
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+            if constexpr (FUSED) {
+                float4 *dstb = reinterpret_cast<float4 *>(bt);
+#pragma unroll
+                for (int i = 0; i < kPerB; ++i) {
+                    const int e = i * kTileThreads + threadIdx.x;
+                    if (e < KT * kD4) dstb[(e / kD4) * (L::kDStride / 4) + (e % kD4)] = stageb[i];
+                }
+            }
+        }
+        __syncthreads();
+        const int kend = k0 + KT;
+        const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
+        bool moved[ROWS];
+
+        // one chunk's worth of a row: `cnt` leading entries of (kreg, vreg) belong to this tile
+        auto process = [&](int r, int slot, int kreg, float vreg, int cnt) {
+            int2 *e = ent + slot * kWave;
+            e[lane] = make_int2(kreg, __builtin_bit_cast(int, vreg));
+            if constexpr (FUSED) {
+                // dot stage, as in ktile_kernel: ER entries a round, LQ lanes x 16 floats per entry
+                float av[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) load_vec<4>(at + (wave * ROWS + r) * DMAX + q16 + 4 * i, av[i]);
+                for (int t = 0; t < cnt; t += ER) {
+                    const int idx = t + ei;
+                    const bool on = idx < cnt;
+                    const int2 kv = e[on ? idx : 0];
+                    const float *brow = bt + (kv.x - k0) * L::kDStride + q16;
+                    float b[4][4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) load_vec<4>(brow + 4 * i, b[i]);
+                    float part = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) part = fmaf(av[i][v], b[i][v], part);
+                    part = group_sum<LQ>(part);
+                    if (on && (lane % LQ) == 0)
+                        reinterpret_cast<int *>(e)[2 * idx + 1] =
+                            __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
+                }
+            }
+            // accumulate stage: group g takes entries t+g, t+G+g, t+2G+g, t+3G+g of each round
+            int t = 0;
+            for (; t + 4 * G <= cnt; t += 4 * G) {
+                int2 ks[4];
+                float c[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) ks[u] = e[t + u * G + g];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
+                                                                ((unsigned)ks[u].x * (unsigned)kRowBytes + lb)),
+                                c[u]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float sv = __builtin_bit_cast(float, ks[u].y);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[r][v] = fmaf(sv, c[u][v], acc[r][v]);
+                }
+            }
+            if (t < cnt) {                  // last, partial round: lanes whose entry does not exist sit out
+                int2 ks[4];
+                float c[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = t + u * G + g;
+                    ks[u] = e[idx < cnt ? idx : 0];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
+                                                                ((unsigned)ks[u].x * (unsigned)kRowBytes + lb)),
+                                c[u]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (t + u * G + g < cnt) {
+                        const float sv = __builtin_bit_cast(float, ks[u].y);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[r][v] = fmaf(sv, c[u][v], acc[r][v]);
+                    }
+                }
+            }
+        };
+
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
+            bad |= descending_lanes(kc[r]);
+            moved[r] = cnt > 0;
+            if (cnt > 0) {
+                process(r, r & 1, kc[r], vc[r], cnt);
+                pos[r] += cnt;
+                if (cnt == kWave) {
+                    // the whole chunk lay in the tile: go on chunk by chunk with blocking loads
+                    int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                    while (pos[r] < end[r]) {
+                        const bool ok2 = lane < end[r] - pos[r];
+                        const int k2 = ok2 ? (colidx + pos[r])[lane] : 0x7fffffff;
+                        const float v2 = ok2 ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                        bad |= descending_lanes(k2);
+                        if (__builtin_amdgcn_readlane(k2, 0) < lastk) bad |= 1;
+                        const int cnt2 = __builtin_popcountll(__ballot(k2 < kend));
+                        if (cnt2 == 0) break;
+                        process(r, r & 1, k2, v2, cnt2);
+                        pos[r] += cnt2;
+                        if (cnt2 < kWave) break;
+                        lastk = __builtin_amdgcn_readlane(k2, kWave - 1);
+                    }
+                }
+            }
+        }
+        // look-ahead chunks for the next tile
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (moved[r]) {
+                const bool okn = lane < end[r] - pos[r];
+                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
+                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+            }
+        }
+    }
+    // add the G partial rows of every row and store
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+#pragma unroll
+        for (int off = LN; off < kWave; off <<= 1)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
+        const int row = row0 + r;
+        if (row < M && g == 0 && n < N) store_vec<4>(O + (size_t)row * N + n, acc[r]);
+    }
+    if (bad != 0 && lane == 0) flags[0] = 1;
+}
+
+}  // namespace csrk

@@ -153,6 +153,20 @@ class Workload:
 WORKLOADS = ("tiny", "spmm4k", "sddmm4k", "fused8k_skew", "large16k")
 
 
+def custom_workload(M: int, K: int, density: float, N: int, D: int, seed: int = 0) -> Workload:
+    """Bernoulli pattern of the given density with U[-1,1] values and operands, all three
+    operations (widths N and D): e.g. the paper's benchmark shapes, M/K/N/sparsity = 8k/8k/128/70 %
+    is custom_workload(8192, 8192, 0.30, 128, 128)."""
+    rp, ci = bernoulli_csr(seed, M, K, density)
+    vals = uniform(seed, STREAM_VALS, len(ci))
+    A = uniform(seed, STREAM_A, (M, D))
+    B = uniform(seed, STREAM_B, (K, D))
+    C = uniform(seed, STREAM_C, (K, N))
+    ops = {"spmm": dict(N=N, B=C), "sddmm": dict(D=D, A=A, B=B), "fusedmm": dict(D=D, N=N, A=A, B=B, C=C)}
+    return Workload(name=f"custom_{M}x{K}_p{density:g}_N{N}_D{D}", M=M, K=K, rowptr=rp, colidx=ci, vals=vals, ops=ops,
+                    recipe=f"Bernoulli p={density:g}, vals U[-1,1], A,B x{D} and C x{N} U[-1,1]")
+
+
 def workload(name: str, seed: int = 0, scale: float = 1.0) -> Workload:
     """Build one of the five named workloads.
 

@@ -41,7 +41,9 @@ def test_spmm_ktile(csrk, M, K, N, p):
 
 
 @pytest.mark.parametrize("M,K,D,N", [(64, 64, 64, 256), (100, 257, 64, 512), (333, 417, 4, 4), (1000, 129, 32, 260),
-                                     (2048, 2048, 64, 512), (130, 70, 60, 500), (70, 300, 16, 64)])
+                                     (2048, 2048, 64, 512), (130, 70, 60, 500), (70, 300, 16, 64),
+                                     (300, 700, 128, 128), (257, 129, 100, 32), (1100, 900, 96, 64), (90, 2000, 128, 4),
+                                     (500, 500, 32, 32), (64, 640, 68, 100)])
 @pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
 def test_fusedmm_ktile(csrk, M, K, D, N, p):
     rng = np.random.default_rng(M + K + N + D)
