@@ -232,7 +232,15 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
-float narrow_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kNarrowMinDensity; }
+float narrow_min_density(const DeviceState &d, int M) {
+    if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
+    return (long long)M >= 96ll * d.cus ? 0.05f : kNarrowMinDensity;    // many rows per wavefront amortise the staging
+}
+float sddmm_min_density(const DeviceState &d, int M, int D) {
+    if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
+    if (D <= 64) return kTileMinDensity;
+    return (long long)M >= 64ll * d.cus ? 0.05f : 0.15f;    // 64 lanes = 64 entries: short segments waste lanes
+}
 
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     const int mode = env_int("CSRK_KTILE", 1);       // 1 auto, 2 force where the kernel can run, 3 off
@@ -248,7 +256,8 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     const int mode = env_int("CSRK_KTILE", 1);
     if (mode == 3 || D % 4 != 0 || D > 128 || D < 4) return false;
     if (mode == 2) return true;
-    return (long long)M >= (long long)d.cus * kTileWaves && (long long)K * D * 4 >= (1ll << 20);
+    (void)K;
+    return (long long)M >= 12ll * d.cus;
 }
 
 template <int DMAX, int ROWS>
@@ -289,12 +298,15 @@ csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const 
     return CSRK_OK;
 }
 
-// narrow outputs (N <= 128): G entries side by side per wavefront
-bool narrow_shape_ok(const DeviceState &d, int M, int N) {
+// narrow outputs (N <= 128): G entries side by side per wavefront.  Thresholds below were read off a
+// sweep of the paper's 72 benchmark shapes on MI355X (tiled against general kernel, per shape).
+bool narrow_shape_ok(const DeviceState &d, int M, int N, bool fused) {
     const int mode = env_int("CSRK_KTILE", 1);
     if (mode == 3 || N % 4 != 0 || N > 128 || N < 4) return false;
     if (mode == 2) return true;
-    return (long long)M >= (long long)d.cus * kTileWaves / 2;
+    const long long rows_per_cu = (long long)M / d.cus;
+    if (N <= 32) return rows_per_cu >= (fused ? 96 : 32);   // tiny dense operand: the general path's gathers stay in cache
+    return rows_per_cu >= 16;                               // at least one workgroup per CU at one row per wavefront
 }
 
 template <int G, int ROWS, bool FUSED, int DMAX>
@@ -429,8 +441,8 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
-    if (vec4 && narrow_shape_ok(*d, M, N)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density())) return s;
+    if (vec4 && narrow_shape_ok(*d, M, N, false)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_narrow<false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
@@ -479,7 +491,7 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     CallRecord rec(2, stream);
     if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(*d, M, D))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
@@ -522,8 +534,8 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     bool done = false;
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
-    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density())) return s;
+    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N, true)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_narrow<true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);

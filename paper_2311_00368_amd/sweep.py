@@ -1,0 +1,128 @@
+"""The paper's 72-shape benchmark grid as synthetic inputs, on one MI355X.
+
+    python -m paper_2311_00368_amd.sweep [--out gpurun_out/sweep72.md] [--iters 10]
+
+The grid is the one on the x axes of the paper's benchmark figures: 12 (M, K) pairs x sparsity
+70 / 80 / 90 % x N in {32, 128}, with D = N as in the paper.  The paper's own matrices (the
+collection of [Trevor2020]) are randomized and not available; each point is a seeded Bernoulli
+pattern of the same size and density with U[-1,1] values (`inputs.custom_workload`).  For every
+point SPMM, SDDMM and FusedMM run `iters` times after two warm-ups; the time is the minimum over
+the runs (the paper's protocol: minimum of 20 back-to-back runs) of the HIP-event pair the
+library records around each call's kernels.  Gflop/s use 2*nnz*N, 2*nnz*D and 2*nnz*(D+N).
+
+The output is a markdown table.  If the repository's benchmark is present its table of the
+paper's bars (Intel Data Center GPU Max 1550, one stack; other hardware, context only) is put
+next to the measured numbers.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+MK = [(1, 1), (3, 1), (4, 1), (2, 2), (6, 2), (8, 2), (4, 4), (12, 4), (16, 4), (8, 8), (24, 8), (32, 8)]
+SPARSITY = [70, 80, 90]
+WIDTHS = [32, 128]
+
+
+def paper_bars():
+    """{(Mk, Kk, sparsity): [sddmm32, sddmm128, spmm32, spmm128, fused32, fused128]} from the benchmark spec."""
+    path = os.path.join(ROOT, "BASELINE.md")
+    out = {}
+    try:
+        text = open(path).read()
+    except OSError:
+        return out
+    for line in text.splitlines():
+        m = re.match(r"\|\s*\d+\s*\|\s*(\d+)k/(\d+)k/(\d+)%\s*\|(.*)\|\s*$", line)
+        if m:
+            cells = [c.strip() for c in m.group(4).split("|")]
+            vals = [int(re.match(r"(\d+)", c).group(1)) for c in cells if re.match(r"\d+", c)]
+            if len(vals) == 6:
+                out[(int(m.group(1)), int(m.group(2)), int(m.group(3)))] = vals
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "sweep72.md"))
+    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--limit", type=int, default=0, help="only the first LIMIT grid points (debug)")
+    args = ap.parse_args()
+
+    import torch
+
+    from . import binding, inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("sweep needs a GPU")
+    binding.load(build_if_missing=False)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    bars = paper_bars()
+    rows = []
+    points = [(mk, sp, n) for mk in MK for sp in SPARSITY for n in WIDTHS]
+    if args.limit:
+        points = points[: args.limit]
+    t_start = time.time()
+    for (mk, kk), sp, n in points:
+        M, K, D = mk * 1024, kk * 1024, n
+        w = inputs.custom_workload(M, K, 1.0 - sp / 100.0, n, D)
+        nnz = w.nnz
+        rp, ci, v = dev(w.rowptr), dev(w.colidx), dev(w.vals)
+        A, B, C = dev(w.ops["fusedmm"]["A"]), dev(w.ops["fusedmm"]["B"]), dev(w.ops["fusedmm"]["C"])
+        O = torch.empty((M, n), dtype=torch.float32, device="cuda")
+        P = torch.empty((nnz,), dtype=torch.float32, device="cuda")
+        calls = {
+            "sddmm": (lambda: binding.sddmm_csr(M, K, D, rp, ci, v, A, B, P), 2.0 * nnz * D),
+            "spmm": (lambda: binding.spmm_csr(M, K, n, rp, ci, v, C, O), 2.0 * nnz * n),
+            "fusedmm": (lambda: binding.fusedmm_csr(M, K, D, n, rp, ci, v, A, B, C, O), 2.0 * nnz * (D + n)),
+        }
+        res = {}
+        for name, (fn, flops) in calls.items():
+            fn()
+            fn()
+            torch.cuda.synchronize()
+            binding.csrk_profile_enable(args.iters)
+            for _ in range(args.iters):
+                fn()
+            torch.cuda.synchronize()
+            times = [ms for _, ms in binding.csrk_profile_collect(args.iters + 4)]
+            binding.csrk_profile_enable(0)
+            res[name] = flops / min(times) / 1e6          # Gflop/s
+        rows.append(((mk, kk, sp, n), nnz, res))
+        print(f"{mk}k/{kk}k/{n}/{sp}%  nnz={nnz}  " + "  ".join(f"{k} {x:8.0f}" for k, x in res.items()), flush=True)
+        del rp, ci, v, A, B, C, O, P
+    wall = time.time() - t_start
+
+    col = {"sddmm": 0, "spmm": 2, "fusedmm": 4}
+    os.makedirs(os.path.dirname(args.out), exist_ok=True)
+    with open(args.out, "w") as f:
+        f.write("| M/K/N/sparsity | nnz | SDDMM | SPMM | FusedMM | paper SDDMM | paper SPMM | paper FusedMM |\n")
+        f.write("|---|---|---|---|---|---|---|---|\n")
+        wins = total = 0
+        for (mk, kk, sp, n), nnz, res in rows:
+            pb = bars.get((mk, kk, sp))
+            cells = []
+            for name in ("sddmm", "spmm", "fusedmm"):
+                if pb:
+                    ref = pb[col[name] + (1 if n == 128 else 0)]
+                    cells.append(str(ref))
+                    total += 1
+                    wins += res[name] > ref
+                else:
+                    cells.append("-")
+            f.write(f"| {mk}k/{kk}k/{n}/{sp}% | {nnz} | {res['sddmm']:.0f} | {res['spmm']:.0f} | {res['fusedmm']:.0f} | "
+                    + " | ".join(cells) + " |\n")
+        f.write(f"\nGflop/s, minimum over {args.iters} runs per point; {len(rows)} grid points in {wall:.0f} s.\n")
+        if total:
+            f.write(f"Measured value above the paper's bar (Intel Max 1550, one stack; context, other hardware) in "
+                    f"{wins} of {total} comparisons.\n")
+    print(f"wrote {args.out}")
+
+
+if __name__ == "__main__":
+    main()
