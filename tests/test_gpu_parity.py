@@ -249,3 +249,95 @@ def test_workload_large16k_sampled_rows(csrk):
     run_fused(csrk, w.M, w.K, 64, 512, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
     s = w.ops["sddmm"]
     run_sddmm(csrk, w.M, w.K, 64, w.rowptr, w.colidx, w.vals, s["A"], s["B"], rows=rows)
+
+
+# ------------------------------------------------------------------ call-site variations
+def test_misaligned_operands_take_the_scalar_path(csrk):
+    # dense operands that start 4 bytes off a 16-byte boundary cannot use 128-bit accesses;
+    # the library must notice and still be right
+    rng = np.random.default_rng(8)
+    M, K, N, D = 200, 300, 64, 64
+    rp, ci = inputs.bernoulli_csr(8, M, K, 0.2)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+
+    def off(a):                 # same values, storage shifted by one float
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        view = buf[1:].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 == 4
+        return view
+
+    d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
+    O = csrk.spmm_csr(M, K, N, d_rp, d_ci, d_v, off(C)).cpu().numpy()
+    want, a = oracle.spmm(M, K, N, rp, ci, v, C)
+    check(O, want, a, "spmm misaligned B")
+    O_buf = torch.empty(M * N + 1, dtype=torch.float32, device="cuda")[1:].view(M, N)
+    csrk.spmm_csr(M, K, N, d_rp, d_ci, d_v, dev(C), O=O_buf)
+    check(O_buf.cpu().numpy(), want, a, "spmm misaligned O")
+    P = csrk.sddmm_csr(M, K, D, d_rp, d_ci, d_v, off(A), off(B)).cpu().numpy()
+    wantp, ap = oracle.sddmm(M, K, D, rp, ci, v, A, B)
+    check(P, wantp, ap, "sddmm misaligned A, B")
+    F = csrk.fusedmm_csr(M, K, D, N, d_rp, d_ci, d_v, off(A), dev(B), off(C)).cpu().numpy()
+    wantf, af = oracle.fusedmm(M, K, D, N, rp, ci, v, A, B, C)
+    check(F, wantf, af, "fusedmm misaligned A, C")
+
+
+def test_side_stream_and_growing_scratch(csrk):
+    # calls enqueued on a non-default stream, with output widths that make the library's
+    # partial-row scratch grow between calls
+    rng = np.random.default_rng(9)
+    M, K = 300, 400
+    rp, ci = inputs.bernoulli_csr(9, M, K, 0.25)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
+    csrk.csrk_release_workspace()
+    side = torch.cuda.Stream()
+    for N in (8, 64, 640, 72):
+        C = rng.normal(size=(K, N)).astype(np.float32)
+        d_C = dev(C)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            O = csrk.spmm_csr(M, K, N, d_rp, d_ci, d_v, d_C)
+        side.synchronize()
+        want, a = oracle.spmm(M, K, N, rp, ci, v, C)
+        check(O.cpu().numpy(), want, a, f"spmm on a side stream, N={N}")
+
+
+def test_back_to_back_calls_do_not_disturb_each_other(csrk):
+    # three different calls queued without synchronising in between share the library's
+    # flags and scratch; stream order must keep them apart
+    w = inputs.workload("tiny")
+    f = w.ops["fusedmm"]
+    d = dict(rp=dev(w.rowptr), ci=dev(w.colidx), v=dev(w.vals), A=dev(f["A"]), B=dev(f["B"]), C=dev(f["C"]))
+    outs = []
+    for _ in range(3):
+        outs.append((csrk.spmm_csr(w.M, w.K, 64, d["rp"], d["ci"], d["v"], d["C"]),
+                     csrk.sddmm_csr(w.M, w.K, 64, d["rp"], d["ci"], d["v"], d["A"], d["B"]),
+                     csrk.fusedmm_csr(w.M, w.K, 64, 64, d["rp"], d["ci"], d["v"], d["A"], d["B"], d["C"])))
+    torch.cuda.synchronize()
+    so, sa = oracle.spmm(w.M, w.K, 64, w.rowptr, w.colidx, w.vals, f["C"])
+    po, pa = oracle.sddmm(w.M, w.K, 64, w.rowptr, w.colidx, w.vals, f["A"], f["B"])
+    fo, fa = oracle.fusedmm(w.M, w.K, 64, 64, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"])
+    for O, P, F in outs:
+        check(O.cpu().numpy(), so, sa, "spmm back to back")
+        check(P.cpu().numpy(), po, pa, "sddmm back to back")
+        check(F.cpu().numpy(), fo, fa, "fusedmm back to back")
+    for O, P, F in outs[1:]:
+        assert torch.equal(O, outs[0][0]) and torch.equal(P, outs[0][1]) and torch.equal(F, outs[0][2])
+
+
+@pytest.mark.parametrize("shape", [(4096, 4096, 0.3, 128, 128), (8192, 2048, 0.2, 32, 32), (4100, 1000, 0.25, 100, 60),
+                                   (9000, 3000, 0.07, 128, 64), (5000, 5000, 0.2, 256, 64)])
+def test_automatic_kernel_choice_mid_sizes(csrk, shape):
+    # shapes around the dispatch thresholds (narrow tiled / wide tiled / general), default mode,
+    # a sample of rows checked (rows are independent)
+    M, K, p, N, D = shape
+    w = inputs.custom_workload(M, K, p, N, D, seed=3)
+    rows = np.unique(np.concatenate([np.arange(0, M, 37), [0, 1, M - 2, M - 1]])).astype(np.int32)
+    f = w.ops["fusedmm"]
+    run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
+    run_sddmm(csrk, M, K, D, w.rowptr, w.colidx, w.vals, f["A"], f["B"], rows=rows)
+    run_fused(csrk, M, K, D, N, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
