@@ -369,8 +369,11 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     using L = KTileLds<T, KT, ROWS, FUSED>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
-    // the register prefetch of the next tile needs more registers than the 512-wide FusedMM can spare
-    auto kern = ktile_kernel<T, KT, ROWS, FUSED, (!FUSED || T == 1)>;
+    // how much of the next tile is prefetched into registers: all of it, except in the 512-wide
+    // FusedMM, whose dot stage leaves registers for 3 of a thread's 7 loads
+    constexpr int kPer = KT * T * 64 / kTileThreads;
+    constexpr int kPrefetch = (FUSED && T == 2) ? 3 : kPer;
+    auto kern = ktile_kernel<T, KT, ROWS, FUSED, kPrefetch>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));

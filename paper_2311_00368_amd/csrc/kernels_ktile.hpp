@@ -111,7 +111,9 @@ struct KTileLds {
     static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
 };
 
-template <int T, int KT, int ROWS, bool FUSED, bool PREFETCH>
+// PF: how many of a thread's kPer loads of the next C tile are issued one tile ahead (0 = none, kPer = all);
+// the rest are loaded at the start of their own tile, and so is FusedMM's B tile unless PF = kPer.
+template <int T, int KT, int ROWS, bool FUSED, int PF>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
@@ -175,22 +177,27 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const bool my_col = my_c4 < n4;
     const size_t my_off = (size_t)my_kk * n4 + my_c4;
     const size_t step_off = (size_t)kStep * n4;
-    auto issue = [&](int k0) {
+    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
+    // loads number [I0, I1) of this thread for the C tile that starts at column k0
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
         const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
         if (k0 + KT <= K) {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (my_col) {
 #pragma unroll
-                for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
+                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
             }
         } else {                                      // last, partial tile
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
+            for (int i = I0; i < I1; ++i) {
                 stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
             }
         }
+    };
+    auto issue_b = [&](int k0) {
         if constexpr (FUSED) {
             const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
             const int d4 = D >> 2;
@@ -203,6 +210,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             }
         }
     };
+    using I0 = std::integral_constant<int, 0>;
+    using IPF = std::integral_constant<int, PF>;
+    using IEND = std::integral_constant<int, kPer>;
     auto commit = [&]() {
         float4 *dst = reinterpret_cast<float4 *>(ct);
 #pragma unroll
@@ -217,14 +227,22 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         }
     };
 
-    if constexpr (PREFETCH) issue(0);
+    constexpr bool kAllAhead = PF == kPer;      // then FusedMM's B tile is prefetched as well
+    if constexpr (PF > 0) issue(0, I0{}, IPF{});
+    if constexpr (kAllAhead) issue_b(0);
     for (int k0 = 0; k0 < K; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
-        if constexpr (!PREFETCH) issue(k0);
+        if constexpr (!kAllAhead) {
+            issue(k0, IPF{}, IEND{});
+            issue_b(k0);
+        }
         commit();
         __syncthreads();
-        if constexpr (PREFETCH) {
-            if (k0 + KT < K) issue(k0 + KT);   // lands while this tile is being worked on
+        if constexpr (PF > 0) {
+            if (k0 + KT < K) {                  // lands while this tile is being worked on
+                issue(k0 + KT, I0{}, IPF{});
+                if constexpr (kAllAhead) issue_b(k0 + KT);
+            }
         }
         const int kend = k0 + KT;
         // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
