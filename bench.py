@@ -10,7 +10,11 @@ workload is the 16384 x 16384, 20 %-dense configuration the benchmark spec's target is
 
   value        GFLOP/s of the whole step, flops = 2*nnz*N (SPMM) + 2*nnz*D (SDDMM)
                + 2*nnz*(D+N) (FusedMM)
-  ops          per-operation GFLOP/s from HIP events around each operation's main kernel
+  ops          per operation, from HIP events around its kernels: GFLOP/s (mean, median, best), the
+               fractions of the FP32 peak, of the plain-FMA ceiling and of HBM bandwidth (algorithmic
+               bytes), the rate at which gathered dense rows reach the ALUs (nnz * width * 4 bytes / time)
+               against the micro-benchmarked LDS read rate, one cold run (caches flushed by writing
+               a 1 GiB buffer) and the wall time of the very first call (workspace allocation included)
   roofline     the dominant kernel against MI355X's FP32 vector peak (157.3 TFLOP/s)
   cpu_baseline the FP64 CPU oracle timed on a sample of the rows of the same workload
 
@@ -28,8 +32,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X: 256 CUs x 2.4 GHz x 256 flop/clk/CU
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X: 256 CUs x 2.4 GHz x 256 flop/clk/CU (needs packed FP32)
+FP32_FMA_CEILING_TFLOPS = 78.6    # one v_fma_f32 per SIMD per 4 clocks: 128 flop/clk/CU (packed FP32 is switched off)
 HBM_PEAK_GBS = 8000.0
+LDS_READ_MEASURED_TBS = 95.7      # 128-bit LDS reads, 16 wavefronts per CU, micro-benchmarked: 155.7 B/clk/CU
 
 KIND = {1: "spmm", 2: "sddmm", 3: "fusedmm"}
 
@@ -109,6 +115,21 @@ def main():
         ops.append(("fusedmm", lambda: binding.fusedmm_csr(w.M, w.K, Df, Nf, rp, ci, v, Af, Bf, Cf, Of)))
         flops["fusedmm"] = 2.0 * nnz * (Df + Nf)
     step_flops = sum(flops.values())
+    # algorithmic HBM bytes per call: S streamed once, every dense operand once, the output once
+    csr_bytes = 8.0 * nnz + 4.0 * (w.M + 1)
+    hbm_bytes, gather_bytes = {}, {}
+    if "spmm" in w.ops:
+        n_ = w.ops["spmm"]["N"]
+        hbm_bytes["spmm"] = csr_bytes + 4.0 * n_ * (w.K + w.M)
+        gather_bytes["spmm"] = 4.0 * nnz * n_
+    if "sddmm" in w.ops:
+        d_ = w.ops["sddmm"]["D"]
+        hbm_bytes["sddmm"] = csr_bytes + 4.0 * nnz + 4.0 * d_ * (w.K + w.M)
+        gather_bytes["sddmm"] = 4.0 * nnz * d_
+    if "fusedmm" in w.ops:
+        d_, n_ = w.ops["fusedmm"]["D"], w.ops["fusedmm"]["N"]
+        hbm_bytes["fusedmm"] = csr_bytes + 4.0 * d_ * (w.K + w.M) + 4.0 * n_ * (w.K + w.M)
+        gather_bytes["fusedmm"] = 4.0 * nnz * (d_ + n_)
 
     def step():
         for _, fn in ops:
@@ -120,7 +141,14 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    first_call_ms = {}
+    for name, fn in ops:                       # very first call of each operation: allocates the workspace
+        torch.cuda.synchronize()
+        t_first = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        first_call_ms[name] = (time.perf_counter() - t_first) * 1e3
+    for _ in range(max(0, args.warmup - 1)):
         step()
     torch.cuda.synchronize()
     binding.csrk_profile_enable(args.steps * len(ops))
@@ -134,16 +162,38 @@ def main():
     binding.csrk_profile_enable(0)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # one cold run per operation: a 1 GiB fill pushes the operands out of L2 and the 256 MB memory-side cache
+    cold_ms = {}
+    flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    for name, fn in ops:
+        flush.fill_(1.0)
+        torch.cuda.synchronize()
+        binding.csrk_profile_enable(1)
+        fn()
+        torch.cuda.synchronize()
+        rec = binding.csrk_profile_collect(4)
+        binding.csrk_profile_enable(0)
+        if rec:
+            cold_ms[name] = rec[0][1]
+    del flush
     per_op = {}
     for kind, ms in records:
         per_op.setdefault(KIND[kind], []).append(ms)
     op_report = {}
     for name, times in per_op.items():
-        avg, mn = float(np.mean(times)), float(np.min(times))
+        avg, mn, med = float(np.mean(times)), float(np.min(times)), float(np.median(times))
+        tf = flops[name] / avg / 1e9
         op_report[name] = {
-            "kernel_ms_avg": round(avg, 4), "kernel_ms_min": round(mn, 4),
+            "kernel_ms_avg": round(avg, 4), "kernel_ms_median": round(med, 4), "kernel_ms_min": round(mn, 4),
+            "kernel_ms_cold": round(cold_ms[name], 4) if name in cold_ms else None,
+            "first_call_wall_ms": round(first_call_ms[name], 3),
             "gflops_avg": round(flops[name] / avg / 1e6, 1), "gflops_best": round(flops[name] / mn / 1e6, 1),
-            "frac_fp32_peak": round(flops[name] / avg / 1e9 / FP32_VECTOR_PEAK_TFLOPS, 4),
+            "frac_fp32_peak": round(tf / FP32_VECTOR_PEAK_TFLOPS, 4),
+            "frac_fma_ceiling": round(tf / FP32_FMA_CEILING_TFLOPS, 4),
+            "hbm_algorithmic_bytes": int(hbm_bytes[name]),
+            "frac_hbm_peak": round(hbm_bytes[name] / avg / 1e6 / HBM_PEAK_GBS, 4),
+            "gathered_TBps": round(gather_bytes[name] / avg / 1e9, 2),
+            "frac_lds_read_measured": round(gather_bytes[name] / avg / 1e9 / LDS_READ_MEASURED_TBS, 4),
         }
     # dominant kernel = the one the step spends most time in
     dom = max(per_op, key=lambda k: float(np.mean(per_op[k])))
@@ -160,7 +210,7 @@ def main():
         "metric": "GFLOP/s (2*nnz*N) for SPMM + SDDMM + FusedMM, one pass each",
         "value": round(step_flops / ms_per_step / 1e6, 1),
         "unit": "GFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": max(1, args.warmup),
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
@@ -212,26 +262,36 @@ def main():
         if args.cpu_rows:
             rows = rows[: args.cpu_rows]
         row_nnz = int(np.sum(w.rowptr[rows + 1] - w.rowptr[rows]))
-        t_cpu = time.perf_counter()
-        cpu_flops = 0.0
-        if "spmm" in w.ops:
-            o = w.ops["spmm"]
-            oracle.spmm(w.M, w.K, o["N"], w.rowptr, w.colidx, w.vals, o["B"], rows=rows)
-            cpu_flops += 2.0 * row_nnz * o["N"]
-        if "sddmm" in w.ops:
-            o = w.ops["sddmm"]
-            oracle.sddmm(w.M, w.K, o["D"], w.rowptr, w.colidx, w.vals, o["A"], o["B"], rows=rows)
-            cpu_flops += 2.0 * row_nnz * o["D"]
-        if "fusedmm" in w.ops:
-            o = w.ops["fusedmm"]
-            oracle.fusedmm(w.M, w.K, o["D"], o["N"], w.rowptr, w.colidx, w.vals, o["A"], o["B"], o["C"], rows=rows)
-            cpu_flops += 2.0 * row_nnz * (o["D"] + o["N"])
-        t_cpu = time.perf_counter() - t_cpu
+
+        def oracle_pass():
+            fl = 0.0
+            if "spmm" in w.ops:
+                o = w.ops["spmm"]
+                oracle.spmm(w.M, w.K, o["N"], w.rowptr, w.colidx, w.vals, o["B"], rows=rows)
+                fl += 2.0 * row_nnz * o["N"]
+            if "sddmm" in w.ops:
+                o = w.ops["sddmm"]
+                oracle.sddmm(w.M, w.K, o["D"], w.rowptr, w.colidx, w.vals, o["A"], o["B"], rows=rows)
+                fl += 2.0 * row_nnz * o["D"]
+            if "fusedmm" in w.ops:
+                o = w.ops["fusedmm"]
+                oracle.fusedmm(w.M, w.K, o["D"], o["N"], w.rowptr, w.colidx, w.vals, o["A"], o["B"], o["C"],
+                               rows=rows)
+                fl += 2.0 * row_nnz * (o["D"] + o["N"])
+            return fl
+
+        # repeat the sample until about 10 s of CPU work have been timed (at most 12 passes)
+        t_begin = time.perf_counter()
+        cpu_flops, passes = 0.0, 0
+        while passes < 12 and (passes == 0 or time.perf_counter() - t_begin < 10.0):
+            cpu_flops += oracle_pass()
+            passes += 1
+        t_cpu = time.perf_counter() - t_begin
         result["cpu_baseline"] = {
             "value": round(cpu_flops / t_cpu / 1e9, 2), "unit": "GFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle",
             "sample": f"every {stride}th row ({len(rows)} rows, {row_nnz} stored entries) of the same workload, "
-                      f"all three operations, {t_cpu:.1f} s",
+                      f"all three operations, {passes} passes, {t_cpu:.1f} s",
         }
     print(json.dumps(result), flush=True)
 

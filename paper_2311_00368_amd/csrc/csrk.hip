@@ -285,7 +285,9 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
                                     const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
     // rows per wavefront: as many as still leave every CU a workgroup
     const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
-    if (blocks1 >= 4ll * d.cus) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
+    // (the 128-wide kernel keeps two rows of A per lane in registers: four would spill)
+    if constexpr (DMAX <= 64)
+        if (blocks1 >= 4ll * d.cus) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
     if (blocks1 >= 2ll * d.cus) return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
     return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
 }

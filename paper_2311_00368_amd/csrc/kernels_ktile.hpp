@@ -359,7 +359,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                 }
             }
         }
-        // look-ahead chunks for the next tile, all requested here, after the arithmetic
+        // look-ahead chunks for the next tile, all requested here, after the arithmetic (requested
+        // earlier, inside the row loop, they measure slower)
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (cnts[r] > 0) {
@@ -384,21 +385,49 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 
 // ---------------------------------------------------------------------------------------
 // LDS-tiled SDDMM.  Lanes are ENTRIES here, not columns: a wavefront takes a chunk of 64
-// stored entries of one row, lane j walks the dot length for its own entry, reading its
-// row of B from the LDS tile 128 bits at a time (rows padded by 4 floats so that the 64
-// row starts spread over the banks) while the row of A, the same for all lanes, sits in
-// scalar registers.  No cross-lane reduction, results leave as one coalesced 256-byte
-// store per chunk (Algorithm 1's loop nest with the two loops swapped between lanes and
-// time).  Nothing is carried from tile to tile except the per-row cursor and look-ahead
-// chunk, found exactly as in ktile_kernel.  P may alias vals: each lane reads its value
+// stored entries of one row and lane j walks the dot length for its own entry, reading its
+// row of B from the LDS tile 128 bits at a time.  No cross-lane reduction, results leave as
+// one coalesced 256-byte store per chunk (Algorithm 1's loop nest with the two loops swapped
+// between lanes and time).
+//
+// Sixty-four lanes that each read 16 bytes of a different, arbitrary row would collide in the
+// LDS banks (rows start at the same bank), so every lane walks its row in a ROTATED order:
+// at step s lane i (numbered inside its group of 16 lanes) reads the 16-byte piece number
+// (i + s) mod 16 of its row.  The 16 lanes the LDS serves together then touch 16 different
+// pieces, i.e. all banks once, whatever rows they are in; no padding is needed.  The row of
+// A that multiplies these pieces is spread over the same 16 lanes, piece i in lane i, and
+// the rotation `row_ror:s` of the DPP operand of the multiply-add hands lane i piece (i + s)
+// at no extra instruction.  Nothing is carried from tile to tile except the per-row cursor
+// and look-ahead chunk, found exactly as in ktile_kernel; the next tile of B is fetched into
+// registers while the current one is worked on.  P may alias vals: each lane reads its value
 // before writing its result.
 // ---------------------------------------------------------------------------------------
 template <int DMAX>
 struct SddmmTileLds {
-    static constexpr int kStride = DMAX + 4;                              // floats per LDS row
-    static constexpr int kKT = (150 * 1024 / (kStride * 4)) / 64 * 64;    // tile height
-    static constexpr int kBytes = kKT * kStride * 4;
+    static constexpr int kPieces = DMAX / 4;                    // 128-bit pieces per LDS row
+    static constexpr int kKT = 147456 / (DMAX * 4);             // tile height: 144 KB of rows of B
+    static constexpr int kBytes = kKT * DMAX * 4;
 };
+
+template <int I0, int I1, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
+// acc += a' * b, where a' is the value of `a` in the lane that the rotation row_ror:S of a row of 16 lanes
+// pairs with this one.  Written as the one DPP multiply-add it is meant to be: left to the compiler, the
+// rotated values (loop invariants) are hoisted out of the loop as hundreds of extra live registers.
+template <int S>
+__device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
+    if constexpr (S == 0) {
+        acc = fmaf(a, b, acc);
+    } else {
+        asm("v_fmac_f32_dpp %0, %1, %2 row_ror:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(a), "v"(b), "n"(S));
+    }
+}
 
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
@@ -406,7 +435,12 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags) {
     using L = SddmmTileLds<DMAX>;
     constexpr int KT = L::kKT;
-    constexpr int kStride = L::kStride;
+    constexpr int C = L::kPieces;
+    constexpr int S = C < 16 ? C : 16;      // steps of the dot loop
+    constexpr int H = C / S;                // 16-piece halves of a row (2 when DMAX = 128)
+    constexpr int GL = 4;                   // LDS reads per group
+    constexpr int NG = S * H / GL;
+    static_assert(S * H % GL == 0, "whole groups of reads");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
     const int lane = lane_id();
@@ -414,7 +448,20 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int d4n = D >> 2;                 // float4s per row of A / B
 
+    // which way row_ror turns is measured, not assumed: `turn` is +1 or -1 (mod 16)
+    const int i16 = lane & 15;
+    const int turn = (__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15;
+    int off[S];                             // byte offset in an LDS row of the piece read at step s
+#pragma unroll
+    for (int s = 0; s < S; ++s) off[s] = ((i16 + turn * s) & (S - 1)) * 16;
+
+    // vals == NULL means all ones: the value loads then read colidx instead (any readable array of
+    // the same length serves) and their results are not used
+    const bool has_vals = vals != nullptr;
+    const float *vsrc = has_vals ? vals : reinterpret_cast<const float *>(colidx);
     int pos[ROWS], end[ROWS], kc[ROWS];
+    float vc[ROWS];                         // look-ahead chunk: columns and values of the next 64 entries of each row
+    float a[ROWS][H][4];                    // this lane's pieces of the rows of A, zero beyond D
     unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -423,62 +470,121 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
         const int j = pos[r] + lane;
         kc[r] = j < end[r] ? colidx[j] : 0x7fffffff;
+        vc[r] = j < end[r] ? vsrc[j] : 1.f;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            const int piece = h * 16 + (i16 & (S - 1));
+#pragma unroll
+            for (int v = 0; v < 4; ++v) a[r][h][v] = 0.f;
+            if (row < M && piece < d4n) load_vec<4>(A + (size_t)row * D + piece * 4, a[r][h]);
+        }
     }
 
-    for (int k0 = 0; k0 < K; k0 += KT) {
-        __syncthreads();
-        // stage B[k0:k0+KT, 0:D] with padded rows
-        {
-            const float4 *src = reinterpret_cast<const float4 *>(Bmat) + (size_t)k0 * d4n;
-            const int rows_here = K - k0 < KT ? K - k0 : KT;
-            const int total4 = rows_here * d4n;
-            for (int e = threadIdx.x; e < total4; e += kTileThreads) {
-                const int kk = e / d4n, c4 = e - kk * d4n;
-                *reinterpret_cast<float4 *>(lds + kk * kStride + c4 * 4) = src[e];
+    // ---- staging of the tiles of B: global -> registers (`issue`), registers -> LDS (`commit`)
+    constexpr int kRound = kTileThreads / C;            // tile rows covered by one round of loads
+    constexpr int kPer = KT / kRound;
+    static_assert(KT % kRound == 0, "tile height must be whole rounds of loads");
+    float4 stage[kPer];
+    const int my_kk = threadIdx.x / C, my_c = threadIdx.x % C;
+    const bool my_col = my_c < d4n;
+    // Every thread issues the same kPer loads for every tile, with no branch around them, so that
+    // the compiler can count outstanding loads exactly and waits for a look-ahead chunk do not also
+    // wait for the tile behind it.  Threads of the padding columns (D < DMAX) re-read the row's last
+    // piece and write zeros; rows past K in the last tile re-read row K-1 and are never used.
+    const size_t my_off = (size_t)my_kk * d4n + (my_col ? my_c : d4n - 1);
+    const size_t step_off = (size_t)kRound * d4n;
+    auto issue = [&](int k0) {
+        const float4 *src = reinterpret_cast<const float4 *>(Bmat);
+        if (k0 + KT <= K) {
+            const float4 *tile = src + (size_t)k0 * d4n;   // uniform
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
+        } else {                                           // last, partial tile: clamp the row
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int k = k0 + i * kRound + my_kk;
+                stage[i] = src[(size_t)(k < K ? k : K - 1) * d4n + (my_col ? my_c : d4n - 1)];
             }
         }
+    };
+    auto commit = [&]() {
+        float4 *dst = reinterpret_cast<float4 *>(lds);   // row kk, piece c sits at float4 number kk * C + c
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            float4 x = stage[i];
+            if (!my_col) x = make_float4(0.f, 0.f, 0.f, 0.f);
+            dst[i * kTileThreads + threadIdx.x] = x;
+        }
+    };
+
+    issue(0);
+    for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();                    // previous tile fully consumed
+        commit();
         __syncthreads();
+        if (k0 + KT < K) issue(k0 + KT);    // lands while this tile is being worked on
         const int kend = k0 + KT;
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            const int row = row0 + r;
-            int kcur = kc[r];
+            // the look-ahead registers hold what was loaded from clamped positions: mask the lanes past the row's end
+            const bool live = lane < end[r] - pos[r];
+            int kcur = live ? kc[r] : 0x7fffffff;
+            float vcur = vc[r];
             int cnt = __builtin_popcountll(__ballot(kcur < kend));
             bad |= descending_lanes(kcur);      // checked where first used, not where requested
             const bool any = cnt > 0;
             while (cnt > 0) {
                 const int j = pos[r] + lane;
                 const bool in = lane < cnt;
-                // speculative look-ahead: the chunk that follows if this one lies wholly in the tile
+                // speculative look-ahead: the chunk that follows if this one lies wholly in the tile.  Loaded
+                // without a branch (position clamped into the row, which has entries here), selected at its use
                 const int jn = j + kWave;
-                const int knext = jn < end[r] ? colidx[jn] : 0x7fffffff;
-                const float v = (in && vals) ? vals[j] : 1.f;
-                const float *brow = lds + (in ? kcur - k0 : 0) * kStride;
-                const float *arow = A + (size_t)row * D;
+                const bool has_next = jn < end[r];
+                const int jl = has_next ? jn : end[r] - 1;
+                const int kload = colidx[jl];
+                const float vload = vsrc[jl];
+                const char *brow = reinterpret_cast<const char *>(lds) + (unsigned)(in ? kcur - k0 : 0) * (DMAX * 4);
+                // the row's S * H pieces in groups of GL reads, the next group requested before the
+                // multiply-adds of the current one
                 float dot = 0.f;
-#pragma unroll 8
-                for (int c4 = 0; c4 < d4n; ++c4) {
-                    const float4 b = *reinterpret_cast<const float4 *>(brow + c4 * 4);
-                    const float4 av = *reinterpret_cast<const float4 *>(arow + c4 * 4);   // uniform address
-                    dot = fmaf(av.x, b.x, dot);
-                    dot = fmaf(av.y, b.y, dot);
-                    dot = fmaf(av.z, b.z, dot);
-                    dot = fmaf(av.w, b.w, dot);
-                }
-                if (in) P[j] = v * dot;
+                float b[2][GL][4];
+                auto read_group = [&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    static_for<0, GL>([&](auto uc) {
+                        constexpr int q = g * GL + decltype(uc)::value;
+                        load_vec<4>(reinterpret_cast<const float *>(brow + off[q / H] + (q % H) * 256),
+                                    b[g & 1][decltype(uc)::value]);
+                    });
+                };
+                read_group(std::integral_constant<int, 0>{});
+                static_for<0, NG>([&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    if constexpr (g + 1 < NG) read_group(std::integral_constant<int, g + 1>{});
+                    static_for<0, GL>([&](auto uc) {
+                        constexpr int u = decltype(uc)::value;
+                        constexpr int q = g * GL + u;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) fma_row_rotated<q / H>(dot, a[r][q % H][c], b[g & 1][u][c]);
+                    });
+                });
+                if (in) P[j] = (has_vals ? vcur : 1.f) * dot;
                 pos[r] += cnt;
                 if (cnt < kWave) break;
                 // the whole chunk lay in the tile: the speculative chunk is the next one; check it
                 // and the pair that straddles the two
+                const int knext = has_next ? kload : 0x7fffffff;
                 bad |= descending_lanes(knext);
                 if (__builtin_amdgcn_readlane(kcur, kWave - 1) > __builtin_amdgcn_readlane(knext, 0)) bad |= 1;
                 kcur = knext;
+                vcur = vload;
                 cnt = __builtin_popcountll(__ballot(kcur < kend));
             }
-            // look-ahead chunk for the next tile
+            // look-ahead chunk for the next tile (clamped like the speculative one)
             if (any) {
                 const int j = pos[r] + lane;
-                kc[r] = j < end[r] ? colidx[j] : 0x7fffffff;
+                const int jl = j < end[r] ? j : end[r] - 1;
+                kc[r] = colidx[jl];
+                vc[r] = vsrc[jl];
             }
         }
     }
