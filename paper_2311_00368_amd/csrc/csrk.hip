@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "kernels_ktile.hpp"
+#include "kernels_ktile_fused.hpp"
 #include "kernels_ktile_narrow.hpp"
 #include "kernels_nnzsplit.hpp"
 
@@ -364,18 +365,49 @@ csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int D, i
     return launch_narrow_d<FUSED, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
 }
 
-template <int T, int KT, int ROWS, bool FUSED>
-csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                              const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                              float *O) {
-    using L = KTileLds<T, KT, ROWS, FUSED>;
+template <int T, int KT, int ROWS>
+csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
+                              const int32_t *ci, const float *v, const float *B, float *O) {
+    using L = KTileLds<T, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
-    // how much of the next tile is prefetched into registers: all of it, except in the 512-wide
-    // FusedMM, whose dot stage leaves registers for 3 of a thread's 7 loads
+    auto kern = ktile_kernel<T, KT, ROWS>;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (!attr_set[dev]) {
+        CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
+        attr_set[dev] = true;
+    }
+    const int rb = kTileWaves * ROWS;
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B, O,
+                       tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+template <int T, int KT>
+csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp, const int32_t *ci,
+                         const float *v, const float *B, float *O) {
+    switch (tile_rows_for(d, M)) {
+        case 4: return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O);
+        case 2: return launch_ktile_rows<T, KT, 2>(d, st, M, K, N, rp, ci, v, B, O);
+        default: return launch_ktile_rows<T, KT, 1>(d, st, M, K, N, rp, ci, v, B, O);
+    }
+}
+
+template <int T, int KT, int ROWS, int SL>
+csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                                    const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                                    float *O) {
+    using L = FusedTileLds<T, KT, ROWS, SL>;
+    static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
+    static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
+    // how much of the next tile is prefetched into registers: all of it for one 256-wide piece of output; for
+    // two, the 3 of a thread's 8 loads that still fit in 128 registers beside the accumulators
     constexpr int kPer = KT * T * 64 / kTileThreads;
-    constexpr int kPrefetch = (FUSED && T == 2) ? 3 : kPer;
-    auto kern = ktile_kernel<T, KT, ROWS, FUSED, kPrefetch>;
+    constexpr int kPrefetch = T == 2 ? 3 : kPer;
+    auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -390,14 +422,14 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     return CSRK_OK;
 }
 
-template <int T, int KT, bool FUSED>
-csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                         const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                         float *O) {
+template <int T, int KT, int SL>
+csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                               const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                               float *O) {
     switch (tile_rows_for(d, M)) {
-        case 4: return launch_ktile_rows<T, KT, 4, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 2: return launch_ktile_rows<T, KT, 2, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        default: return launch_ktile_rows<T, KT, 1, FUSED>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 4: return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 2: return launch_fused_ktile_rows<T, KT, 2, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        default: return launch_fused_ktile_rows<T, KT, 1, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
     }
 }
 
@@ -458,8 +490,8 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
         gate = tile_flags(*d);
         rec.begin();
-        csrk_status s = N <= 256 ? launch_ktile<1, 128, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O)
-                                 : launch_ktile<2, 64, false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
+        csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
+                                 : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
         if (s) return s;
     }
     rec.begin();
@@ -549,8 +581,8 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
         gate = tile_flags(*d);
         rec.begin();
-        csrk_status s = N <= 256 ? launch_ktile<1, 96, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
-                                 : launch_ktile<2, 56, true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+        csrk_status s = N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
+                                 : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     }
     rec.begin();

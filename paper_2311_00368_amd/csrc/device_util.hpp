@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace csrk {
 
 constexpr int kWave = 64;
@@ -36,6 +38,27 @@ __device__ __forceinline__ float group_sum(float v) {
     if (LG >= 32) v += __shfl_xor(v, 16);
     if (LG >= 64) v += __shfl_xor(v, 32);
     return v;
+}
+
+// f(std::integral_constant<int, i>) for i = I0 .. I1-1, unrolled at compile time.
+template <int I0, int I1, typename F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
+// acc += a' * b, where a' is the value of `a` in the lane that the rotation row_ror:S of a row of 16 lanes
+// pairs with this one.  Written as the one DPP multiply-add it is meant to be: left to the compiler, the
+// rotated values (loop invariants) are hoisted out of the loop as hundreds of extra live registers.
+template <int S>
+__device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
+    if constexpr (S == 0) {
+        acc = fmaf(a, b, acc);
+    } else {
+        asm("v_fmac_f32_dpp %0, %1, %2 row_ror:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(a), "v"(b), "n"(S));
+    }
 }
 
 // VEC consecutive floats; VEC == 4 is one 128-bit access (address must be 16-byte aligned).

@@ -40,12 +40,8 @@
 // (never out of bounds: the cursors only move inside the row and LDS reads cannot fault)
 // and the general kernels, which are launched right behind it, redo the whole call.
 //
-// FusedMM adds a dot stage per segment: 16 entries at a time, 4 lanes x 16 floats over
-// D <= 64; the tile's rows of the first dense operand B (padded to 68 floats) and the
-// block's rows of A are staged in LDS too; two quad-permute DPP adds reduce; the
-// finished score (times the stored value) overwrites the value half of the entry's
-// pair in the LDS slot, from where the accumulate stage broadcasts it.  Scores never
-// leave the CU (Algorithm 3's `arow`).
+// The FusedMM version of this kernel (same accumulate stage plus a score stage) is in
+// kernels_ktile_fused.hpp.
 #pragma once
 #include <type_traits>
 
@@ -97,42 +93,32 @@ __device__ __forceinline__ unsigned long long descending_lanes(int k) {
     return __ballot(prev > k);
 }
 
-template <int T, int KT, int ROWS, bool FUSED>
+template <int T, int KT>
 struct KTileLds {
     static constexpr int kRowFloats = T * 256;
     static constexpr int kCFloats = KT * kRowFloats;
-    static constexpr int kDStride = 68;     // FUSED: floats per staged row of B (64 + 4 so row starts spread over banks)
-    static constexpr int kDFloats = FUSED ? KT * kDStride : 0;
-    static constexpr int kAFloats = FUSED ? kTileWaves * ROWS * 64 : 0;   // FUSED: the block's rows of A
-    // (column, value) pairs: SPMM keeps two 64-entry slots per wavefront so that the next
-    // row's chunk is written while the current row is consumed; FusedMM has one
-    static constexpr int kSlots = FUSED ? 1 : 2;
-    static constexpr int kEntFloats = kTileWaves * kSlots * kWave * 2;
-    static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
+    // (column, value) pairs: two 64-entry slots per wavefront, so that the next row's chunk is
+    // written while the current row is consumed
+    static constexpr int kEntFloats = kTileWaves * 2 * kWave * 2;
+    static constexpr int kBytes = (kCFloats + kEntFloats) * 4;
 };
 
-// PF: how many of a thread's kPer loads of the next C tile are issued one tile ahead (0 = none, kPer = all);
-// the rest are loaded at the start of their own tile, and so is FusedMM's B tile unless PF = kPer.
-template <int T, int KT, int ROWS, bool FUSED, int PF>
+// SPMM: O[row, :] = sum over the row's entries of value * B[column, :] (Algorithm 2), B called Cmat here.
+template <int T, int KT, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
-    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
-    using L = KTileLds<T, KT, ROWS, FUSED>;
+    int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    using L = KTileLds<T, KT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
     constexpr int kRowBytes = L::kRowFloats * 4;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;                        // KT x (T*256) floats
-    float *bt = lds + L::kCFloats;          // KT x 68 floats (FUSED)
-    float *at = bt + L::kDFloats;           // 16*ROWS x 64 floats (FUSED): rows of A of this block, zero-padded
-    int2 *ent = reinterpret_cast<int2 *>(at + L::kAFloats) + wave * (L::kSlots * kWave);
+    int2 *ent = reinterpret_cast<int2 *>(lds + L::kCFloats) + wave * (2 * kWave);
 
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
-    const int q16 = (lane & 3) * 16;        // FUSED: this lane's 16-float slice of the dot length
-    const int ei = lane >> 2;               // FUSED: which of 16 side-by-side entries
 
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
@@ -153,22 +139,12 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][t][v] = 0.f;
     }
-    if constexpr (FUSED) {
-        // the block's rows of A, padded with zeros to 64 columns and to whole rows
-        const int brow0 = blockIdx.x * (kTileWaves * ROWS);
-        for (int e = threadIdx.x; e < kTileWaves * ROWS * 64; e += kTileThreads) {
-            const int rr = e >> 6, cc = e & 63;
-            at[e] = (brow0 + rr < M && cc < D) ? A[(size_t)(brow0 + rr) * D + cc] : 0.f;
-        }
-    }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
     const int n4 = N >> 2;                  // float4s per dense row
     constexpr int kRow4 = T * 64;
     constexpr int kPer = KT * kRow4 / kTileThreads;
-    constexpr int kPerB = FUSED ? (KT * 16 + kTileThreads - 1) / kTileThreads : 1;
     float4 stage[kPer];
-    float4 stageb[kPerB];
     // Thread t copies float4 number (t % kRow4) of tile rows t / kRow4, + kStep, + 2 kStep, ...: its
     // offset inside a tile never changes, so a tile costs this thread kPer loads off a uniform
     // base pointer with no address arithmetic in vector registers.
@@ -177,79 +153,41 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const bool my_col = my_c4 < n4;
     const size_t my_off = (size_t)my_kk * n4 + my_c4;
     const size_t step_off = (size_t)kStep * n4;
-    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
-    // loads number [I0, I1) of this thread for the C tile that starts at column k0
-    auto issue = [&](int k0, auto i0c, auto i1c) {
-        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+    auto issue = [&](int k0) {
         const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
         if (k0 + KT <= K) {
 #pragma unroll
-            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int i = 0; i < kPer; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (my_col) {
 #pragma unroll
-                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
+                for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
             }
         } else {                                      // last, partial tile
 #pragma unroll
-            for (int i = I0; i < I1; ++i) {
+            for (int i = 0; i < kPer; ++i) {
                 stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
             }
         }
     };
-    auto issue_b = [&](int k0) {
-        if constexpr (FUSED) {
-            const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
-            const int d4 = D >> 2;
-#pragma unroll
-            for (int i = 0; i < kPerB; ++i) {
-                const int e = i * kTileThreads + threadIdx.x;
-                const int kk = e >> 4, c4 = e & 15;
-                stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < KT * 16 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
-            }
-        }
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using IPF = std::integral_constant<int, PF>;
-    using IEND = std::integral_constant<int, kPer>;
     auto commit = [&]() {
         float4 *dst = reinterpret_cast<float4 *>(ct);
 #pragma unroll
         for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
-        if constexpr (FUSED) {
-            float4 *dstb = reinterpret_cast<float4 *>(bt);
-#pragma unroll
-            for (int i = 0; i < kPerB; ++i) {
-                const int e = i * kTileThreads + threadIdx.x;
-                if (e < KT * 16) dstb[(e >> 4) * (L::kDStride / 4) + (e & 15)] = stageb[i];
-            }
-        }
     };
 
-    constexpr bool kAllAhead = PF == kPer;      // then FusedMM's B tile is prefetched as well
-    if constexpr (PF > 0) issue(0, I0{}, IPF{});
-    if constexpr (kAllAhead) issue_b(0);
+    issue(0);
     for (int k0 = 0; k0 < K; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
-        if constexpr (!kAllAhead) {
-            issue(k0, IPF{}, IEND{});
-            issue_b(k0);
-        }
         commit();
         __syncthreads();
-        if constexpr (PF > 0) {
-            if (k0 + KT < K) {                  // lands while this tile is being worked on
-                issue(k0 + KT, I0{}, IPF{});
-                if constexpr (kAllAhead) issue_b(k0 + KT);
-            }
-        }
+        if (k0 + KT < K) issue(k0 + KT);    // lands while this tile is being worked on
         const int kend = k0 + KT;
         // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
         // large column numbers wrap instead of overflowing (the sum below is always a small offset)
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
         int cnts[ROWS];
-        if constexpr (!FUSED) ent[lane] = make_int2(kc[0], __builtin_bit_cast(int, vc[0]));
+        ent[lane] = make_int2(kc[0], __builtin_bit_cast(int, vc[0]));
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             // entries of this tile = leading lanes of the chunk with column < kend
@@ -258,47 +196,21 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             // order check on the chunk, here where it is first used (not where it was requested,
             // which would make the request a wait)
             bad |= descending_lanes(kc[r]);
-            int2 *e;
-            if constexpr (FUSED) {
-                e = ent;
-                if (cnt > 0) {
-                    e[lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
-                    // dot stage: 16 entries per round; lane (ei, q) = (lane / 4, lane % 4) takes
-                    // columns 16q..16q+15 of entry t+ei, so a quad of lanes covers the dot length
-                    // and two quad-permute DPP adds finish it
-                    float av[4][4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) load_vec<4>(at + (wave * ROWS + r) * 64 + q16 + 4 * i, av[i]);
-                    for (int t = 0; t < cnt; t += 16) {
-                        const int idx = t + ei;
-                        const bool on = idx < cnt;
-                        const int2 kv = e[on ? idx : 0];
-                        const float *brow = bt + (kv.x - k0) * L::kDStride + q16;
-                        float b[4][4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) load_vec<4>(brow + 4 * i, b[i]);
-                        float part = 0.f;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) part = fmaf(av[i][v], b[i][v], part);
-                        part = group_sum<4>(part);
-                        if (on && (lane & 3) == 0)
-                            reinterpret_cast<int *>(e)[2 * idx + 1] =
-                                __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
-                    }
-                }
-            } else {
-                if (r + 1 < ROWS)
-                    ent[((r + 1) & 1) * kWave + lane] = make_int2(kc[r + 1], __builtin_bit_cast(int, vc[r + 1]));
-                e = ent + (r & 1) * kWave;
-            }
+            if (r + 1 < ROWS)
+                ent[((r + 1) & 1) * kWave + lane] = make_int2(kc[r + 1], __builtin_bit_cast(int, vc[r + 1]));
+            const int2 *e = ent + (r & 1) * kWave;
             auto batch = [&](int t, auto count) {
                 constexpr int CNT = decltype(count)::value;
                 float c[CNT][T][4];
                 int2 ks[CNT];
+                // same address in all lanes (an LDS broadcast), two pairs per 128-bit read; t is a multiple of 4
 #pragma unroll
-                for (int u = 0; u < CNT; ++u) ks[u] = e[t + u];    // same address in all lanes: broadcast
+                for (int u = 0; u + 1 < CNT; u += 2) {
+                    const int4 two = *reinterpret_cast<const int4 *>(e + t + u);
+                    ks[u] = make_int2(two.x, two.y);
+                    ks[u + 1] = make_int2(two.z, two.w);
+                }
+                if constexpr (CNT % 2 == 1) ks[CNT - 1] = e[t + CNT - 1];
 #pragma unroll
                 for (int u = 0; u < CNT; ++u) {
                     const char *crow = reinterpret_cast<const char *>(ct) + ((unsigned)ks[u].x * (unsigned)kRowBytes + lb);
@@ -333,20 +245,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                     if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
                     lastk = k;
                     if (k >= kend) break;
-                    float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
-                    if constexpr (FUSED) {
-                        float part = 0.f;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            float av[4], b[4];
-                            load_vec<4>(at + (wave * ROWS + r) * 64 + q16 + 4 * i, av);
-                            load_vec<4>(bt + (k - k0) * L::kDStride + q16 + 4 * i, b);
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) part = fmaf(av[v], b[v], part);
-                        }
-                        part = group_sum<4>(part);
-                        s *= readlane_f(part, 0);
-                    }
+                    const float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
                     const float *crow = ct + (k - k0) * L::kRowFloats + n;
 #pragma unroll
                     for (int tt = 0; tt < T; ++tt) {
@@ -408,26 +307,6 @@ struct SddmmTileLds {
     static constexpr int kKT = 147456 / (DMAX * 4);             // tile height: 144 KB of rows of B
     static constexpr int kBytes = kKT * DMAX * 4;
 };
-
-template <int I0, int I1, typename F>
-__device__ __forceinline__ void static_for(F &&f) {
-    if constexpr (I0 < I1) {
-        f(std::integral_constant<int, I0>{});
-        static_for<I0 + 1, I1>(f);
-    }
-}
-
-// acc += a' * b, where a' is the value of `a` in the lane that the rotation row_ror:S of a row of 16 lanes
-// pairs with this one.  Written as the one DPP multiply-add it is meant to be: left to the compiler, the
-// rotated values (loop invariants) are hoisted out of the loop as hundreds of extra live registers.
-template <int S>
-__device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
-    if constexpr (S == 0) {
-        acc = fmaf(a, b, acc);
-    } else {
-        asm("v_fmac_f32_dpp %0, %1, %2 row_ror:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(a), "v"(b), "n"(S));
-    }
-}
 
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(

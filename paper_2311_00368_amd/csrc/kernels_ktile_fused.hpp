@@ -1,0 +1,320 @@
+// LDS-tiled FusedMM for wide outputs (128 < N <= 512, D <= 64): O = (S .* (A B^T)) C with the
+// scores kept on the CU (Algorithm 3's `arow`).
+//
+// The accumulate stage is the SPMM tile kernel's: a workgroup of 16 wavefronts owns 16*ROWS rows
+// of S, sweeps K in tiles of KT columns of C staged in LDS, and every wavefront adds, for each of
+// its rows, score * C[k, :] for the entries of the tile (lane l holds columns 4l..4l+3 of each
+// 256-wide piece of the output; entries in batches of 4 fetched as (column, score) pairs by LDS
+// broadcast reads).
+//
+// The score stage runs ONCE per tile for all rows of the wavefront, with lanes as ENTRIES: the
+// 64 lanes are 4 groups of 16; a group belongs to one row (ROWS = 4: group g is row g; fewer rows:
+// several groups per row) and its lane i scores the row's entry number base + i of the tile,
+// walking the dot length in 16 pieces of 4 floats.  The tile's rows of B sit in LDS (64 floats
+// each, zero beyond D); the row of A is spread over the group, piece i in lane i, and lane i walks
+// its row of B in rotated order - piece (i - s) mod 16 at step s - taking the matching piece of A
+// through the row_ror:s rotation of the multiply-add's DPP operand.  The 16 lanes the LDS serves
+// together therefore read 16 different pieces (all banks once) whatever rows of B they are in, no
+// cross-lane reduction is needed, and one chain of 16 reads scores up to 64 entries.  The finished
+// score times the stored value overwrites the value half of the entry's pair in the wavefront's
+// LDS slot, where the accumulate stage finds it.
+#pragma once
+#include "kernels_ktile.hpp"
+
+namespace csrk {
+
+// SL: entries per row that the wavefront's LDS slot holds (32 or 64); a row with more entries than that in
+// one tile finishes them one at a time.
+template <int T, int KT, int ROWS, int SL>
+struct FusedTileLds {
+    static constexpr int kRowFloats = T * 256;
+    static constexpr int kCFloats = KT * kRowFloats;            // tile of C
+    static constexpr int kBFloats = KT * 64;                    // tile of B, rows zero-padded to 64 floats
+    static constexpr int kEntFloats = kTileWaves * ROWS * SL * 2;      // one slot of SL (column, value) pairs per row
+    static constexpr int kBytes = (kCFloats + kBFloats + kEntFloats) * 4;
+};
+
+// PF: how many of a thread's kPer loads of the next C tile are issued one tile ahead; the rest and the
+// B tile are loaded at the start of their own tile (all of it ahead, B included, when PF == kPer).
+template <int T, int KT, int ROWS, int SL, int PF>
+__global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
+    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    using L = FusedTileLds<T, KT, ROWS, SL>;
+    static_assert(SL == 32 || SL == 64, "slot sizes");
+    static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if (!ktile_ok(flags)) return;
+    constexpr int kRowBytes = L::kRowFloats * 4;
+    constexpr int kGroupsPerRow = 4 / ROWS;
+    constexpr int kPass = 16 * kGroupsPerRow;      // entries of a row scored per pass
+    const int lane = lane_id();
+    const int wave = uniform(threadIdx.x >> 6);
+    float *ct = lds;
+    float *bt = lds + L::kCFloats;
+    int2 *ent = reinterpret_cast<int2 *>(bt + L::kBFloats) + wave * (ROWS * SL);
+
+    // The rotated walk below is written for row_ror:s handing lane i the value of lane i - s.  Measure it;
+    // should it ever turn the other way, stand down and let the general kernel behind this one do the call.
+    const int i16 = lane & 15;
+    if (((__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15) != 15) {
+        if (threadIdx.x == 0) flags[0] = 1;
+        return;
+    }
+
+    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const int n = lane * 4;                 // this lane's first column inside each 256-wide piece of the output
+    const int my_r = (lane >> 4) / kGroupsPerRow;       // the row this lane's group scores entries of
+    const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
+
+    int pos[ROWS], end[ROWS];
+    int kc[ROWS];
+    float vc[ROWS];
+    float acc[ROWS][T][4];
+    unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = row0 + r;
+        pos[r] = row < M ? uniform(rowptr[row]) : 0;
+        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        const int j = pos[r] + lane;
+        const bool ok = j < end[r];
+        kc[r] = ok ? colidx[j] : 0x7fffffff;
+        vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[r][t][v] = 0.f;
+    }
+    float a[4] = {0.f, 0.f, 0.f, 0.f};      // piece i16 of this group's row of A, zero beyond D
+    if (row0 + my_r < M && i16 * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + i16 * 4, a);
+
+    // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
+    const int n4 = N >> 2;                  // float4s per row of C
+    constexpr int kRow4 = T * 64;
+    constexpr int kPer = KT * kRow4 / kTileThreads;
+    constexpr int kPerB = (KT * 16 + kTileThreads - 1) / kTileThreads;
+    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
+    float4 stage[kPer];
+    float4 stageb[kPerB];
+    constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
+    const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
+    const bool my_col = my_c4 < n4;
+    const size_t my_off = (size_t)my_kk * n4 + my_c4;
+    const size_t step_off = (size_t)kStep * n4;
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        if (k0 + KT <= K) {
+#pragma unroll
+            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (my_col) {
+#pragma unroll
+                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
+            }
+        } else {                                      // last, partial tile
+#pragma unroll
+            for (int i = I0; i < I1; ++i) {
+                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+            }
+        }
+    };
+    auto issue_b = [&](int k0) {
+        const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
+        const int d4 = D >> 2;
+#pragma unroll
+        for (int i = 0; i < kPerB; ++i) {
+            const int e = i * kTileThreads + threadIdx.x;
+            const int kk = e >> 4, c4 = e & 15;
+            stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < KT * 16 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
+        }
+    };
+    auto commit = [&]() {
+        float4 *dst = reinterpret_cast<float4 *>(ct);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        float4 *dstb = reinterpret_cast<float4 *>(bt);
+#pragma unroll
+        for (int i = 0; i < kPerB; ++i) {
+            const int e = i * kTileThreads + threadIdx.x;
+            if (e < KT * 16) dstb[e] = stageb[i];
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using IPF = std::integral_constant<int, PF>;
+    using IEND = std::integral_constant<int, kPer>;
+    constexpr bool kAllAhead = PF == kPer;
+
+    if constexpr (PF > 0) issue(0, I0{}, IPF{});
+    if constexpr (kAllAhead) issue_b(0);
+    for (int k0 = 0; k0 < K; k0 += KT) {
+        __syncthreads();                    // previous tile fully consumed
+        if constexpr (!kAllAhead) {
+            issue(k0, IPF{}, IEND{});
+            issue_b(k0);
+        }
+        commit();
+        __syncthreads();
+        if constexpr (PF > 0) {
+            if (k0 + KT < K) {                  // lands while this tile is being worked on
+                issue(k0 + KT, I0{}, IPF{});
+                if constexpr (kAllAhead) issue_b(k0 + KT);
+            }
+        }
+        const int kend = k0 + KT;
+        // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
+        // large column numbers wrap instead of overflowing (the sum below is always a small offset)
+        const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
+
+        // entries of this tile = leading lanes of each row's chunk with column < kend; park the chunks
+        int cnts[ROWS];
+        int maxcnt = 0, my_cnt = 0;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
+            cnt = cnt < SL ? cnt : SL;          // what the slot holds; a row that fills it continues below
+            cnts[r] = cnt;
+            maxcnt = cnt > maxcnt ? cnt : maxcnt;
+            if (my_r == r) my_cnt = cnt;
+            // order check on the chunk, here where it is first used
+            bad |= descending_lanes(kc[r]);
+            if (SL == kWave || lane < SL) ent[r * SL + lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+        }
+
+        for (int base = 0; base < maxcnt; base += kPass) {
+            // ---- score stage: this lane's entry of this pass
+            {
+                const int idx = base + my_first;
+                const bool on = idx < my_cnt;
+                int2 *mine = ent + my_r * SL + (on ? idx : 0);
+                const int2 kv = *mine;
+                // byte address of piece i16 of the entry's row of B; lanes without an entry walk row 0 of the tile
+                const unsigned row_b = (unsigned)(L::kCFloats * 4) + (on ? (unsigned)(kv.x - k0) * 256u : 0u) + i16 * 16;
+                const char *base_a = reinterpret_cast<const char *>(lds) + row_b;
+                const char *base_b = base_a - 256;
+                float dot = 0.f;
+                constexpr int GL = 4, NG = 16 / GL;
+                float b[2][GL][4];
+                auto read_group = [&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    static_for<0, GL>([&](auto uc) {
+                        constexpr int s = g * GL + decltype(uc)::value;
+                        // piece (i16 - s) mod 16: 16 * (16 - s) bytes past base_b for lanes i16 >= s, past base_a otherwise
+                        const char *p = s == 0 ? base_a : ((i16 >= s ? base_b : base_a) + 16 * (16 - s));
+                        load_vec<4>(reinterpret_cast<const float *>(p), b[g & 1][decltype(uc)::value]);
+                    });
+                };
+                read_group(std::integral_constant<int, 0>{});
+                static_for<0, NG>([&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    if constexpr (g + 1 < NG) read_group(std::integral_constant<int, g + 1>{});
+                    static_for<0, GL>([&](auto uc) {
+                        constexpr int u = decltype(uc)::value;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) fma_row_rotated<g * GL + u>(dot, a[c], b[g & 1][u][c]);
+                    });
+                });
+                if (on) reinterpret_cast<int *>(mine)[1] = __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * dot);
+            }
+            // ---- accumulate stage: entries [base, base + kPass) of every row
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int2 *e = ent + r * SL;
+                const int lim = cnts[r] < base + kPass ? cnts[r] : base + kPass;
+                auto batch = [&](int t, auto count) {
+                    constexpr int CNT = decltype(count)::value;
+                    float c[CNT][T][4];
+                    int2 ks[CNT];
+                    // same address in all lanes (an LDS broadcast), two pairs per 128-bit read; t is a multiple of 4
+#pragma unroll
+                    for (int u = 0; u + 1 < CNT; u += 2) {
+                        const int4 two = *reinterpret_cast<const int4 *>(e + t + u);
+                        ks[u] = make_int2(two.x, two.y);
+                        ks[u + 1] = make_int2(two.z, two.w);
+                    }
+                    if constexpr (CNT % 2 == 1) ks[CNT - 1] = e[t + CNT - 1];
+#pragma unroll
+                    for (int u = 0; u < CNT; ++u) {
+                        const char *crow = reinterpret_cast<const char *>(ct) + ((unsigned)ks[u].x * (unsigned)kRowBytes + lb);
+#pragma unroll
+                        for (int tt = 0; tt < T; ++tt)
+                            load_vec<4>(reinterpret_cast<const float *>(crow + tt * 1024), c[u][tt]);
+                    }
+#pragma unroll
+                    for (int u = 0; u < CNT; ++u) {
+                        const float sv = __builtin_bit_cast(float, ks[u].y);
+#pragma unroll
+                        for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(sv, c[u][tt][v], acc[r][tt][v]);
+                    }
+                };
+                int t = base;
+                for (; t + 4 <= lim; t += 4) batch(t, std::integral_constant<int, 4>{});
+                switch (lim - t) {
+                    case 3: batch(t, std::integral_constant<int, 3>{}); break;
+                    case 2: batch(t, std::integral_constant<int, 2>{}); break;
+                    case 1: batch(t, std::integral_constant<int, 1>{}); break;
+                    default: break;
+                }
+            }
+        }
+
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            pos[r] += cnts[r];
+            if (cnts[r] == SL) {
+                // rare (a row with SL or more entries inside one tile): finish the tile's entries of this row
+                // one at a time straight from memory; the 16 lanes of the row's first group hold the row of A
+                int lastk = __builtin_amdgcn_readlane(kc[r], SL - 1);
+                while (pos[r] < end[r]) {
+                    const int k = uniform(colidx[pos[r]]);
+                    if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
+                    lastk = k;
+                    if (k >= kend) break;
+                    float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
+                    float bq[4];
+                    load_vec<4>(bt + (k - k0) * 64 + i16 * 4, bq);
+                    float part = a[0] * bq[0];
+#pragma unroll
+                    for (int v = 1; v < 4; ++v) part = fmaf(a[v], bq[v], part);
+                    part = group_sum<16>(part);
+                    s *= readlane_f(part, r * kGroupsPerRow * 16);
+                    const float *crow = ct + (k - k0) * L::kRowFloats + n;
+#pragma unroll
+                    for (int tt = 0; tt < T; ++tt) {
+                        float c[4];
+                        load_vec<4>(crow + tt * 256, c);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
+                    }
+                    ++pos[r];
+                }
+            }
+        }
+        // look-ahead chunks for the next tile, all requested here, after the arithmetic
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (cnts[r] > 0) {
+                const bool okn = lane < end[r] - pos[r];
+                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
+                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+            }
+        }
+    }
+    if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = row0 + r;
+        if (row < M) {
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+                if (n + tt * 256 < N) store_vec<4>(O + (size_t)row * N + n + tt * 256, acc[r][tt]);
+        }
+    }
+}
+
+}  // namespace csrk

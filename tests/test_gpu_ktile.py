@@ -44,7 +44,7 @@ def test_spmm_ktile(csrk, M, K, N, p):
                                      (2048, 2048, 64, 512), (130, 70, 60, 500), (70, 300, 16, 64),
                                      (300, 700, 128, 128), (257, 129, 100, 32), (1100, 900, 96, 64), (90, 2000, 128, 4),
                                      (500, 500, 32, 32), (64, 640, 68, 100)])
-@pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
+@pytest.mark.parametrize("p", [0.05, 0.3, 0.7, 1.0])   # 0.7: rows overflow the wide kernel's 32-entry slots, not the chunk
 def test_fusedmm_ktile(csrk, M, K, D, N, p):
     rng = np.random.default_rng(M + K + N + D)
     rp, ci = inputs.bernoulli_csr(N + D, M, K, p)
