@@ -403,10 +403,10 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
-    // how much of the next tile is prefetched into registers: all of it for one 256-wide piece of output; for
-    // two, the 3 of a thread's 8 loads that still fit in 128 registers beside the accumulators
+    // how much of the next tile is prefetched into registers: as many of a thread's loads as still fit in 128
+    // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 3 of 8 for two)
     constexpr int kPer = KT * T * 64 / kTileThreads;
-    constexpr int kPrefetch = T == 2 ? 3 : kPer;
+    constexpr int kPrefetch = T == 2 ? 3 : kPer - 1;
     auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
@@ -531,8 +531,9 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(*d, M, D))) return s;
         gate = tile_flags(*d);
         rec.begin();
-        csrk_status s = D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
-                                : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
+        csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
+                        : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
+                                  : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
         if (s) return s;
     }
     rec.begin();

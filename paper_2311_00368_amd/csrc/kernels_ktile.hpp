@@ -229,12 +229,13 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             };
             int t = 0;
             for (; t + 4 <= cnt; t += 4) batch(t, std::integral_constant<int, 4>{});
-            switch (cnt - t) {
-                case 3: batch(t, std::integral_constant<int, 3>{}); break;
-                case 2: batch(t, std::integral_constant<int, 2>{}); break;
-                case 1: batch(t, std::integral_constant<int, 1>{}); break;
-                default: break;
+            // the last 1-3 entries as a pair and a single: two plain ifs keep the accumulators in place, where a
+            // switch over the three cases made the compiler copy them in and out
+            if (cnt - t >= 2) {
+                batch(t, std::integral_constant<int, 2>{});
+                t += 2;
             }
+            if (cnt - t >= 1) batch(t, std::integral_constant<int, 1>{});
             pos[r] += cnt;
             if (cnt == kWave) {
                 // rare (a row with 64 or more entries inside one tile): finish the tile's

@@ -254,12 +254,13 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 };
                 int t = base;
                 for (; t + 4 <= lim; t += 4) batch(t, std::integral_constant<int, 4>{});
-                switch (lim - t) {
-                    case 3: batch(t, std::integral_constant<int, 3>{}); break;
-                    case 2: batch(t, std::integral_constant<int, 2>{}); break;
-                    case 1: batch(t, std::integral_constant<int, 1>{}); break;
-                    default: break;
+                // the last 1-3 entries as a pair and a single: two plain ifs keep the accumulators in place, where a
+                // switch over the three cases made the compiler copy them in and out
+                if (lim - t >= 2) {
+                    batch(t, std::integral_constant<int, 2>{});
+                    t += 2;
                 }
+                if (lim - t >= 1) batch(t, std::integral_constant<int, 1>{});
             }
         }
 
