@@ -143,3 +143,34 @@ def test_one_descending_pair_anywhere_is_noticed(csrk, swap_at):
     run_spmm(csrk, M, K, N, rp, ci, v, C)
     run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
     run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+
+
+@pytest.mark.parametrize("N,D", [(512, 64), (256, 64), (128, 128), (32, 32)])
+def test_nonfinite_values_in_unreferenced_rows_do_not_leak_ktile(csrk, N, D):
+    """Rows of the dense right-hand operands that no stored entry references may hold NaN / Inf: the
+    tiled kernels stage them in LDS with the rest of the tile (and idle lanes of the score stages walk
+    tile rows they have no entry for), but nothing of them may reach an output (only stored entries
+    contribute: eq. (1)-(3))."""
+    rng = np.random.default_rng(N + D)
+    M, K = 200, 300
+    poisoned = [0, 1, 63, 64, 150, 299]            # first row of a tile, tile edges, last row
+    rows = [sorted(c for c in rng.permutation(K)[: int(rng.integers(0, 120))] if c not in poisoned) for _ in range(M)]
+    rp, ci = helpers.csr_from_rows(rows, K)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    B[poisoned, :] = np.nan
+    C[poisoned, :] = np.inf
+    O = csrk.spmm_csr(M, K, N, dev(rp), dev(ci), dev(v), dev(C)).cpu().numpy()
+    assert np.all(np.isfinite(O))
+    P = csrk.sddmm_csr(M, K, D, dev(rp), dev(ci), dev(v), dev(A), dev(B)).cpu().numpy()
+    assert np.all(np.isfinite(P))
+    O = csrk.fusedmm_csr(M, K, D, N, dev(rp), dev(ci), dev(v), dev(A), dev(B), dev(C)).cpu().numpy()
+    assert np.all(np.isfinite(O))
+    # and with clean operands the same calls agree with the oracle
+    B[poisoned, :] = 0.5
+    C[poisoned, :] = -0.25
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
