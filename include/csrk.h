@@ -31,11 +31,13 @@
  *  - O must not overlap any input.  P may be the same array as vals (the
  *    paper's SDDMM overwrites the values of the sparse matrix in place).
  *  - SPMM and FusedMM use a per-device scratch area owned by the library for
- *    partial rows; it is allocated (hipMalloc, which synchronises) the first time
- *    it is needed or has to grow, and kept until csrk_release_workspace or process
- *    exit.  Two calls in flight at once on different streams of one device would
- *    share it and race: serialise such calls on one stream.  Results do not
- *    depend on timing: partial rows are combined in a fixed order.
+ *    partial rows (8192 x N floats on an MI355X) or, when M is small and the
+ *    reduction dimension is cut into up to 8 ranges, for partial outputs (at most
+ *    8 x M x N floats); it is allocated (hipMalloc, which synchronises) the first
+ *    time it is needed or has to grow, and kept until csrk_release_workspace or
+ *    process exit.  Two calls in flight at once on different streams of one device
+ *    would share it and race: serialise such calls on one stream.  Results do not
+ *    depend on timing: partial rows and partial outputs are added in a fixed order.
  *  - Return value: CSRK_OK or an error code; csrk_last_error() then gives a
  *    message for the calling thread.  On error nothing has been enqueued.
  *  - Any N >= 1 and D >= 1 work.  Widths that are multiples of 4 with 16-byte

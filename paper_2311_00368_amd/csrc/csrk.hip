@@ -38,6 +38,7 @@ csrk_status fail(csrk_status code, const char *fmt, ...) {
     } while (0)
 
 constexpr int kMaxDevices = 64;
+constexpr int kMaxKSplit = 8;
 
 struct DeviceState {
     bool init = false;
@@ -46,6 +47,7 @@ struct DeviceState {
     float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way
     int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
     size_t head_floats = 0;
+
 };
 
 DeviceState g_dev[kMaxDevices];
@@ -106,9 +108,11 @@ csrk_status device_state(DeviceState **out) {
     return CSRK_OK;
 }
 
-// scratch for `width` columns of partial rows; grows, never shrinks
-csrk_status ensure_scratch(DeviceState &d, int width) {
-    const size_t need = (size_t)d.workers * (size_t)width;
+// scratch for `width` columns of partial rows of the equal-nonzero split, or `min_floats` floats if that is
+// more (partial outputs of a K-split launch); grows, never shrinks
+csrk_status ensure_scratch(DeviceState &d, int width, size_t min_floats = 0) {
+    size_t need = (size_t)d.workers * (size_t)width;
+    if (min_floats > need) need = min_floats;
     if (!d.head_row) {
         if (hipMalloc((void **)&d.head_row, sizeof(int32_t) * ((size_t)d.workers + 16)) != hipSuccess) {
             d.head_row = nullptr;
@@ -225,6 +229,21 @@ int tile_rows_for(const DeviceState &d, int M) {
     const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
     return blocks1 >= 4ll * d.cus ? 4 : blocks1 >= 2ll * d.cus ? 2 : 1;
 }
+// K-split (the small-M regime): when even one row per wavefront would leave CUs without a workgroup of the
+// tiled kernels, keep 4 rows per wavefront and cut K into S ranges instead, one workgroup per (row block,
+// range) - the counterpart, for the reduction dimension, of the paper's NT work-items per row (section
+// "SDDMM", the NT heuristic).  Returns S (1 = no split).  Every range keeps at least four tiles (with fewer the
+// split measured slower than one row per wavefront over the whole of K).
+int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block) {
+    if (env_int("CSRK_KSPLIT", 1) == 2) return 1;                  // 2 = off (tests and measurements)
+    const long long blocks = ((long long)M + rows_per_block - 1) / rows_per_block;
+    if (blocks >= d.cus) return 1;
+    long long s = (d.cus + blocks - 1) / blocks;
+    const long long tiles = ((long long)K + tile_height - 1) / tile_height;
+    if (s > tiles / 4) s = tiles / 4;
+    if (s > kMaxKSplit) s = kMaxKSplit;
+    return s < 2 ? 1 : (int)s;
+}
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
 constexpr float kNarrowMinDensity = 0.18f;    // narrow-output tiled kernels (measured cross-over with the general path)
 
@@ -248,9 +267,12 @@ bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     if (mode == 3) return false;
     if (N % 4 != 0 || N > 512 || N <= 128) return mode == 2 && N % 4 == 0 && N <= 512;
     if (mode == 2) return true;
-    // enough row blocks to occupy the CUs, and a dense operand too big to live in one XCD's L2
-    const long long min_dense_bytes = (long long)env_int("CSRK_KTILE_MIN_MB", 8) << 20;
-    return (long long)M >= (long long)d.cus * kTileWaves / 2 && (long long)K * N * 4 >= min_dense_bytes;
+    // Measured cross-over with the general path (whose gathers run at L2 speed while the dense operand fits an
+    // XCD's L2 and collapse beyond): a dense operand of 4 MB or more with at least 1024 rows, or 2 MB with 4096.
+    // Small M is handled by cutting K into ranges (ksplit_for).  CSRK_KTILE_MIN_MB overrides the 4 (tests).
+    const long long dense_bytes = (long long)K * N * 4;
+    const long long min_bytes = (long long)env_int("CSRK_KTILE_MIN_MB", 4) << 20;
+    return (M >= 1024 && dense_bytes >= min_bytes) || (M >= 4096 && dense_bytes >= min_bytes / 2);
 }
 
 bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
@@ -259,6 +281,24 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     if (mode == 2) return true;
     (void)K;
     return (long long)M >= 12ll * d.cus;
+}
+
+// the full column-order check that K-split launches need (see order_check_kernel); after launch_analysis
+csrk_status launch_order_check(DeviceState &d, hipStream_t st, int M, const int32_t *rp, const int32_t *ci) {
+    hipLaunchKernelGGL(order_check_kernel, dim3(d.cus * 8), dim3(256), 0, st, M, rp, ci, tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+// second half of a K-split SPMM / FusedMM call: O = sum of the `ksplit` partial outputs in the scratch
+csrk_status launch_ksplit_reduce(DeviceState &d, hipStream_t st, int M, int N, int ksplit, float *O) {
+    const size_t count4 = (size_t)M * (size_t)N / 4;     // tiled kernels run only with N % 4 == 0
+    size_t blocks = (count4 + 255) / 256;
+    if (blocks > (size_t)d.cus * 8) blocks = (size_t)d.cus * 8;
+    hipLaunchKernelGGL(ksplit_reduce_kernel, dim3((unsigned)(blocks > 0 ? blocks : 1)), dim3(256), 0, st, count4, ksplit,
+                       reinterpret_cast<const float4 *>(d.head), reinterpret_cast<float4 *>(O), tile_flags(d));
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
 }
 
 template <int DMAX, int ROWS>
@@ -284,6 +324,8 @@ csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int
 template <int DMAX>
 csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
                                     const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
+    // (cutting K into ranges for small M, as SPMM and FusedMM do, measured no gain here: the tile is 288-1152
+    // rows high, so a K of a few thousand leaves too few tiles per range)
     // rows per wavefront: as many as still leave every CU a workgroup
     const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
     // (the 128-wide kernel keeps two rows of A per lane in registers: four would spill)
@@ -315,7 +357,7 @@ bool narrow_shape_ok(const DeviceState &d, int M, int N, bool fused) {
 template <int G, int ROWS, bool FUSED, int DMAX>
 csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                               float *O) {
+                               float *O, int ksplit = 1) {
     // 128-row tiles, except where FusedMM's staging of 128-long rows of A and B would not leave room
     constexpr int KT = (FUSED && DMAX == 128 && G == 2) ? 96 : 128;
     using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
@@ -329,9 +371,10 @@ csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v, A, B,
-                       C, O, tile_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
+                       A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
+    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
     return CSRK_OK;
 }
 
@@ -339,6 +382,15 @@ template <int G, bool FUSED, int DMAX>
 csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                             const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                             float *O) {
+    // small M: keep 4 rows per wavefront and cut K into ranges instead
+    constexpr int KT = (FUSED && DMAX == 128 && G == 2) ? 96 : 128;
+    // (not for outputs of 32 columns or fewer, G = 8: there the split never measured faster)
+    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, KT, kTileWaves * 4);
+    if (ksplit > 1) {
+        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
+        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
+        return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+    }
     // two workgroups share a CU, so aim for at least two per CU before giving a wavefront more rows
     const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
     if (blocks1 >= 8ll * d.cus)
@@ -367,7 +419,7 @@ csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int D, i
 
 template <int T, int KT, int ROWS>
 csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
-                              const int32_t *ci, const float *v, const float *B, float *O) {
+                              const int32_t *ci, const float *v, const float *B, float *O, int ksplit = 1) {
     using L = KTileLds<T, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
@@ -380,15 +432,22 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B, O,
-                       tile_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B,
+                       O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
+    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
     return CSRK_OK;
 }
 
 template <int T, int KT>
 csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp, const int32_t *ci,
                          const float *v, const float *B, float *O) {
+    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
+    if (ksplit > 1) {
+        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
+        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
+        return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O, ksplit);
+    }
     switch (tile_rows_for(d, M)) {
         case 4: return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O);
         case 2: return launch_ktile_rows<T, KT, 2>(d, st, M, K, N, rp, ci, v, B, O);
@@ -399,7 +458,7 @@ csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, co
 template <int T, int KT, int ROWS, int SL>
 csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                     const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                                    float *O) {
+                                    float *O, int ksplit = 1) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
@@ -416,9 +475,10 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v, A, B,
-                       C, O, tile_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
+                       A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
+    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
     return CSRK_OK;
 }
 
@@ -426,6 +486,12 @@ template <int T, int KT, int SL>
 csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                                float *O) {
+    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
+    if (ksplit > 1) {
+        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
+        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
+        return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+    }
     switch (tile_rows_for(d, M)) {
         case 4: return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
         case 2: return launch_fused_ktile_rows<T, KT, 2, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);

@@ -93,6 +93,78 @@ __device__ __forceinline__ unsigned long long descending_lanes(int k) {
     return __ballot(prev > k);
 }
 
+// Full check of the column order of every row: raises flags[0] on a descending pair inside a row.  One thread
+// per stored entry compares it with the entry before it; a descending pair is harmless only if the second entry
+// starts a row, which a binary search of rowptr decides (needed for few entries: about one per row).
+// Needed only by launches that cut K into ranges (K-split): a workgroup then starts inside each row, at a
+// position found by binary search, and the order check built into the tiled kernels sees only the entries it
+// streams - which proves nothing about a row that is not sorted.  Runs after reset_flags_kernel and does
+// nothing if that has already ruled the tiled kernels out.
+__global__ __launch_bounds__(256) void order_check_kernel(int M, const int32_t *__restrict__ rowptr,
+                                                         const int32_t *__restrict__ colidx, int32_t *flags) {
+    if (flags[1] == 0) return;
+    const int nnz = rowptr[M];
+    bool bad = false;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x + 1; j < nnz; j += gridDim.x * blockDim.x) {
+        if (colidx[j - 1] > colidx[j]) {
+            // does some row start at j?  lo = first row index with rowptr[lo] >= j
+            int lo = 0, hi = M;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (rowptr[mid] < j) lo = mid + 1;
+                else hi = mid;
+            }
+            bad |= rowptr[lo] != j;
+        }
+    }
+    if (bad) flags[0] = 1;
+}
+
+// K-split bookkeeping shared by the tiled kernels.  A launch with gridDim.y = S > 1 gives workgroup (x, y) the
+// rows of block x and the columns [kb, ke) of K; it leaves its result rows in `partial` (S x M x N floats) and
+// ksplit_reduce_kernel adds the S partial rows in the order of y: no atomics on floats, same bits every run.
+struct KSplit {
+    int kb, ke;
+};
+template <int KT>
+__device__ __forceinline__ KSplit ksplit_range(int K) {
+    const int tiles = (K + KT - 1) / KT;
+    const int per = (tiles + (int)gridDim.y - 1) / (int)gridDim.y;
+    KSplit r;
+    r.kb = (int)blockIdx.y * per * KT;
+    r.ke = r.kb + per * KT;
+    r.ke = r.ke < K ? r.ke : K;
+    r.kb = r.kb < K ? r.kb : K;
+    return r;
+}
+
+// position of the first entry of [p0, p1) whose column is >= kb (columns ascending)
+__device__ __forceinline__ int first_entry_at_or_after(const int32_t *colidx, int p0, int p1, int kb) {
+    if (kb <= 0 || p1 <= p0) return p0;
+    return p0 + wave_lower_bound(colidx + p0, p1 - p0, kb);
+}
+
+// O = sum over y of partial[y] (S x M x N floats), in the order of y: the second half of a K-split call.  Does
+// nothing if the tiled kernel before it stood down or met unsorted columns (the general kernels, launched after
+// this one, then write O).  A separate launch rather than a "last workgroup adds" inside the tiled kernel: the
+// device-wide fences that needs write back and invalidate an XCD's whole L2 each time, which cost three times
+// what the split gained.
+__global__ __launch_bounds__(256) void ksplit_reduce_kernel(size_t count4, int S, const float4 *__restrict__ partial,
+                                                           float4 *__restrict__ O, const int32_t *flags) {
+    if (!ktile_ok(flags)) return;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count4; i += (size_t)gridDim.x * blockDim.x) {
+        float4 sum = partial[i];
+        for (int y = 1; y < S; ++y) {
+            const float4 p = partial[(size_t)y * count4 + i];
+            sum.x += p.x;
+            sum.y += p.y;
+            sum.z += p.z;
+            sum.w += p.w;
+        }
+        O[i] = sum;
+    }
+}
+
 template <int T, int KT>
 struct KTileLds {
     static constexpr int kRowFloats = T * 256;
@@ -107,7 +179,8 @@ struct KTileLds {
 template <int T, int KT, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
+    float *partial) {
     using L = KTileLds<T, KT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
@@ -120,6 +193,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
 
+    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -130,6 +204,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         const int row = row0 + r;
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
@@ -176,12 +251,12 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
     };
 
-    issue(0);
-    for (int k0 = 0; k0 < K; k0 += KT) {
+    issue(ks.kb);
+    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         commit();
         __syncthreads();
-        if (k0 + KT < K) issue(k0 + KT);    // lands while this tile is being worked on
+        if (k0 + KT < ks.ke) issue(k0 + KT);    // lands while this tile is being worked on
         const int kend = k0 + KT;
         // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
         // large column numbers wrap instead of overflowing (the sum below is always a small offset)
@@ -271,13 +346,14 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         }
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
         if (row < M) {
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(O + (size_t)row * N + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * N + n + tt * 256, acc[r][tt]);
         }
     }
 }

@@ -40,7 +40,7 @@ template <int T, int KT, int ROWS, int SL, int PF>
 __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(SL == 32 || SL == 64, "slot sizes");
     static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
@@ -68,6 +68,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     const int my_r = (lane >> 4) / kGroupsPerRow;       // the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
+    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         const int row = row0 + r;
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
@@ -148,9 +150,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     using IEND = std::integral_constant<int, kPer>;
     constexpr bool kAllAhead = PF == kPer;
 
-    if constexpr (PF > 0) issue(0, I0{}, IPF{});
-    if constexpr (kAllAhead) issue_b(0);
-    for (int k0 = 0; k0 < K; k0 += KT) {
+    if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
+    if constexpr (kAllAhead) issue_b(ks.kb);
+    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         if constexpr (!kAllAhead) {
             issue(k0, IPF{}, IEND{});
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         commit();
         __syncthreads();
         if constexpr (PF > 0) {
-            if (k0 + KT < K) {                  // lands while this tile is being worked on
+            if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
                 issue(k0 + KT, I0{}, IPF{});
                 if constexpr (kAllAhead) issue_b(k0 + KT);
             }
@@ -307,13 +309,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         }
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
         if (row < M) {
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(O + (size_t)row * N + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * N + n + tt * 256, acc[r][tt]);
         }
     }
 }

@@ -38,7 +38,7 @@ template <int G, int KT, int ROWS, bool FUSED, int DMAX>
 __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags) {
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
     using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
     constexpr int LN = kWave / G;           // lanes per entry
     constexpr int LQ = DMAX / 16;           // FUSED dot stage: lanes per entry (16 floats each)
@@ -60,6 +60,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     const int q16 = (lane % LQ) * 16;       // FUSED dot stage: 16-float slice of the dot length
     const int ei = lane / LQ;               // FUSED dot stage: which of ER side-by-side entries
 
+    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -70,6 +71,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         const int row = row0 + r;
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     const size_t my_off = (size_t)my_kk * n4 + my_c4;
     const size_t step_off = (size_t)kStep * n4;
 
-    for (int k0 = 0; k0 < K; k0 += KT) {
+    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();
         {   // stage C[k0:k0+KT, 0:N] (and B[k0:k0+KT, 0:D]) in LDS
             const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;
@@ -250,7 +252,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
         const int row = row0 + r;
-        if (row < M && g == 0 && n < N) store_vec<4>(O + (size_t)row * N + n, acc[r]);
+        float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
+        if (row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
     }
     if (bad != 0 && lane == 0) flags[0] = 1;
 }

@@ -174,3 +174,76 @@ def test_nonfinite_values_in_unreferenced_rows_do_not_leak_ktile(csrk, N, D):
     run_spmm(csrk, M, K, N, rp, ci, v, C)
     run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
     run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
+def _env(name, value):
+    old = os.environ.get(name)
+    if value is None:
+        os.environ.pop(name, None)
+    else:
+        os.environ[name] = value
+    return old
+
+
+@pytest.mark.parametrize("M,K,D,N", [(300, 4096, 64, 512), (1000, 2500, 32, 256), (130, 3000, 128, 128), (257, 2048, 64, 64)])
+def test_ksplit_agrees_with_unsplit_and_repeats_bit_for_bit(csrk, M, K, D, N):
+    """Small M: the tiled SPMM / FusedMM kernels cut K into ranges, one workgroup per (row block, range), and a
+    second kernel adds the partial outputs in a fixed order.  Same answer (to the oracle's tolerance) as with the
+    split switched off, and the same bits on every run."""
+    rng = np.random.default_rng(M + K)
+    rp, ci = inputs.bernoulli_csr(7, M, K, 0.2)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    args = (dev(rp), dev(ci), dev(v))
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    outs = {}
+    for split in ("1", "2"):                       # 1 = automatic split, 2 = off
+        old = _env("CSRK_KSPLIT", split)
+        try:
+            run_spmm(csrk, M, K, N, rp, ci, v, C)
+            run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+            outs[split] = (csrk.spmm_csr(M, K, N, *args, dC).cpu().numpy(),
+                           csrk.fusedmm_csr(M, K, D, N, *args, dA, dB, dC).cpu().numpy())
+            again = (csrk.spmm_csr(M, K, N, *args, dC).cpu().numpy(),
+                     csrk.fusedmm_csr(M, K, D, N, *args, dA, dB, dC).cpu().numpy())
+            assert np.array_equal(outs[split][0], again[0]) and np.array_equal(outs[split][1], again[1])
+        finally:
+            _env("CSRK_KSPLIT", old)
+    # the two ways differ only by where partial sums are rounded
+    for a, b in zip(outs["1"], outs["2"]):
+        assert np.allclose(a, b, rtol=0, atol=1e-5 * (np.abs(a).max() + 1) * 50)
+
+
+@pytest.mark.parametrize("kind", ["shuffled", "rotated", "big_first", "one_swap_far_from_range_starts"])
+def test_ksplit_never_trusts_a_binary_search_in_unsorted_rows(csrk, kind):
+    """With K cut into ranges a workgroup finds its starting entry in each row by binary search, which means
+    nothing if the row is not sorted; such inputs must be noticed by the full order check that precedes a
+    K-split launch and handed to the general kernels."""
+    rng = np.random.default_rng(len(kind))
+    M, K, D, N = 200, 4096, 64, 512
+    rows = []
+    for i in range(M):
+        cols = sorted(rng.permutation(K)[: int(rng.integers(300, 1200))].tolist())
+        if kind == "shuffled":
+            cols = rng.permutation(cols).tolist()
+        elif kind == "rotated" and i % 3 == 0:
+            h = len(cols) // 2
+            cols = cols[h:] + cols[:h]                       # two sorted halves, the larger columns first
+        elif kind == "big_first" and i % 5 == 0:
+            cols = [cols[-1]] + cols[:-1]
+        rows.append(cols)
+    if kind == "one_swap_far_from_range_starts":
+        r = rows[77]
+        p = next(i for i, c in enumerate(r) if c > 700)      # well inside the first range
+        r[p], r[p + 1] = r[p + 1], r[p]
+    rp, ci = helpers.csr_from_rows(rows, K)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_spmm(csrk, M, K, 128, rp, ci, v, C[:, :128].copy())
+    run_fused(csrk, M, K, D, 128, rp, ci, v, A, B, C[:, :128].copy())
