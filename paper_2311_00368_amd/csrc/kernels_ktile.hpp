@@ -18,12 +18,12 @@
 // within a row, the entries of the current tile are a prefix of the chunk, whose
 // length is a ballot + popcount.
 //
-// Instruction budget (the kernel is bound by VALU issue, not by LDS or HBM):
+// Instruction budget (the kernel is bound by VALU issue and LDS delivery together, not by HBM):
 //  - The chunk is parked in a small per-wavefront LDS slot as (column, value) pairs
-//    and each entry is fetched back with one 64-bit read whose address is the same in
-//    every lane (an LDS broadcast).  That puts column and value in VGPRs of all lanes
-//    with no VALU work; v_readlane_b32 would cost two 8-cycle VALU slots per entry,
-//    a third of the kernel's time when measured.
+//    and entries are fetched back two at a time with one 128-bit read whose address is
+//    the same in every lane (an LDS broadcast).  That puts column and value in VGPRs of
+//    all lanes with no VALU work; v_readlane_b32 would cost two 8-cycle VALU slots per
+//    entry, a third of the kernel's time when measured.
 //  - Per entry that leaves one address computation plus the 4*T multiply-adds.
 //  - Entries go in batches of 4: pair reads, then all row reads, then the multiply-adds,
 //    so LDS latency overlaps.
@@ -32,7 +32,7 @@
 //    tile barrier: no vector-memory wait ever sits inside the arithmetic.
 //
 // Requirements: columns of every row non-decreasing; S dense enough for the LDS copy to
-// pay.  Density is read off rowptr[M] by a one-thread kernel beforehand.  Ordering is
+// pay.  Density and row-length spread are read off rowptr by reset_flags_kernel beforehand.  Ordering is
 // verified by the tiled kernels themselves at no extra memory traffic: every look-ahead
 // chunk they load is compared lane against neighbouring lane (one DPP shift and a
 // compare), and chunks overlap, so every adjacent pair of a row passes through the check.
@@ -40,8 +40,10 @@
 // (never out of bounds: the cursors only move inside the row and LDS reads cannot fault)
 // and the general kernels, which are launched right behind it, redo the whole call.
 //
+// Small M: a launch may cut K into ranges, one workgroup per (row block, range); see KSplit below.
+//
 // The FusedMM version of this kernel (same accumulate stage plus a score stage) is in
-// kernels_ktile_fused.hpp.
+// kernels_ktile_fused.hpp; the tiled SDDMM kernel is at the end of this file.
 #pragma once
 #include <type_traits>
 
