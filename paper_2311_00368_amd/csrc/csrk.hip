@@ -304,7 +304,7 @@ csrk_status launch_ksplit_reduce(DeviceState &d, hipStream_t st, int M, int N, i
 template <int DMAX, int ROWS>
 csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
-    using L = SddmmTileLds<DMAX>;
+    using L = SddmmTileLds<DMAX, ROWS>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     auto kern = sddmm_ktile_kernel<DMAX, ROWS>;
     static bool attr_set[kMaxDevices] = {};

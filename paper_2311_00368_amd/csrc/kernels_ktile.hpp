@@ -380,18 +380,20 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 // registers while the current one is worked on.  P may alias vals: each lane reads its value
 // before writing its result.
 // ---------------------------------------------------------------------------------------
-template <int DMAX>
+template <int DMAX, int ROWS>
 struct SddmmTileLds {
     static constexpr int kPieces = DMAX / 4;                    // 128-bit pieces per LDS row
     static constexpr int kKT = 147456 / (DMAX * 4);             // tile height: 144 KB of rows of B
-    static constexpr int kBytes = kKT * DMAX * 4;
+    static constexpr int kTileFloats = kKT * DMAX;
+    static constexpr int kAFloats = kTileWaves * ROWS * DMAX;   // the workgroup's rows of A, zero beyond D
+    static constexpr int kBytes = (kTileFloats + kAFloats) * 4;
 };
 
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     int M, int K, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
     const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags) {
-    using L = SddmmTileLds<DMAX>;
+    using L = SddmmTileLds<DMAX, ROWS>;
     constexpr int KT = L::kKT;
     constexpr int C = L::kPieces;
     constexpr int S = C < 16 ? C : 16;      // steps of the dot loop
@@ -405,6 +407,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const int wave = uniform(threadIdx.x >> 6);
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int d4n = D >> 2;                 // float4s per row of A / B
+    float *arows = lds + L::kTileFloats + wave * (ROWS * DMAX);   // this wavefront's rows of A
 
     // which way row_ror turns is measured, not assumed: `turn` is +1 or -1 (mod 16)
     const int i16 = lane & 15;
@@ -417,9 +420,11 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     // the same length serves) and their results are not used
     const bool has_vals = vals != nullptr;
     const float *vsrc = has_vals ? vals : reinterpret_cast<const float *>(colidx);
-    int pos[ROWS], end[ROWS], kc[ROWS];
-    float vc[ROWS];                         // look-ahead chunk: columns and values of the next 64 entries of each row
-    float a[ROWS][H][4];                    // this lane's pieces of the rows of A, zero beyond D
+    // Two look-ahead chunks per row: columns and values of the next 128 entries, requested at the end of a
+    // tile for the next one.  A row's entries of a tile (115 on average at 20 % and D = 64) then need no load
+    // inside the tile's arithmetic; only a row with more than 128 entries in one tile loads as it goes.
+    int pos[ROWS], end[ROWS], kc[ROWS], kc2[ROWS];
+    float vc[ROWS], vc2[ROWS];
     unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -429,12 +434,13 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
         const int j = pos[r] + lane;
         kc[r] = j < end[r] ? colidx[j] : 0x7fffffff;
         vc[r] = j < end[r] ? vsrc[j] : 1.f;
-#pragma unroll
-        for (int h = 0; h < H; ++h) {
-            const int piece = h * 16 + (i16 & (S - 1));
-#pragma unroll
-            for (int v = 0; v < 4; ++v) a[r][h][v] = 0.f;
-            if (row < M && piece < d4n) load_vec<4>(A + (size_t)row * D + piece * 4, a[r][h]);
+        kc2[r] = j + kWave < end[r] ? colidx[j + kWave] : 0x7fffffff;
+        vc2[r] = j + kWave < end[r] ? vsrc[j + kWave] : 1.f;
+        // the row of A into LDS, zero beyond D (piece `lane` of each row; read back per tile, 16 bytes per lane)
+        if (lane < C) {
+            float piece[4] = {0.f, 0.f, 0.f, 0.f};
+            if (row < M && lane < d4n) load_vec<4>(A + (size_t)row * D + lane * 4, piece);
+            store_vec<4>(arows + r * DMAX + lane * 4, piece);
         }
     }
 
@@ -484,23 +490,13 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
         const int kend = k0 + KT;
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            // the look-ahead registers hold what was loaded from clamped positions: mask the lanes past the row's end
-            const bool live = lane < end[r] - pos[r];
-            int kcur = live ? kc[r] : 0x7fffffff;
-            float vcur = vc[r];
-            int cnt = __builtin_popcountll(__ballot(kcur < kend));
-            bad |= descending_lanes(kcur);      // checked where first used, not where requested
-            const bool any = cnt > 0;
-            while (cnt > 0) {
+            float a[H][4];                  // this lane's pieces of the row of A
+#pragma unroll
+            for (int h = 0; h < H; ++h) load_vec<4>(arows + r * DMAX + (h * 16 + (i16 & (S - 1))) * 4, a[h]);
+            // one chunk: lane j < cnt scores entry pos[r] + j, whose column is kcur and value vcur
+            auto chunk = [&](int kcur, float vcur, int cnt) {
                 const int j = pos[r] + lane;
                 const bool in = lane < cnt;
-                // speculative look-ahead: the chunk that follows if this one lies wholly in the tile.  Loaded
-                // without a branch (position clamped into the row, which has entries here), selected at its use
-                const int jn = j + kWave;
-                const bool has_next = jn < end[r];
-                const int jl = has_next ? jn : end[r] - 1;
-                const int kload = colidx[jl];
-                const float vload = vsrc[jl];
                 const char *brow = reinterpret_cast<const char *>(lds) + (unsigned)(in ? kcur - k0 : 0) * (DMAX * 4);
                 // the row's S * H pieces in groups of GL reads, the next group requested before the
                 // multiply-adds of the current one
@@ -522,27 +518,49 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
                         constexpr int u = decltype(uc)::value;
                         constexpr int q = g * GL + u;
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) fma_row_rotated<q / H>(dot, a[r][q % H][c], b[g & 1][u][c]);
+                        for (int c = 0; c < 4; ++c) fma_row_rotated<q / H>(dot, a[q % H][c], b[g & 1][u][c]);
                     });
                 });
                 if (in) P[j] = (has_vals ? vcur : 1.f) * dot;
                 pos[r] += cnt;
-                if (cnt < kWave) break;
-                // the whole chunk lay in the tile: the speculative chunk is the next one; check it
-                // and the pair that straddles the two
-                const int knext = has_next ? kload : 0x7fffffff;
-                bad |= descending_lanes(knext);
-                if (__builtin_amdgcn_readlane(kcur, kWave - 1) > __builtin_amdgcn_readlane(knext, 0)) bad |= 1;
-                kcur = knext;
-                vcur = vload;
-                cnt = __builtin_popcountll(__ballot(kcur < kend));
-            }
-            // look-ahead chunk for the next tile (clamped like the speculative one)
-            if (any) {
+            };
+            // the look-ahead registers hold what was loaded from clamped positions: mask the lanes past the row's end
+            const int left = end[r] - pos[r];
+            const int k1 = lane < left ? kc[r] : 0x7fffffff;
+            const int k2 = lane + kWave < left ? kc2[r] : 0x7fffffff;
+            const int cnt1 = __builtin_popcountll(__ballot(k1 < kend));
+            bad |= descending_lanes(k1);        // checked where first used, not where requested
+            if (cnt1 > 0) {
+                chunk(k1, vc[r], cnt1);
+                if (cnt1 == kWave) {
+                    // the whole first chunk lay in the tile: on to the second, and check the pair that straddles the two
+                    bad |= descending_lanes(k2);
+                    if (__builtin_amdgcn_readlane(k1, kWave - 1) > __builtin_amdgcn_readlane(k2, 0)) bad |= 1;
+                    int cnt = __builtin_popcountll(__ballot(k2 < kend));
+                    if (cnt > 0) chunk(k2, vc2[r], cnt);
+                    // rare: more than 128 entries of this row in the tile; go on chunk by chunk with blocking loads
+                    int lastk = __builtin_amdgcn_readlane(k2, kWave - 1);
+                    while (cnt == kWave && pos[r] < end[r]) {
+                        const int jn = pos[r] + lane;
+                        const int jl = jn < end[r] ? jn : end[r] - 1;
+                        const int kl = colidx[jl];
+                        const float vl = vsrc[jl];
+                        const int k3 = jn < end[r] ? kl : 0x7fffffff;
+                        bad |= descending_lanes(k3);
+                        if (lastk > __builtin_amdgcn_readlane(k3, 0)) bad |= 1;
+                        lastk = __builtin_amdgcn_readlane(k3, kWave - 1);
+                        cnt = __builtin_popcountll(__ballot(k3 < kend));
+                        if (cnt > 0) chunk(k3, vl, cnt);
+                    }
+                }
+                // look-ahead chunks for the next tile (positions clamped into the row, which has entries here)
                 const int j = pos[r] + lane;
-                const int jl = j < end[r] ? j : end[r] - 1;
-                kc[r] = colidx[jl];
-                vc[r] = vsrc[jl];
+                const int j1 = j < end[r] ? j : end[r] - 1;
+                const int j2 = j + kWave < end[r] ? j + kWave : end[r] - 1;
+                kc[r] = colidx[j1];
+                vc[r] = vsrc[j1];
+                kc2[r] = colidx[j2];
+                vc2[r] = vsrc[j2];
             }
         }
     }
