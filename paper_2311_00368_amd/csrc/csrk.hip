@@ -223,11 +223,23 @@ void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32
 
 // --- LDS-tiled path ---------------------------------------------------------------------
 // Host-side eligibility (shapes only); the device-side analysis has the last word.
-// rows of S per wavefront in the LDS-tiled SPMM/FusedMM kernels: 4 when that still gives every CU
-// a workgroup (M >= 64 * CUs), else 2, else 1
+// Rows of S per wavefront in the LDS-tiled SPMM/FusedMM kernels (one workgroup of 16 wavefronts per CU at a
+// time): 4, 2 or 1.  More rows spread the per-tile work (staging, barriers) over more entries, but the grid
+// runs in rounds of `CUs` workgroups and a last round that is mostly empty costs as much as a full one:
+// pick the count with the least rounds x (rows + one half row's worth of per-tile work); ties go to more rows.
 int tile_rows_for(const DeviceState &d, int M) {
-    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
-    return blocks1 >= 4ll * d.cus ? 4 : blocks1 >= 2ll * d.cus ? 2 : 1;
+    int best = 4;
+    long long best_cost = -1;
+    for (int rows = 4; rows >= 1; rows >>= 1) {
+        const long long blocks = ((long long)M + kTileWaves * rows - 1) / (kTileWaves * rows);
+        const long long rounds = (blocks + d.cus - 1) / d.cus;
+        const long long cost = rounds * (2 * rows + 1);
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best = rows;
+        }
+    }
+    return best;
 }
 // K-split (the small-M regime): when even one row per wavefront would leave CUs without a workgroup of the
 // tiled kernels, keep 4 rows per wavefront and cut K into S ranges instead, one workgroup per (row block,
@@ -242,7 +254,12 @@ int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per
     const long long tiles = ((long long)K + tile_height - 1) / tile_height;
     if (s > tiles / 4) s = tiles / 4;
     if (s > kMaxKSplit) s = kMaxKSplit;
-    return s < 2 ? 1 : (int)s;
+    if (s < 2) return 1;
+    // worth it only if the split grid fills the CUs, or at least offers more workgroups than one row per
+    // wavefront over the whole of K would
+    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
+    if (blocks * s < d.cus && blocks * s <= blocks1) return 1;
+    return (int)s;
 }
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
 constexpr float kNarrowMinDensity = 0.18f;    // narrow-output tiled kernels (measured cross-over with the general path)
@@ -252,9 +269,11 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
-float narrow_min_density(const DeviceState &d, int M) {
+float narrow_min_density(const DeviceState &d, int M, int N) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
-    return (long long)M >= 96ll * d.cus ? 0.05f : kNarrowMinDensity;    // many rows per wavefront amortise the staging
+    if ((long long)M >= 96ll * d.cus) return 0.05f;        // many rows per wavefront amortise the staging
+    if (N > 64 && (long long)M >= 32ll * d.cus) return 0.08f;
+    return kNarrowMinDensity;
 }
 float sddmm_min_density(const DeviceState &d, int M, int D) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
@@ -354,15 +373,23 @@ bool narrow_shape_ok(const DeviceState &d, int M, int N, bool fused) {
     return rows_per_cu >= 16;                               // at least one workgroup per CU at one row per wavefront
 }
 
+// tile height of the narrow kernels: SPMM as high as LDS allows with 128-entry look-ahead in mind (256 rows of
+// 128 columns, 384 of 64 or 32); FusedMM 128 rows (B's rows are staged too), 96 where those are 128 floats long
+template <int G, bool FUSED, int DMAX>
+constexpr int narrow_kt() {
+    return FUSED ? ((DMAX == 128 && G == 2) ? 96 : 128) : (G == 2 ? 256 : 384);
+}
+
 template <int G, int ROWS, bool FUSED, int DMAX>
 csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                                float *O, int ksplit = 1) {
-    // 128-row tiles, except where FusedMM's staging of 128-long rows of A and B would not leave room
-    constexpr int KT = (FUSED && DMAX == 128 && G == 2) ? 96 : 128;
+    constexpr int KT = narrow_kt<G, FUSED, DMAX>();
     using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
-    auto kern = ktile_narrow_kernel<G, KT, ROWS, FUSED, DMAX>;
+    // register prefetch of the next tile: all of a thread's loads
+    constexpr int kPer = KT / (kTileThreads / (64 / G));
+    auto kern = ktile_narrow_kernel<G, KT, ROWS, FUSED, DMAX, kPer>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -383,7 +410,7 @@ csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D,
                             const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                             float *O) {
     // small M: keep 4 rows per wavefront and cut K into ranges instead
-    constexpr int KT = (FUSED && DMAX == 128 && G == 2) ? 96 : 128;
+    constexpr int KT = narrow_kt<G, FUSED, DMAX>();
     // (not for outputs of 32 columns or fewer, G = 8: there the split never measured faster)
     const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, KT, kTileWaves * 4);
     if (ksplit > 1) {
@@ -391,13 +418,11 @@ csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D,
         if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
         return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
     }
-    // two workgroups share a CU, so aim for at least two per CU before giving a wavefront more rows
-    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
-    if (blocks1 >= 8ll * d.cus)
-        return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-    if (blocks1 >= 4ll * d.cus)
-        return launch_narrow_rows<G, 2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-    return launch_narrow_rows<G, 1, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    switch (tile_rows_for(d, M)) {
+        case 4: return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 2: return launch_narrow_rows<G, 2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        default: return launch_narrow_rows<G, 1, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    }
 }
 
 template <bool FUSED, int DMAX>
@@ -545,7 +570,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     if (vec4 && narrow_shape_ok(*d, M, N, false)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_narrow<false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
@@ -639,7 +664,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N, true)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_narrow<true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);

@@ -6,13 +6,14 @@
 // narrow dense row: the wavefront is cut into G groups of 64/G lanes, a group covers the
 // 256/G-column row with one 128-bit read per lane, and the G groups work on G different
 // entries at once.  Each group accumulates its own partial row; the G partial rows are added
-// once, at the very end.  A tile is 128 rows (64 KB at 128 columns, 32 KB at 64, 16 KB at
-// 32), so that two workgroups fit a CU and cover each other's staging phases; the staging
-// therefore goes straight through registers without a look-ahead of its own.
+// once, at the very end.  One workgroup per CU (the kernel needs more than 64 registers per lane), so the
+// next tile is requested into registers while the current one is worked on (PF of a thread's loads, the
+// rest at the start of the tile), and SPMM's tiles are as high as LDS allows (256 rows at 128 columns, 384
+// at 64 and 32): more entries per row and tile to spread the per-tile work over.
 //
-// A segment longer than the chunk (more than 64 entries of a row inside one tile: dense or
-// very long rows) continues chunk by chunk with blocking loads; that path is correct for any
-// length but only the first 64 entries of a segment run at full speed.
+// Two look-ahead chunks per row (128 entries) are kept in registers.  A segment longer than that (dense or
+// very long rows) continues chunk by chunk with blocking loads; that path is correct for any length but
+// only the first 128 entries of a segment run at full speed.
 #pragma once
 #include <type_traits>
 
@@ -34,7 +35,7 @@ struct NarrowLds {
     static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
 };
 
-template <int G, int KT, int ROWS, bool FUSED, int DMAX>
+template <int G, int KT, int ROWS, bool FUSED, int DMAX, int PF>
 __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
@@ -62,8 +63,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
     int pos[ROWS], end[ROWS];
-    int kc[ROWS];
-    float vc[ROWS];
+    int kc[ROWS], kc2[ROWS];                // look-ahead: columns of the next 64 entries and of the 64 after them
+    float vc[ROWS], vc2[ROWS];              // ... and their values
     float acc[ROWS][4];
     unsigned long long bad = 0;
 #pragma unroll
@@ -76,6 +77,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
         vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+        const bool ok2 = j + kWave < end[r];
+        kc2[r] = ok2 ? colidx[j + kWave] : 0x7fffffff;
+        vc2[r] = ok2 ? (vals ? vals[j + kWave] : 1.f) : 0.f;
         acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.f;
     }
     if constexpr (FUSED) {
@@ -97,41 +101,75 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     const size_t my_off = (size_t)my_kk * n4 + my_c4;
     const size_t step_off = (size_t)kStep * n4;
 
-    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
-        __syncthreads();
-        {   // stage C[k0:k0+KT, 0:N] (and B[k0:k0+KT, 0:D]) in LDS
-            const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;
-            float4 stage[kPer];
+    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
+    float4 stage[kPer];
+    float4 stageb[kPerB];
+    // loads number [I0, I1) of this thread for the C tile that starts at column k0
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        if (k0 + KT <= K) {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
+            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (my_col) {
+#pragma unroll
+                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
+            }
+        } else {                                      // last, partial tile
+#pragma unroll
+            for (int i = I0; i < I1; ++i) {
                 stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
             }
-            float4 stageb[kPerB];
-            if constexpr (FUSED) {
-                const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
-                const int d4 = D >> 2;
+        }
+    };
+    auto issue_b = [&](int k0) {
+        if constexpr (FUSED) {
+            const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
+            const int d4 = D >> 2;
 #pragma unroll
-                for (int i = 0; i < kPerB; ++i) {
-                    const int e = i * kTileThreads + threadIdx.x;
-                    const int kk = e / kD4, c4 = e % kD4;
-                    stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
-                }
-            }
-            float4 *dst = reinterpret_cast<float4 *>(ct);
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
-            if constexpr (FUSED) {
-                float4 *dstb = reinterpret_cast<float4 *>(bt);
-#pragma unroll
-                for (int i = 0; i < kPerB; ++i) {
-                    const int e = i * kTileThreads + threadIdx.x;
-                    if (e < KT * kD4) dstb[(e / kD4) * (L::kDStride / 4) + (e % kD4)] = stageb[i];
-                }
+            for (int i = 0; i < kPerB; ++i) {
+                const int e = i * kTileThreads + threadIdx.x;
+                const int kk = e / kD4, c4 = e % kD4;
+                stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
             }
         }
+    };
+    auto commit = [&]() {
+        float4 *dst = reinterpret_cast<float4 *>(ct);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        if constexpr (FUSED) {
+            float4 *dstb = reinterpret_cast<float4 *>(bt);
+#pragma unroll
+            for (int i = 0; i < kPerB; ++i) {
+                const int e = i * kTileThreads + threadIdx.x;
+                if (e < KT * kD4) dstb[(e / kD4) * (L::kDStride / 4) + (e % kD4)] = stageb[i];
+            }
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using IPF = std::integral_constant<int, PF>;
+    using IEND = std::integral_constant<int, kPer>;
+    constexpr bool kAllAhead = PF == kPer;      // then FusedMM's B tile is prefetched as well
+
+    if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
+    if constexpr (kAllAhead) issue_b(ks.kb);
+    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
+        __syncthreads();                    // previous tile fully consumed
+        if constexpr (!kAllAhead) {
+            issue(k0, IPF{}, IEND{});
+            issue_b(k0);
+        }
+        commit();
         __syncthreads();
+        if constexpr (PF > 0) {
+            if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
+                issue(k0 + KT, I0{}, IPF{});
+                if constexpr (kAllAhead) issue_b(k0 + KT);
+            }
+        }
         const int kend = k0 + KT;
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
         bool moved[ROWS];
@@ -209,27 +247,37 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
+            const int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
             bad |= descending_lanes(kc[r]);
             moved[r] = cnt > 0;
             if (cnt > 0) {
-                process(r, r & 1, kc[r], vc[r], cnt);
+                process(r, 0, kc[r], vc[r], cnt);
                 pos[r] += cnt;
                 if (cnt == kWave) {
-                    // the whole chunk lay in the tile: go on chunk by chunk with blocking loads
-                    int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
-                    while (pos[r] < end[r]) {
-                        const bool ok2 = lane < end[r] - pos[r];
-                        const int k2 = ok2 ? (colidx + pos[r])[lane] : 0x7fffffff;
-                        const float v2 = ok2 ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
-                        bad |= descending_lanes(k2);
-                        if (__builtin_amdgcn_readlane(k2, 0) < lastk) bad |= 1;
-                        const int cnt2 = __builtin_popcountll(__ballot(k2 < kend));
-                        if (cnt2 == 0) break;
-                        process(r, r & 1, k2, v2, cnt2);
-                        pos[r] += cnt2;
-                        if (cnt2 < kWave) break;
-                        lastk = __builtin_amdgcn_readlane(k2, kWave - 1);
+                    // the whole first chunk lay in the tile: on to the second one
+                    bad |= descending_lanes(kc2[r]);
+                    if (__builtin_amdgcn_readlane(kc2[r], 0) < __builtin_amdgcn_readlane(kc[r], kWave - 1)) bad |= 1;
+                    const int cntb = __builtin_popcountll(__ballot(kc2[r] < kend));
+                    if (cntb > 0) {
+                        process(r, 1, kc2[r], vc2[r], cntb);
+                        pos[r] += cntb;
+                    }
+                    if (cntb == kWave) {
+                        // rare: more than 128 entries of the row in this tile: chunk by chunk with blocking loads
+                        int lastk = __builtin_amdgcn_readlane(kc2[r], kWave - 1);
+                        while (pos[r] < end[r]) {
+                            const bool ok3 = lane < end[r] - pos[r];
+                            const int k3 = ok3 ? (colidx + pos[r])[lane] : 0x7fffffff;
+                            const float v3 = ok3 ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                            bad |= descending_lanes(k3);
+                            if (__builtin_amdgcn_readlane(k3, 0) < lastk) bad |= 1;
+                            const int cnt3 = __builtin_popcountll(__ballot(k3 < kend));
+                            if (cnt3 == 0) break;
+                            process(r, 0, k3, v3, cnt3);
+                            pos[r] += cnt3;
+                            if (cnt3 < kWave) break;
+                            lastk = __builtin_amdgcn_readlane(k3, kWave - 1);
+                        }
                     }
                 }
             }
@@ -238,9 +286,12 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (moved[r]) {
-                const bool okn = lane < end[r] - pos[r];
+                const int left = end[r] - pos[r];
+                const bool okn = lane < left, okn2 = lane + kWave < left;
                 kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
                 vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                kc2[r] = okn2 ? (colidx + pos[r] + kWave)[lane] : 0x7fffffff;
+                vc2[r] = okn2 ? (vals ? (vals + pos[r] + kWave)[lane] : 1.f) : 0.f;
             }
         }
     }
