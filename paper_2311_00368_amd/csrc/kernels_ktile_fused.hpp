@@ -24,7 +24,7 @@
 namespace csrk {
 
 // SL: entries per row that the wavefront's LDS slot holds (32 or 64); a row with more entries than that in
-// one tile finishes them one at a time.
+// one tile goes through the slot in parts.
 template <int T, int KT, int ROWS, int SL>
 struct FusedTileLds {
     static constexpr int kRowFloats = T * 256;
@@ -171,19 +171,30 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         // large column numbers wrap instead of overflowing (the sum below is always a small offset)
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
 
-        // entries of this tile = leading lanes of each row's chunk with column < kend; park the chunks
+        // entries of this tile = leading lanes of each row's chunk with column < kend
+        int full[ROWS];                     // ... how many of the chunk's 64
+        int most = 0;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            full[r] = __builtin_popcountll(__ballot(kc[r] < kend));
+            most = full[r] > most ? full[r] : most;
+            // order check on the chunk, here where it is first used
+            bad |= descending_lanes(kc[r]);
+        }
+        // the slots hold SL entries per row: lanes [part, part + SL) of the chunks at a time (one part unless a
+        // row has more than SL entries in this tile)
+        for (int part = 0; part < most; part += SL) {
         int cnts[ROWS];
         int maxcnt = 0, my_cnt = 0;
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
-            cnt = cnt < SL ? cnt : SL;          // what the slot holds; a row that fills it continues below
+            int cnt = full[r] - part;
+            cnt = cnt < 0 ? 0 : (cnt < SL ? cnt : SL);
             cnts[r] = cnt;
             maxcnt = cnt > maxcnt ? cnt : maxcnt;
             if (my_r == r) my_cnt = cnt;
-            // order check on the chunk, here where it is first used
-            bad |= descending_lanes(kc[r]);
-            if (SL == kWave || lane < SL) ent[r * SL + lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+            if (lane >= part && lane < part + SL)
+                ent[r * SL + lane - part] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
         }
 
         for (int base = 0; base < maxcnt; base += kPass) {
@@ -266,13 +277,15 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             }
         }
 
+        }   // part
+
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            pos[r] += cnts[r];
-            if (cnts[r] == SL) {
-                // rare (a row with SL or more entries inside one tile): finish the tile's entries of this row
+            pos[r] += full[r];
+            if (full[r] == kWave) {
+                // rare (a row with 64 or more entries inside one tile): finish the tile's entries of this row
                 // one at a time straight from memory; the 16 lanes of the row's first group hold the row of A
-                int lastk = __builtin_amdgcn_readlane(kc[r], SL - 1);
+                int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
                 while (pos[r] < end[r]) {
                     const int k = uniform(colidx[pos[r]]);
                     if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
@@ -301,7 +314,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         // look-ahead chunks for the next tile, all requested here, after the arithmetic
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            if (cnts[r] > 0) {
+            if (full[r] > 0) {
                 const bool okn = lane < end[r] - pos[r];
                 kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
                 vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
