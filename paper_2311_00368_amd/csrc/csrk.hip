@@ -271,6 +271,7 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
 float narrow_min_density(const DeviceState &d, int M, int N) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
+    if (N <= 32) return (long long)M >= 96ll * d.cus ? 0.15f : kNarrowMinDensity;   // general path wins at 10 %
     if ((long long)M >= 96ll * d.cus) return 0.05f;        // many rows per wavefront amortise the staging
     if (N > 64 && (long long)M >= 32ll * d.cus) return 0.08f;
     return kNarrowMinDensity;
