@@ -374,23 +374,22 @@ bool narrow_shape_ok(const DeviceState &d, int M, int N, bool fused) {
     return rows_per_cu >= 16;                               // at least one workgroup per CU at one row per wavefront
 }
 
-// tile height of the narrow kernels: SPMM as high as LDS allows with 128-entry look-ahead in mind (256 rows of
-// 128 columns, 384 of 64 or 32); FusedMM 128 rows (B's rows are staged too), 96 where those are 128 floats long
-template <int G, bool FUSED, int DMAX>
+// tile height of the narrow SPMM kernel: as high as LDS allows with the 128-entry look-ahead in mind (256 rows
+// of 128 columns, 384 of 64 or 32)
+template <int G>
 constexpr int narrow_kt() {
-    return FUSED ? ((DMAX == 128 && G == 2) ? 96 : 128) : (G == 2 ? 256 : 384);
+    return G == 2 ? 256 : 384;
 }
 
-template <int G, int ROWS, bool FUSED, int DMAX>
-csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                               const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                               float *O, int ksplit = 1) {
-    constexpr int KT = narrow_kt<G, FUSED, DMAX>();
-    using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
+template <int G, int ROWS>
+csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
+                               const int32_t *ci, const float *v, const float *C, float *O, int ksplit = 1) {
+    constexpr int KT = narrow_kt<G>();
+    using L = NarrowLds<G, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     // register prefetch of the next tile: all of a thread's loads
     constexpr int kPer = KT / (kTileThreads / (64 / G));
-    auto kern = ktile_narrow_kernel<G, KT, ROWS, FUSED, DMAX, kPer>;
+    auto kern = ktile_narrow_kernel<G, KT, ROWS, kPer>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -399,48 +398,37 @@ csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
-                       A, B, C, O, tile_flags(d), d.head);
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, C,
+                       O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
     return CSRK_OK;
 }
 
-template <int G, bool FUSED, int DMAX>
-csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                            const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                            float *O) {
+template <int G>
+csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
+                            const int32_t *ci, const float *v, const float *C, float *O) {
     // small M: keep 4 rows per wavefront and cut K into ranges instead
-    constexpr int KT = narrow_kt<G, FUSED, DMAX>();
     // (not for outputs of 32 columns or fewer, G = 8: there the split never measured faster)
-    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, KT, kTileWaves * 4);
+    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, narrow_kt<G>(), kTileWaves * 4);
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
-        return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+        return launch_narrow_rows<G, 4>(d, st, M, K, N, rp, ci, v, C, O, ksplit);
     }
     switch (tile_rows_for(d, M)) {
-        case 4: return launch_narrow_rows<G, 4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 2: return launch_narrow_rows<G, 2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        default: return launch_narrow_rows<G, 1, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 4: return launch_narrow_rows<G, 4>(d, st, M, K, N, rp, ci, v, C, O);
+        case 2: return launch_narrow_rows<G, 2>(d, st, M, K, N, rp, ci, v, C, O);
+        default: return launch_narrow_rows<G, 1>(d, st, M, K, N, rp, ci, v, C, O);
     }
 }
 
-template <bool FUSED, int DMAX>
-csrk_status launch_narrow_d(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                            const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                            float *O) {
-    if (N > 64) return launch_narrow_g<2, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-    if (N > 32) return launch_narrow_g<4, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-    return launch_narrow_g<8, FUSED, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-}
-
-template <bool FUSED>
-csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                          const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                          float *O) {
-    if (FUSED && D > 64) return launch_narrow_d<FUSED, 128>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-    return launch_narrow_d<FUSED, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+// narrow SPMM: G entries side by side, G chosen by the output width
+csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp, const int32_t *ci,
+                          const float *v, const float *C, float *O) {
+    if (N > 64) return launch_narrow_g<2>(d, st, M, K, N, rp, ci, v, C, O);
+    if (N > 32) return launch_narrow_g<4>(d, st, M, K, N, rp, ci, v, C, O);
+    return launch_narrow_g<8>(d, st, M, K, N, rp, ci, v, C, O);
 }
 
 template <int T, int KT, int ROWS>
@@ -525,6 +513,75 @@ csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int
     }
 }
 
+// --- narrow FusedMM (N <= 128, D <= 128): fused_narrow_kernel -------------------------------------------
+// tile height: 128 rows (C and B tiles plus 64-entry slots fit 160 KB at any width), 160 where both are narrow
+template <int G, int DMAX>
+constexpr int fused_narrow_kt() {
+    return (G == 2 && DMAX == 64) ? 160 : 128;
+}
+
+template <int G, int ROWS, int DMAX>
+csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                                     const int32_t *ci, const float *v, const float *A, const float *B,
+                                     const float *C, float *O, int ksplit = 1) {
+    constexpr int KT = fused_narrow_kt<G, DMAX>();
+    constexpr int SL = 64;
+    using L = FusedNarrowLds<G, KT, ROWS, SL, DMAX>;
+    static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
+    // register prefetch of the next tile: as many of a thread's loads as fit in 128 registers beside the score
+    // stage (which is twice as long for 128-float rows of B)
+    constexpr int kPer = KT / (kTileThreads / (64 / G));
+    constexpr int kPrefetch = DMAX == 128 ? (kPer - 1 < 2 ? kPer - 1 : 2) : (kPer <= 2 ? kPer : kPer - 1);
+    auto kern = fused_narrow_kernel<G, KT, ROWS, SL, DMAX, kPrefetch>;
+    static bool attr_set[kMaxDevices] = {};
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (!attr_set[dev]) {
+        CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
+        attr_set[dev] = true;
+    }
+    const int rb = kTileWaves * ROWS;
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
+                       A, B, C, O, tile_flags(d), d.head);
+    CSRK_HIP(hipGetLastError());
+    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
+    return CSRK_OK;
+}
+
+template <int G, int DMAX>
+csrk_status launch_fused_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                                  const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                                  float *O) {
+    // small M: keep 4 rows per wavefront and cut K into ranges (not for outputs of 32 columns or fewer)
+    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4);
+    if (ksplit > 1) {
+        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
+        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
+        return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+    }
+    switch (tile_rows_for(d, M)) {
+        case 4: return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 2: return launch_fused_narrow_rows<G, 2, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        default: return launch_fused_narrow_rows<G, 1, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    }
+}
+
+template <int DMAX>
+csrk_status launch_fused_narrow_d(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                                  const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                                  float *O) {
+    if (N > 64) return launch_fused_narrow_g<2, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    if (N > 32) return launch_fused_narrow_g<4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    return launch_fused_narrow_g<8, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+}
+
+csrk_status launch_fused_narrow(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
+                                const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
+                                float *O) {
+    if (D > 64) return launch_fused_narrow_d<128>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+    return launch_fused_narrow_d<64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+}
+
 // --- validation kernels -------------------------------------------------------------
 __global__ void validate_rowptr_kernel(int M, const int32_t *rowptr, int32_t *flags) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -574,7 +631,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
         gate = tile_flags(*d);
         rec.begin();
-        csrk_status s = launch_narrow<false>(*d, stream, M, K, 0, N, rowptr, colidx, vals, nullptr, nullptr, B, O);
+        csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
         if (s) return s;
     } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
         // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
@@ -668,7 +725,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
         gate = tile_flags(*d);
         rec.begin();
-        csrk_status s = launch_narrow<true>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+        csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;

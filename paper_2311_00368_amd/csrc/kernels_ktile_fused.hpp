@@ -334,4 +334,324 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// FusedMM for narrow outputs (N <= 128, D <= 128): the paper's own shapes.  Score stage exactly as above (lanes
+// as entries, a group of 16 lanes per row, rotated walk of the rows of B, which may now be 128 floats = two
+// halves of 16 pieces); accumulate stage as in ktile_narrow_kernel: the wavefront is cut into G groups of 64/G
+// lanes, a group covers the 256/G-column row of C with one 128-bit read per lane, the G groups work on G
+// different entries at once and their G partial rows are added at the very end.
+// ---------------------------------------------------------------------------------------------------------
+template <int G, int KT, int ROWS, int SL, int DMAX>
+struct FusedNarrowLds {
+    static constexpr int kRowFloats = 256 / G;
+    static constexpr int kCFloats = KT * kRowFloats;            // tile of C
+    static constexpr int kBFloats = KT * DMAX;                  // tile of B, rows zero-padded to DMAX floats
+    static constexpr int kEntFloats = kTileWaves * ROWS * SL * 2;
+    static constexpr int kBytes = (kCFloats + kBFloats + kEntFloats) * 4;
+};
+
+template <int G, int KT, int ROWS, int SL, int DMAX, int PF>
+__global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
+    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
+    using L = FusedNarrowLds<G, KT, ROWS, SL, DMAX>;
+    static_assert(SL == 32 || SL == 64, "slot sizes");
+    static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
+    static_assert(DMAX == 64 || DMAX == 128, "dot lengths the score stage is laid out for");
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    if (!ktile_ok(flags)) return;
+    constexpr int LN = kWave / G;           // lanes per entry in the accumulate stage
+    constexpr int H = DMAX / 64;            // 16-piece halves of a row of B
+    constexpr int kRowBytes = L::kRowFloats * 4;
+    constexpr int kBRowBytes = DMAX * 4;
+    constexpr int kGroupsPerRow = 4 / ROWS;
+    constexpr int kPass = 16 * kGroupsPerRow;      // entries of a row scored per pass
+    const int lane = lane_id();
+    const int wave = uniform(threadIdx.x >> 6);
+    float *ct = lds;
+    float *bt = lds + L::kCFloats;
+    int2 *ent = reinterpret_cast<int2 *>(bt + L::kBFloats) + wave * (ROWS * SL);
+
+    // see fused_ktile_kernel: the rotated walk assumes row_ror:s hands lane i the value of lane i - s
+    const int i16 = lane & 15;
+    if (((__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15) != 15) {
+        if (threadIdx.x == 0) flags[0] = 1;
+        return;
+    }
+
+    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const int g = lane / LN;                // accumulate stage: which of the G side-by-side entries
+    const int n = (lane % LN) * 4;          // accumulate stage: this lane's first column
+    const int my_r = (lane >> 4) / kGroupsPerRow;       // score stage: the row this lane's group scores entries of
+    const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
+
+    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
+    int pos[ROWS], end[ROWS];
+    int kc[ROWS];
+    float vc[ROWS];
+    float acc[ROWS][4];
+    unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int row = row0 + r;
+        pos[r] = row < M ? uniform(rowptr[row]) : 0;
+        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
+        const int j = pos[r] + lane;
+        const bool ok = j < end[r];
+        kc[r] = ok ? colidx[j] : 0x7fffffff;
+        vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+        acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.f;
+    }
+    float a[H][4];                          // pieces i16 (and 16 + i16) of this group's row of A, zero beyond D
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        a[h][0] = a[h][1] = a[h][2] = a[h][3] = 0.f;
+        if (row0 + my_r < M && (h * 16 + i16) * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + (h * 16 + i16) * 4, a[h]);
+    }
+
+    // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
+    const int n4 = N >> 2;                  // float4s per row of C
+    constexpr int kRow4 = 64 / G;
+    constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
+    constexpr int kPer = KT / kStep;
+    static_assert(KT % kStep == 0, "tile height must be a whole number of load rounds");
+    constexpr int kD4 = DMAX / 4;
+    constexpr int kPerB = (KT * kD4 + kTileThreads - 1) / kTileThreads;
+    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
+    float4 stage[kPer];
+    float4 stageb[kPerB];
+    const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
+    const bool my_col = my_c4 < n4;
+    const size_t my_off = (size_t)my_kk * n4 + my_c4;
+    const size_t step_off = (size_t)kStep * n4;
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        if (k0 + KT <= K) {
+#pragma unroll
+            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (my_col) {
+#pragma unroll
+                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
+            }
+        } else {                                      // last, partial tile
+#pragma unroll
+            for (int i = I0; i < I1; ++i) {
+                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+            }
+        }
+    };
+    auto issue_b = [&](int k0) {
+        const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
+        const int d4 = D >> 2;
+#pragma unroll
+        for (int i = 0; i < kPerB; ++i) {
+            const int e = i * kTileThreads + threadIdx.x;
+            const int kk = e / kD4, c4 = e % kD4;
+            stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
+        }
+    };
+    auto commit = [&]() {
+        float4 *dst = reinterpret_cast<float4 *>(ct);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        float4 *dstb = reinterpret_cast<float4 *>(bt);
+#pragma unroll
+        for (int i = 0; i < kPerB; ++i) {
+            const int e = i * kTileThreads + threadIdx.x;
+            if (e < KT * kD4) dstb[e] = stageb[i];
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using IPF = std::integral_constant<int, PF>;
+    using IEND = std::integral_constant<int, kPer>;
+    constexpr bool kAllAhead = PF == kPer;
+
+    if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
+    if constexpr (kAllAhead) issue_b(ks.kb);
+    for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
+        __syncthreads();                    // previous tile fully consumed
+        if constexpr (!kAllAhead) {
+            issue(k0, IPF{}, IEND{});
+            issue_b(k0);
+        }
+        commit();
+        __syncthreads();
+        if constexpr (PF > 0) {
+            if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
+                issue(k0 + KT, I0{}, IPF{});
+                if constexpr (kAllAhead) issue_b(k0 + KT);
+            }
+        }
+        const int kend = k0 + KT;
+        const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
+
+        // entries of this tile = leading lanes of each row's chunk with column < kend.  A row whose whole chunk
+        // lies in the tile gets its next chunk (a blocking load: dense rows only) and the tile goes round again
+        // for those rows.
+        bool fresh[ROWS];                   // this row's chunk has not been counted for this tile yet
+        bool moved[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            fresh[r] = true;
+            moved[r] = false;
+        }
+        for (;;) {
+        int full[ROWS];                     // ... how many of the chunk's 64
+        int most = 0;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            full[r] = fresh[r] ? __builtin_popcountll(__ballot(kc[r] < kend)) : 0;
+            most = full[r] > most ? full[r] : most;
+            if (fresh[r]) bad |= descending_lanes(kc[r]);
+        }
+        if (most == 0) break;
+        // the slots hold SL entries per row: lanes [part, part + SL) of the chunks at a time
+        for (int part = 0; part < most; part += SL) {
+            int cnts[ROWS];
+            int maxcnt = 0, my_cnt = 0;
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                int cnt = full[r] - part;
+                cnt = cnt < 0 ? 0 : (cnt < SL ? cnt : SL);
+                cnts[r] = cnt;
+                maxcnt = cnt > maxcnt ? cnt : maxcnt;
+                if (my_r == r) my_cnt = cnt;
+                if (lane >= part && lane < part + SL)
+                    ent[r * SL + lane - part] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+            }
+            for (int base = 0; base < maxcnt; base += kPass) {
+                // ---- score stage: this lane's entry of this pass
+                {
+                    const int idx = base + my_first;
+                    const bool on = idx < my_cnt;
+                    int2 *mine = ent + my_r * SL + (on ? idx : 0);
+                    const int2 kv = *mine;
+                    // byte address of piece i16 of the entry's row of B; lanes without an entry walk row 0 of the tile
+                    const unsigned row_b = (unsigned)(L::kCFloats * 4) + (on ? (unsigned)(kv.x - k0) * (unsigned)kBRowBytes : 0u) + i16 * 16;
+                    const char *base_a = reinterpret_cast<const char *>(lds) + row_b;
+                    const char *base_b = base_a - 256;
+                    float dot = 0.f;
+                    constexpr int GL = 4, NR = 16 * H, NG = NR / GL;     // reads: step s, half h -> number s * H + h
+                    float b[2][GL][4];
+                    auto read_group = [&](auto gc) {
+                        constexpr int gi = decltype(gc)::value;
+                        static_for<0, GL>([&](auto uc) {
+                            constexpr int q = gi * GL + decltype(uc)::value;
+                            constexpr int st = q / H, hh = q % H;
+                            // piece (i16 - st) mod 16 of half hh
+                            const char *p = (st == 0 ? base_a : ((i16 >= st ? base_b : base_a) + 16 * (16 - st))) + hh * 256;
+                            load_vec<4>(reinterpret_cast<const float *>(p), b[gi & 1][decltype(uc)::value]);
+                        });
+                    };
+                    read_group(std::integral_constant<int, 0>{});
+                    static_for<0, NG>([&](auto gc) {
+                        constexpr int gi = decltype(gc)::value;
+                        if constexpr (gi + 1 < NG) read_group(std::integral_constant<int, gi + 1>{});
+                        static_for<0, GL>([&](auto uc) {
+                            constexpr int u = decltype(uc)::value;
+                            constexpr int q = gi * GL + u;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) fma_row_rotated<q / H>(dot, a[q % H][c], b[gi & 1][u][c]);
+                        });
+                    });
+                    if (on) reinterpret_cast<int *>(mine)[1] = __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * dot);
+                }
+                // ---- accumulate stage: entries [base, base + kPass) of every row; group g takes entries
+                // t+g, t+G+g, t+2G+g, t+3G+g of each round
+#pragma unroll
+                for (int r = 0; r < ROWS; ++r) {
+                    const int2 *e = ent + r * SL;
+                    const int lim = cnts[r] < base + kPass ? cnts[r] : base + kPass;
+                    int t = base;
+                    for (; t + 4 * G <= lim; t += 4 * G) {
+                        int2 ks4[4];
+                        float c[4][4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) ks4[u] = e[t + u * G + g];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
+                                                                        ((unsigned)ks4[u].x * (unsigned)kRowBytes + lb)),
+                                        c[u]);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const float sv = __builtin_bit_cast(float, ks4[u].y);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) acc[r][v] = fmaf(sv, c[u][v], acc[r][v]);
+                        }
+                    }
+                    if (t < lim) {                  // last, partial round: lanes whose entry does not exist sit out
+                        int2 ks4[4];
+                        float c[4][4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const int idx = t + u * G + g;
+                            ks4[u] = e[idx < lim ? idx : base];
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
+                                                                        ((unsigned)ks4[u].x * (unsigned)kRowBytes + lb)),
+                                        c[u]);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            if (t + u * G + g < lim) {
+                                const float sv = __builtin_bit_cast(float, ks4[u].y);
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) acc[r][v] = fmaf(sv, c[u][v], acc[r][v]);
+                            }
+                        }
+                    }
+                }
+            }
+        }   // part
+
+        bool again = false;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            pos[r] += full[r];
+            moved[r] |= full[r] > 0;
+            fresh[r] = false;
+            if (full[r] == kWave) {
+                const int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                const bool okn = lane < end[r] - pos[r];
+                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
+                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                if (__builtin_amdgcn_readlane(kc[r], 0) < lastk) bad |= 1;   // descending across the chunk boundary
+                fresh[r] = true;
+                moved[r] = false;           // its look-ahead chunk is already the right one
+                again = true;
+            }
+        }
+        if (!again) break;
+        }   // rounds of this tile
+        // look-ahead chunks for the next tile, all requested here, after the arithmetic
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (moved[r]) {
+                const bool okn = lane < end[r] - pos[r];
+                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
+                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+            }
+        }
+    }
+    if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
+    // add the G partial rows of every row and store
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+#pragma unroll
+        for (int off = LN; off < kWave; off <<= 1)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
+        const int row = row0 + r;
+        if (row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
+    }
+}
+
 }  // namespace csrk

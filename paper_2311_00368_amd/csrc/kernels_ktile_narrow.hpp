@@ -1,4 +1,5 @@
-// LDS-tiled SPMM / FusedMM for narrow outputs (N <= 128): the paper's own widths, 32 and 128.
+// LDS-tiled SPMM for narrow outputs (N <= 128): the paper's own widths, 32 and 128.  (FusedMM for these
+// widths: fused_narrow_kernel in kernels_ktile_fused.hpp, which has the same accumulate stage.)
 //
 // Same scheme as ktile_kernel (a workgroup of 16 wavefronts owns 16*ROWS rows of S, sweeps K in
 // tiles staged in LDS, finds each row's entries of a tile as a prefix of a 64-entry look-ahead
@@ -22,44 +23,32 @@
 
 namespace csrk {
 
-// DMAX (FusedMM only): 64 or 128, the dot length the staging areas and the dot stage are laid out
-// for; D <= DMAX, shorter rows are zero-padded.
-template <int G, int KT, int ROWS, bool FUSED, int DMAX>
+template <int G, int KT>
 struct NarrowLds {
     static constexpr int kRowFloats = 256 / G;
     static constexpr int kCFloats = KT * kRowFloats;
-    static constexpr int kDStride = DMAX + 4;
-    static constexpr int kDFloats = FUSED ? KT * kDStride : 0;
-    static constexpr int kAFloats = FUSED ? kTileWaves * ROWS * DMAX : 0;
-    static constexpr int kEntFloats = kTileWaves * 2 * kWave * 2;
-    static constexpr int kBytes = (kCFloats + kDFloats + kAFloats + kEntFloats) * 4;
+    static constexpr int kEntFloats = kTileWaves * 2 * kWave * 2;     // two 64-entry slots of pairs per wavefront
+    static constexpr int kBytes = (kCFloats + kEntFloats) * 4;
 };
 
-template <int G, int KT, int ROWS, bool FUSED, int DMAX, int PF>
+template <int G, int KT, int ROWS, int PF>
 __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
-    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
-    using L = NarrowLds<G, KT, ROWS, FUSED, DMAX>;
+    int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
+    float *partial) {
+    using L = NarrowLds<G, KT>;
     constexpr int LN = kWave / G;           // lanes per entry
-    constexpr int LQ = DMAX / 16;           // FUSED dot stage: lanes per entry (16 floats each)
-    constexpr int ER = kWave / LQ;          // FUSED dot stage: entries per round
-    constexpr int kD4 = DMAX / 4;           // float4s per staged row of A / B
     constexpr int kRowBytes = L::kRowFloats * 4;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!ktile_ok(flags)) return;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;
-    float *bt = lds + L::kCFloats;
-    float *at = bt + L::kDFloats;
-    int2 *ent = reinterpret_cast<int2 *>(at + L::kAFloats) + wave * (2 * kWave);
+    int2 *ent = reinterpret_cast<int2 *>(lds + L::kCFloats) + wave * (2 * kWave);
 
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int g = lane / LN;                // which of the G side-by-side entries
     const int n = (lane % LN) * 4;          // this lane's first column
-    const int q16 = (lane % LQ) * 16;       // FUSED dot stage: 16-float slice of the dot length
-    const int ei = lane / LQ;               // FUSED dot stage: which of ER side-by-side entries
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
     int pos[ROWS], end[ROWS];
@@ -82,20 +71,11 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         vc2[r] = ok2 ? (vals ? vals[j + kWave] : 1.f) : 0.f;
         acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.f;
     }
-    if constexpr (FUSED) {
-        const int brow0 = blockIdx.x * (kTileWaves * ROWS);
-        for (int e = threadIdx.x; e < kTileWaves * ROWS * DMAX; e += kTileThreads) {
-            const int rr = e / DMAX, cc = e % DMAX;
-            at[e] = (brow0 + rr < M && cc < D) ? A[(size_t)(brow0 + rr) * D + cc] : 0.f;
-        }
-    }
-
     const int n4 = N >> 2;
     constexpr int kRow4 = 64 / G;                       // float4s per tile row
     constexpr int kStep = kTileThreads / kRow4;         // tile rows per round of loads
     constexpr int kPer = KT / kStep;
     static_assert(KT % kStep == 0, "tile height must be a whole number of load rounds");
-    constexpr int kPerB = FUSED ? (KT * kD4 + kTileThreads - 1) / kTileThreads : 1;
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
     const bool my_col = my_c4 < n4;
     const size_t my_off = (size_t)my_kk * n4 + my_c4;
@@ -103,7 +83,6 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 
     static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
     float4 stage[kPer];
-    float4 stageb[kPerB];
     // loads number [I0, I1) of this thread for the C tile that starts at column k0
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
@@ -123,52 +102,23 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
             }
         }
     };
-    auto issue_b = [&](int k0) {
-        if constexpr (FUSED) {
-            const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
-            const int d4 = D >> 2;
-#pragma unroll
-            for (int i = 0; i < kPerB; ++i) {
-                const int e = i * kTileThreads + threadIdx.x;
-                const int kk = e / kD4, c4 = e % kD4;
-                stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
-            }
-        }
-    };
     auto commit = [&]() {
         float4 *dst = reinterpret_cast<float4 *>(ct);
 #pragma unroll
         for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
-        if constexpr (FUSED) {
-            float4 *dstb = reinterpret_cast<float4 *>(bt);
-#pragma unroll
-            for (int i = 0; i < kPerB; ++i) {
-                const int e = i * kTileThreads + threadIdx.x;
-                if (e < KT * kD4) dstb[(e / kD4) * (L::kDStride / 4) + (e % kD4)] = stageb[i];
-            }
-        }
     };
     using I0 = std::integral_constant<int, 0>;
     using IPF = std::integral_constant<int, PF>;
     using IEND = std::integral_constant<int, kPer>;
-    constexpr bool kAllAhead = PF == kPer;      // then FusedMM's B tile is prefetched as well
 
     if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
-    if constexpr (kAllAhead) issue_b(ks.kb);
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
-        if constexpr (!kAllAhead) {
-            issue(k0, IPF{}, IEND{});
-            issue_b(k0);
-        }
+        if constexpr (PF < kPer) issue(k0, IPF{}, IEND{});
         commit();
         __syncthreads();
         if constexpr (PF > 0) {
-            if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
-                issue(k0 + KT, I0{}, IPF{});
-                if constexpr (kAllAhead) issue_b(k0 + KT);
-            }
+            if (k0 + KT < ks.ke) issue(k0 + KT, I0{}, IPF{});   // lands while this tile is being worked on
         }
         const int kend = k0 + KT;
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
@@ -178,30 +128,6 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         auto process = [&](int r, int slot, int kreg, float vreg, int cnt) {
             int2 *e = ent + slot * kWave;
             e[lane] = make_int2(kreg, __builtin_bit_cast(int, vreg));
-            if constexpr (FUSED) {
-                // dot stage, as in ktile_kernel: ER entries a round, LQ lanes x 16 floats per entry
-                float av[4][4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) load_vec<4>(at + (wave * ROWS + r) * DMAX + q16 + 4 * i, av[i]);
-                for (int t = 0; t < cnt; t += ER) {
-                    const int idx = t + ei;
-                    const bool on = idx < cnt;
-                    const int2 kv = e[on ? idx : 0];
-                    const float *brow = bt + (kv.x - k0) * L::kDStride + q16;
-                    float b[4][4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) load_vec<4>(brow + 4 * i, b[i]);
-                    float part = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) part = fmaf(av[i][v], b[i][v], part);
-                    part = group_sum<LQ>(part);
-                    if (on && (lane % LQ) == 0)
-                        reinterpret_cast<int *>(e)[2 * idx + 1] =
-                            __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
-                }
-            }
             // accumulate stage: group g takes entries t+g, t+G+g, t+2G+g, t+3G+g of each round
             int t = 0;
             for (; t + 4 * G <= cnt; t += 4 * G) {
