@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
             bad |= descending_lanes(kc[r]);
             if (r + 1 < ROWS)
                 ent[((r + 1) & 1) * kWave + lane] = make_int2(kc[r + 1], __builtin_bit_cast(int, vc[r + 1]));
-            const int2 *e = ent + (r & 1) * kWave;
+            const int2 *e = ent + (r & 1) * kWave;     // this row's slot
             auto batch = [&](int t, auto count) {
                 constexpr int CNT = decltype(count)::value;
                 float c[CNT][T][4];
@@ -304,35 +304,59 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                         for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(sv, c[u][tt][v], acc[r][tt][v]);
                 }
             };
-            int t = 0;
-            for (; t + 4 <= cnt; t += 4) batch(t, std::integral_constant<int, 4>{});
-            // the last 1-3 entries as a pair and a single: two plain ifs keep the accumulators in place, where a
-            // switch over the three cases made the compiler copy them in and out
-            if (cnt - t >= 2) {
-                batch(t, std::integral_constant<int, 2>{});
-                t += 2;
-            }
-            if (cnt - t >= 1) batch(t, std::integral_constant<int, 1>{});
-            pos[r] += cnt;
-            if (cnt == kWave) {
-                // rare (a row with 64 or more entries inside one tile): finish the tile's
-                // entries of this row one at a time straight from memory
-                int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
-                while (pos[r] < end[r]) {
-                    const int k = uniform(colidx[pos[r]]);
-                    if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
-                    lastk = k;
-                    if (k >= kend) break;
-                    const float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
-                    const float *crow = ct + (k - k0) * L::kRowFloats + n;
+            // all entries [0, cnt) of the slot, in batches of 4
+            auto run = [&](int cnt) {
+                int t = 0;
+                for (; t + 4 <= cnt; t += 4) batch(t, std::integral_constant<int, 4>{});
+                // the last 1-3 entries as a pair and a single: two plain ifs keep the accumulators in place, where a
+                // switch over the three cases made the compiler copy them in and out
+                if (cnt - t >= 2) {
+                    batch(t, std::integral_constant<int, 2>{});
+                    t += 2;
+                }
+                if (cnt - t >= 1) batch(t, std::integral_constant<int, 1>{});
+            };
+            if constexpr (KT > kWave) {
+                // A row whose whole chunk lies in the tile (64 or more entries of it in one tile: dense rows) gets its
+                // next chunk with a blocking load and goes through the same slot again.
+                for (int c = cnt;;) {
+                    run(c);
+                    pos[r] += c;
+                    if (__builtin_expect(c < kWave || pos[r] >= end[r], 1)) break;
+                    const int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                    const bool okn = lane < end[r] - pos[r];
+                    kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
+                    vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                    bad |= descending_lanes(kc[r]);
+                    if (__builtin_amdgcn_readlane(kc[r], 0) < lastk) bad |= 1;     // descending across the chunk boundary
+                    c = __builtin_popcountll(__ballot(kc[r] < kend));
+                    if (c == 0) break;
+                    ent[(r & 1) * kWave + lane] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+                }
+            } else {
+                // A tile of at most 64 columns holds more than a chunk of one row only if columns repeat, and a
+                // full chunk only for a dense row: the simple continuation, one entry at a time, is enough (and
+                // keeps this, the 512-wide kernel, free of the loop above, which costs it 2 %).
+                run(cnt);
+                pos[r] += cnt;
+                if (cnt == kWave) {
+                    int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                    while (pos[r] < end[r]) {
+                        const int k = uniform(colidx[pos[r]]);
+                        if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
+                        lastk = k;
+                        if (k >= kend) break;
+                        const float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
+                        const float *crow = ct + (k - k0) * L::kRowFloats + n;
 #pragma unroll
-                    for (int tt = 0; tt < T; ++tt) {
-                        float c[4];
-                        load_vec<4>(crow + tt * 256, c);
+                        for (int tt = 0; tt < T; ++tt) {
+                            float c[4];
+                            load_vec<4>(crow + tt * 256, c);
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
+                            for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
+                        }
+                        ++pos[r];
                     }
-                    ++pos[r];
                 }
             }
         }

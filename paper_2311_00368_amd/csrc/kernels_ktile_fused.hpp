@@ -171,16 +171,27 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         // large column numbers wrap instead of overflowing (the sum below is always a small offset)
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
 
-        // entries of this tile = leading lanes of each row's chunk with column < kend
+        // entries of this tile = leading lanes of each row's chunk with column < kend.  A row whose whole chunk
+        // lies in the tile gets its next chunk (a blocking load: dense rows only) and the tile goes round again
+        // for those rows.
+        bool fresh[ROWS];                   // this row's chunk has not been counted for this tile yet
+        bool moved[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            fresh[r] = true;
+            moved[r] = false;
+        }
+        for (;;) {
         int full[ROWS];                     // ... how many of the chunk's 64
         int most = 0;
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            full[r] = __builtin_popcountll(__ballot(kc[r] < kend));
+            full[r] = fresh[r] ? __builtin_popcountll(__ballot(kc[r] < kend)) : 0;
             most = full[r] > most ? full[r] : most;
             // order check on the chunk, here where it is first used
-            bad |= descending_lanes(kc[r]);
+            if (fresh[r]) bad |= descending_lanes(kc[r]);
         }
+        if (most == 0) break;
         // the slots hold SL entries per row: lanes [part, part + SL) of the chunks at a time (one part unless a
         // row has more than SL entries in this tile)
         for (int part = 0; part < most; part += SL) {
@@ -279,42 +290,67 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
 
         }   // part
 
+        if constexpr (KT <= kWave) {
+            // A tile of at most 64 columns holds more than a chunk of one row only if columns repeat, and a full
+            // chunk only for a dense row: the simple continuation, one entry at a time, is enough (and keeps the
+            // 512-wide kernel free of the bookkeeping of the rounds, which costs it 2 %).
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            pos[r] += full[r];
-            if (full[r] == kWave) {
-                // rare (a row with 64 or more entries inside one tile): finish the tile's entries of this row
-                // one at a time straight from memory; the 16 lanes of the row's first group hold the row of A
-                int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
-                while (pos[r] < end[r]) {
-                    const int k = uniform(colidx[pos[r]]);
-                    if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
-                    lastk = k;
-                    if (k >= kend) break;
-                    float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
-                    float bq[4];
-                    load_vec<4>(bt + (k - k0) * 64 + i16 * 4, bq);
-                    float part = a[0] * bq[0];
+            for (int r = 0; r < ROWS; ++r) {
+                pos[r] += full[r];
+                moved[r] = full[r] > 0;
+                if (full[r] == kWave) {
+                    int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                    while (pos[r] < end[r]) {
+                        const int k = uniform(colidx[pos[r]]);
+                        if (k < lastk) bad |= 1;     // descending across the chunk boundary or inside this run
+                        lastk = k;
+                        if (k >= kend) break;
+                        float s = vals ? __builtin_bit_cast(float, uniform(__builtin_bit_cast(int, vals[pos[r]]))) : 1.f;
+                        float bq[4];
+                        load_vec<4>(bt + (k - k0) * 64 + i16 * 4, bq);
+                        float part = a[0] * bq[0];
 #pragma unroll
-                    for (int v = 1; v < 4; ++v) part = fmaf(a[v], bq[v], part);
-                    part = group_sum<16>(part);
-                    s *= readlane_f(part, r * kGroupsPerRow * 16);
-                    const float *crow = ct + (k - k0) * L::kRowFloats + n;
+                        for (int v = 1; v < 4; ++v) part = fmaf(a[v], bq[v], part);
+                        part = group_sum<16>(part);           // the 16 lanes of the row's first group hold its row of A
+                        s *= readlane_f(part, r * kGroupsPerRow * 16);
+                        const float *crow = ct + (k - k0) * L::kRowFloats + n;
 #pragma unroll
-                    for (int tt = 0; tt < T; ++tt) {
-                        float c[4];
-                        load_vec<4>(crow + tt * 256, c);
+                        for (int tt = 0; tt < T; ++tt) {
+                            float c[4];
+                            load_vec<4>(crow + tt * 256, c);
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
+                            for (int v = 0; v < 4; ++v) acc[r][tt][v] = fmaf(s, c[v], acc[r][tt][v]);
+                        }
+                        ++pos[r];
                     }
-                    ++pos[r];
                 }
             }
+            break;
+        } else {
+            bool again = false;
+    #pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                pos[r] += full[r];
+                moved[r] |= full[r] > 0;
+                fresh[r] = false;
+                if (full[r] == kWave) {
+                    const int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
+                    const bool okn = lane < end[r] - pos[r];
+                    kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
+                    vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                    if (__builtin_amdgcn_readlane(kc[r], 0) < lastk) bad |= 1;   // descending across the chunk boundary
+                    fresh[r] = true;
+                    moved[r] = false;           // its look-ahead chunk is already the right one
+                    again = true;
+                }
+            }
+            if (__builtin_expect(!again, 1)) break;
         }
+        }   // rounds of this tile
         // look-ahead chunks for the next tile, all requested here, after the arithmetic
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            if (full[r] > 0) {
+            if (moved[r]) {
                 const bool okn = lane < end[r] - pos[r];
                 kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
                 vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
@@ -628,7 +664,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
                 again = true;
             }
         }
-        if (!again) break;
+        if (__builtin_expect(!again, 1)) break;
         }   // rounds of this tile
         // look-ahead chunks for the next tile, all requested here, after the arithmetic
 #pragma unroll
