@@ -227,10 +227,10 @@ void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32
 // time): 4, 2 or 1.  More rows spread the per-tile work (staging, barriers) over more entries, but the grid
 // runs in rounds of `CUs` workgroups and a last round that is mostly empty costs as much as a full one:
 // pick the count with the least rounds x (rows + one half row's worth of per-tile work); ties go to more rows.
-int tile_rows_for(const DeviceState &d, int M) {
-    int best = 4;
+int tile_rows_for(const DeviceState &d, int M, int max_rows = 4) {
+    int best = max_rows;
     long long best_cost = -1;
-    for (int rows = 4; rows >= 1; rows >>= 1) {
+    for (int rows = max_rows; rows >= 1; rows >>= 1) {
         const long long blocks = ((long long)M + kTileWaves * rows - 1) / (kTileWaves * rows);
         const long long rounds = (blocks + d.cus - 1) / d.cus;
         const long long cost = rounds * (2 * rows + 1);
@@ -269,17 +269,23 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
-float narrow_min_density(const DeviceState &d, int M, int N) {
+// Density from which the narrow tiled kernels beat the general path (measured on a grid of M, K, N, density).
+// It depends mostly on how big the gathered dense operand is: the general path gathers at L2 speed while K x N
+// floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not care.
+float narrow_min_density(int K, int N, bool fused) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
-    if (N <= 32) return (long long)M >= 96ll * d.cus ? 0.15f : kNarrowMinDensity;   // general path wins at 10 %
-    if ((long long)M >= 96ll * d.cus) return 0.05f;        // many rows per wavefront amortise the staging
-    if (N > 64 && (long long)M >= 32ll * d.cus) return 0.08f;
-    return kNarrowMinDensity;
+    const long long dense_bytes = (long long)K * N * 4;
+    if (N <= 32) return fused ? kNarrowMinDensity : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
+    if (dense_bytes >= (8ll << 20)) return 0.04f;
+    if (dense_bytes >= (4ll << 20)) return 0.06f;
+    if (dense_bytes >= (2ll << 20)) return 0.09f;
+    return 0.15f;
 }
-float sddmm_min_density(const DeviceState &d, int M, int D) {
+// ... and the tiled SDDMM kernel (64 lanes = 64 entries of one row: short segments waste lanes)
+float sddmm_min_density(int K, int D) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
-    if (D <= 64) return kTileMinDensity;
-    return (long long)M >= 64ll * d.cus ? 0.05f : 0.15f;    // 64 lanes = 64 entries: short segments waste lanes
+    if (D <= 64) return 0.05f;
+    return (long long)K * D * 4 >= (8ll << 20) ? 0.05f : 0.09f;
 }
 
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
@@ -346,13 +352,16 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
                                     const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
     // (cutting K into ranges for small M, as SPMM and FusedMM do, measured no gain here: the tile is 288-1152
     // rows high, so a K of a few thousand leaves too few tiles per range)
-    // rows per wavefront: as many as still leave every CU a workgroup
-    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
-    // (the 128-wide kernel keeps two rows of A per lane in registers: four would spill)
-    if constexpr (DMAX <= 64)
-        if (blocks1 >= 4ll * d.cus) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
-    if (blocks1 >= 2ll * d.cus) return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
-    return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
+    // rows per wavefront by the same rule as SPMM / FusedMM (the 128-wide kernel takes at most two: its score loop
+    // is twice as long and four rows would spill)
+    constexpr int kMaxRows = DMAX <= 64 ? 4 : 2;
+    switch (tile_rows_for(d, M, kMaxRows)) {
+        case 4:
+            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
+            [[fallthrough]];
+        case 2: return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
+        default: return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
+    }
 }
 
 csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, float min_density) {
@@ -628,7 +637,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     if (vec4 && narrow_shape_ok(*d, M, N, false)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(K, N, false))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
@@ -677,7 +686,7 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     CallRecord rec(2, stream);
     if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(*d, M, D))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(K, D))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
@@ -722,7 +731,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N, true)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(*d, M, N))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(K, N, true))) return s;
         gate = tile_flags(*d);
         rec.begin();
         csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
