@@ -215,10 +215,9 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
     return false;
 }
 
-void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32_t *gate) {
-    const int ytiles = (N + kBlockThreads - 1) / kBlockThreads;
-    hipLaunchKernelGGL(combine_heads_kernel, dim3(d.workers, ytiles < 8 ? ytiles : 8), dim3(kBlockThreads), 0, st, N,
-                       d.workers, O, d.head, d.head_row, gate);
+void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32_t *gate, bool vec4) {
+    hipLaunchKernelGGL(combine_heads_kernel, dim3((d.workers + kWavesPerBlock - 1) / kWavesPerBlock),
+                       dim3(kBlockThreads), 0, st, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0);
 }
 
 // --- LDS-tiled path ---------------------------------------------------------------------
@@ -665,7 +664,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
 #undef CSRK_SPMM_CASE
     rec.end();
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O, gate);
+    launch_combine(*d, stream, N, O, gate, vec4);
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
@@ -759,7 +758,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     rec.end();
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O, gate);
+    launch_combine(*d, stream, N, O, gate, nvec4);
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }

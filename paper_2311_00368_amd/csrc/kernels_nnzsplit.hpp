@@ -169,23 +169,41 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
 }
 
 // O[r, :] += head[w, :] + head[w+1, :] + ... for the run of workers whose head is row r.
-// One thread per output column; only the first worker of a run does the adding, in
-// worker order, so sums are reproducible.
+// One wavefront per worker, lanes over the output columns; only the first worker of a run does the
+// adding, in worker order, so sums are reproducible.  `vec4`: N is a multiple of 4 and O and head
+// are 16-byte aligned.
 __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int W, float *__restrict__ O,
                                                                        const float *__restrict__ head,
                                                                        const int32_t *__restrict__ head_row,
-                                                                       const int32_t *__restrict__ gate) {
+                                                                       const int32_t *__restrict__ gate, int vec4) {
     if (gate && ktile_ok(gate)) return;
-    const int w = blockIdx.x;
-    const int r = head_row[w];
+    const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (w >= W) return;
+    const int r = uniform(head_row[w]);
     if (r < 0) return;
-    if (w > 0 && head_row[w - 1] == r) return;
+    if (w > 0 && uniform(head_row[w - 1]) == r) return;
     int wend = w + 1;
-    while (wend < W && head_row[wend] == r) ++wend;
-    for (int n = blockIdx.y * blockDim.x + threadIdx.x; n < N; n += gridDim.y * blockDim.x) {
-        float s = O[(size_t)r * N + n];
-        for (int ww = w; ww < wend; ++ww) s += head[(size_t)ww * N + n];
-        O[(size_t)r * N + n] = s;
+    while (wend < W && uniform(head_row[wend]) == r) ++wend;
+    const int lane = lane_id();
+    float *orow = O + (size_t)r * N;
+    if (vec4) {
+        for (int n = lane * 4; n < N; n += kWave * 4) {
+            float s[4];
+            load_vec<4>(orow + n, s);
+            for (int ww = w; ww < wend; ++ww) {
+                float h[4];
+                load_vec<4>(head + (size_t)ww * N + n, h);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) s[v] += h[v];
+            }
+            store_vec<4>(orow + n, s);
+        }
+    } else {
+        for (int n = lane; n < N; n += kWave) {
+            float s = orow[n];
+            for (int ww = w; ww < wend; ++ww) s += head[(size_t)ww * N + n];
+            orow[n] = s;
+        }
     }
 }
 
