@@ -67,9 +67,19 @@ __global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const i
                                                           float min_density, int32_t *flags) {
     __shared__ int wave_max[16];
     int longest = 0;
-    for (int r = threadIdx.x; r < M; r += blockDim.x) {
-        const int len = rowptr[r + 1] - rowptr[r];
-        longest = len > longest ? len : longest;
+    constexpr int U = 8;                     // row lengths requested together per thread
+    for (long long r0 = threadIdx.x; r0 < M; r0 += blockDim.x * U) {
+        int lo[U], hi[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // unconditional loads (a row past the end repeats the last row): conditional ones are waited for one by one
+            long long r = r0 + u * (long long)blockDim.x;
+            r = r < M ? r : M - 1;
+            lo[u] = rowptr[r];
+            hi[u] = rowptr[r + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) longest = hi[u] - lo[u] > longest ? hi[u] - lo[u] : longest;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
