@@ -30,8 +30,8 @@ namespace csrk {
 constexpr int kBlockThreads = 256;
 constexpr int kWavesPerBlock = kBlockThreads / kWave;
 
-// f(t) for t = t0, t0+stride, ... < t1, in blocks of U statically unrolled calls (so the
-// U gathers of a block are all in flight together) and a one-at-a-time remainder.
+// f(t) for t = t0, t0+stride, ... < t1, in blocks of U statically unrolled calls and a
+// one-at-a-time remainder.
 template <int U, typename F>
 __device__ __forceinline__ void for_unrolled(int t0, int t1, int stride, F &&f) {
     int t = t0;
@@ -43,6 +43,70 @@ __device__ __forceinline__ void for_unrolled(int t0, int t1, int stride, F &&f) 
 }
 
 // ---------------------------------------------------------------------------------
+// Gather-and-accumulate over the entries [t0, t1) of one chunk (entry t: column in lane t
+// of `kc`, scale in lane t of `sc`):
+//     acc[tt][v] += sc_t * Mat[kc_t, n + tt*TW + v]
+// A group of LG lanes covers the dense width, NPAR = 64/LG entries go side by side.
+//
+// The gathers of a block of U steps are all requested before the first is used.  That
+// only happens if no load sits under a condition (the compiler waits for such a load on
+// the spot, which would put the U gathers one after the other): every lane loads in every
+// step, with columns beyond N moved to column 0 and steps beyond the chunk's end moved
+// to entry t0, and the condition is applied to the multiply-adds instead.
+// ---------------------------------------------------------------------------------
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void gather_axpy(int kc, float sc, int t0, int t1, const float *__restrict__ Mat, int N,
+                                            int n, float (&acc)[T][VEC]) {
+    constexpr int NPAR = kWave / LG;
+    constexpr int TW = LG * VEC;
+    constexpr int U = NPAR == 1 ? 8 : 4;         // steps per full block
+    constexpr int UR = NPAR == 1 ? 4 : 2;        // steps per block of the remainder
+    const int g = lane_id() / LG;
+    int off[T];
+    bool col_ok[T];
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+        col_ok[tt] = n + tt * TW < N;
+        off[tt] = col_ok[tt] ? n + tt * TW : 0;
+    }
+    auto block = [&](int t, auto uc) {
+        constexpr int UU = decltype(uc)::value;
+        float s[UU];
+        bool on[UU];
+        float b[UU][T][VEC];
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+            const int idx = t + u * NPAR + g;
+            on[u] = idx >= t0 && idx < t1;
+            const int src = on[u] ? idx : t0;
+            int k;
+            if constexpr (NPAR == 1) {
+                const int su = uniform(src);
+                k = __builtin_amdgcn_readlane(kc, su);
+                s[u] = readlane_f(sc, su);
+            } else {
+                k = __shfl(kc, src);
+                s[u] = __shfl(sc, src);
+            }
+            const float *row = Mat + (size_t)k * N;
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) load_vec<VEC>(row + off[tt], b[u][tt]);
+        }
+#pragma unroll
+        for (int u = 0; u < UU; ++u)
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt)
+                if (on[u] && col_ok[tt]) {
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(s[u], b[u][tt][v], acc[tt][v]);
+                }
+    };
+    int t = t0 - (t0 % NPAR);
+    for (; t + U * NPAR <= t1; t += U * NPAR) block(t, std::integral_constant<int, U>{});
+    for (; t < t1; t += UR * NPAR) block(t, std::integral_constant<int, UR>{});
+}
+
+// ---------------------------------------------------------------------------------
 // SPMM segment: acc[t][v] += sum_{j in [s0,s1)} vals[j] * Bmat[colidx[j], n + t*TW + v]
 // ---------------------------------------------------------------------------------
 template <int VEC, int LG, int T>
@@ -50,10 +114,7 @@ __device__ __forceinline__ void spmm_segment(int s0, int s1, const int32_t *__re
                                              const float *__restrict__ vals,
                                              const float *__restrict__ Bmat, int N, int n,
                                              float (&acc)[T][VEC]) {
-    constexpr int NPAR = kWave / LG;
-    constexpr int TW = LG * VEC;
     const int lane = lane_id();
-    const int g = lane / LG;
     if (s1 <= s0) return;
     int base = s0 & ~(kWave - 1);
     int j = base + lane;
@@ -68,40 +129,7 @@ __device__ __forceinline__ void spmm_segment(int s0, int s1, const int32_t *__re
         const float vn = okn ? (vals ? vals[jn] : 1.f) : 0.f;
         const int t0 = s0 > base ? s0 - base : 0;
         const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
-        if constexpr (NPAR == 1) {
-            for_unrolled<8>(t0, t1, 1, [&](int t) {
-                const int k = __builtin_amdgcn_readlane(kc, t);
-                const float s = readlane_f(vc, t);
-                const float *brow = Bmat + (size_t)k * N + n;
-#pragma unroll
-                for (int tt = 0; tt < T; ++tt) {
-                    if (n + tt * TW < N) {
-                        float b[VEC];
-                        load_vec<VEC>(brow + tt * TW, b);
-#pragma unroll
-                        for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(s, b[v], acc[tt][v]);
-                    }
-                }
-            });
-        } else {
-            for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
-                const int idx = t + g;
-                const int k = __shfl(kc, idx);
-                const float s = __shfl(vc, idx);
-                if (idx >= t0 && idx < t1) {
-                    const float *brow = Bmat + (size_t)k * N + n;
-#pragma unroll
-                    for (int tt = 0; tt < T; ++tt) {
-                        if (n + tt * TW < N) {
-                            float b[VEC];
-                            load_vec<VEC>(brow + tt * TW, b);
-#pragma unroll
-                            for (int v = 0; v < VEC; ++v) acc[tt][v] = fmaf(s, b[v], acc[tt][v]);
-                        }
-                    }
-                }
-            });
-        }
+        gather_axpy<VEC, LG, T>(kc, vc, t0, t1, Bmat, N, n, acc);
         kc = kn;
         vc = vn;
     }
@@ -221,24 +249,54 @@ __device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float 
     constexpr int TW = LG * VEC;
     const int lane = lane_id();
     const int g = lane / LG;
-    for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
-        const int idx = t + g;
-        const int k = (NPAR == 1) ? __builtin_amdgcn_readlane(kc, t) : __shfl(kc, idx);
-        const bool act = idx >= t0 && idx < t1;
-        float part = 0.f;
-        if (act) {
-            const float *brow = Bmat + (size_t)k * D + d;
-            if constexpr (T > 0) {
+    if constexpr (T > 0) {
+        // Blocks of U steps whose gathers are all requested before the first dot product starts; loads in every
+        // lane and step, conditions on the arithmetic only (see gather_axpy).
+        constexpr int U = 4, UR = 2;
+        int off[T];
+        bool col_ok[T];
 #pragma unroll
-                for (int tt = 0; tt < T; ++tt) {
-                    if (d + tt * TW < D) {
-                        float b[VEC];
-                        load_vec<VEC>(brow + tt * TW, b);
+        for (int tt = 0; tt < T; ++tt) {
+            col_ok[tt] = d + tt * TW < D;
+            off[tt] = col_ok[tt] ? d + tt * TW : 0;
+        }
+        auto block = [&](int t, auto uc) {
+            constexpr int UU = decltype(uc)::value;
+            float b[UU][T][VEC];
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) part = fmaf(a[tt][v], b[v], part);
+            for (int u = 0; u < UU; ++u) {
+                const int idx = t + u * NPAR + g;
+                const int src = (idx >= t0 && idx < t1) ? idx : t0;
+                const int k = (NPAR == 1) ? __builtin_amdgcn_readlane(kc, uniform(src)) : __shfl(kc, src);
+                const float *brow = Bmat + (size_t)k * D;
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt) load_vec<VEC>(brow + off[tt], b[u][tt]);
+            }
+#pragma unroll
+            for (int u = 0; u < UU; ++u) {
+                const int idx = t + u * NPAR + g;
+                float part = 0.f;
+#pragma unroll
+                for (int tt = 0; tt < T; ++tt)
+                    if (col_ok[tt]) {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) part = fmaf(a[tt][v], b[u][tt][v], part);
                     }
-                }
-            } else {
+                part = group_sum<LG>(part);
+                if (idx >= t0 && idx < t1 && (lane % LG) == 0) slot[idx] = part;
+            }
+        };
+        int t = t0 - (t0 % NPAR);
+        for (; t + U * NPAR <= t1; t += U * NPAR) block(t, std::integral_constant<int, U>{});
+        for (; t < t1; t += UR * NPAR) block(t, std::integral_constant<int, UR>{});
+    } else {
+        for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
+            const int idx = t + g;
+            const int k = (NPAR == 1) ? __builtin_amdgcn_readlane(kc, t) : __shfl(kc, idx);
+            const bool act = idx >= t0 && idx < t1;
+            float part = 0.f;
+            if (act) {
+                const float *brow = Bmat + (size_t)k * D + d;
                 for (int dd = 0; d + dd < D; dd += TW) {
                     float b[VEC], av[VEC];
                     load_vec<VEC>(brow + dd, b);
@@ -247,10 +305,10 @@ __device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float 
                     for (int v = 0; v < VEC; ++v) part = fmaf(av[v], b[v], part);
                 }
             }
-        }
-        part = group_sum<LG>(part);
-        if (act && (lane % LG) == 0) slot[idx] = part;
-    });
+            part = group_sum<LG>(part);
+            if (act && (lane % LG) == 0) slot[idx] = part;
+        });
+    }
 }
 
 template <int VEC, int LG, int T>
@@ -323,48 +381,6 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
 // them from there; scores never reach device memory (Algorithm 3's `arow`).
 // Dot stage uses (VD, LD, TD) over D, the accumulate stage (VN, LN, TN) over N.
 // ---------------------------------------------------------------------------------
-template <int VN, int LN, int TN>
-__device__ __forceinline__ void saxpy_chunk(int kc, float sc, int t0, int t1, const float *__restrict__ Cmat,
-                                            int N, int n, float (&acc)[TN][VN]) {
-    constexpr int NPAR = kWave / LN;
-    constexpr int TW = LN * VN;
-    const int g = lane_id() / LN;
-    if constexpr (NPAR == 1) {
-        for_unrolled<8>(t0, t1, 1, [&](int t) {
-            const int k = __builtin_amdgcn_readlane(kc, t);
-            const float s = readlane_f(sc, t);
-            const float *crow = Cmat + (size_t)k * N + n;
-#pragma unroll
-            for (int tt = 0; tt < TN; ++tt) {
-                if (n + tt * TW < N) {
-                    float c[VN];
-                    load_vec<VN>(crow + tt * TW, c);
-#pragma unroll
-                    for (int v = 0; v < VN; ++v) acc[tt][v] = fmaf(s, c[v], acc[tt][v]);
-                }
-            }
-        });
-    } else {
-        for_unrolled<4>(t0 - (t0 % NPAR), t1, NPAR, [&](int t) {
-            const int idx = t + g;
-            const int k = __shfl(kc, idx);
-            const float s = __shfl(sc, idx);
-            if (idx >= t0 && idx < t1) {
-                const float *crow = Cmat + (size_t)k * N + n;
-#pragma unroll
-                for (int tt = 0; tt < TN; ++tt) {
-                    if (n + tt * TW < N) {
-                        float c[VN];
-                        load_vec<VN>(crow + tt * TW, c);
-#pragma unroll
-                        for (int v = 0; v < VN; ++v) acc[tt][v] = fmaf(s, c[v], acc[tt][v]);
-                    }
-                }
-            }
-        });
-    }
-}
-
 template <int VD, int LD, int TD, int VN, int LN, int TN>
 __device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int32_t *__restrict__ colidx,
                                               const float *__restrict__ vals, const float *__restrict__ A,
@@ -386,7 +402,7 @@ __device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int
         __builtin_amdgcn_wave_barrier();
         const float sc = ok ? vc * slot[lane] : 0.f;
         __builtin_amdgcn_wave_barrier();
-        saxpy_chunk<VN, LN, TN>(kc, sc, t0, t1, Cmat, N, n, acc);
+        gather_axpy<VN, LN, TN>(kc, sc, t0, t1, Cmat, N, n, acc);
     }
 }
 
