@@ -275,7 +275,7 @@ float narrow_min_density(int K, int N, bool fused) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const long long dense_bytes = (long long)K * N * 4;
     if (N <= 32) return fused ? kNarrowMinDensity : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
-    if (dense_bytes >= (8ll << 20)) return 0.04f;
+    if (dense_bytes >= (8ll << 20)) return 0.03f;
     if (dense_bytes >= (4ll << 20)) return 0.06f;
     if (dense_bytes >= (2ll << 20)) return 0.09f;
     return 0.15f;
@@ -293,11 +293,13 @@ bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     if (N % 4 != 0 || N > 512 || N <= 128) return mode == 2 && N % 4 == 0 && N <= 512;
     if (mode == 2) return true;
     // Measured cross-over with the general path (whose gathers run at L2 speed while the dense operand fits an
-    // XCD's L2 and collapse beyond): a dense operand of 4 MB or more with at least 1024 rows, or 2 MB with 4096.
-    // Small M is handled by cutting K into ranges (ksplit_for).  CSRK_KTILE_MIN_MB overrides the 4 (tests).
+    // XCD's L2 and collapse beyond): a dense operand of 8 MB or more with at least 1024 rows, 4 MB with 2048,
+    // 2 MB with 4096.  Small M is handled by cutting K into ranges (ksplit_for).  CSRK_KTILE_MIN_MB overrides
+    // the 4 (tests).
     const long long dense_bytes = (long long)K * N * 4;
     const long long min_bytes = (long long)env_int("CSRK_KTILE_MIN_MB", 4) << 20;
-    return (M >= 1024 && dense_bytes >= min_bytes) || (M >= 4096 && dense_bytes >= min_bytes / 2);
+    return (M >= 1024 && dense_bytes >= 2 * min_bytes) || (M >= 2048 && dense_bytes >= min_bytes) ||
+           (M >= 4096 && dense_bytes >= min_bytes / 2);
 }
 
 bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
