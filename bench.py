@@ -10,7 +10,7 @@ workload is the 16384 x 16384, 20 %-dense configuration the benchmark spec's target is
 
   value        GFLOP/s of the whole step, flops = 2*nnz*N (SPMM) + 2*nnz*D (SDDMM)
                + 2*nnz*(D+N) (FusedMM)
-  ops          per operation, from HIP events around its kernels: GFLOP/s (mean, median, best), the
+  ops          per operation, from one HIP-event pair around all kernels of a call: GFLOP/s (mean, median, best), the
                fractions of the FP32 peak, of the plain-FMA ceiling and of HBM bandwidth (algorithmic
                bytes), the rate at which gathered dense rows reach the ALUs (nnz * width * 4 bytes / time)
                against the micro-benchmarked LDS read rate, one cold run (caches flushed by writing

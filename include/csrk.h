@@ -110,11 +110,10 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
  * Benchmark aid (not part of the paper's method; it mirrors the paper's practice of
  * timing each kernel on its own, section "Experiments").  csrk_profile_enable(n)
  * with n > 0 creates n pairs of HIP events; from then on every spmm_csr / sddmm_csr /
- * fusedmm_csr call records one pair on the call's stream around the kernel launches
- * that can do the call's arithmetic (the LDS-tiled kernel when one is tried, and the
- * general kernel behind it: exactly one of the two does the work, the other returns at
- * once; the row analysis before them and the combine pass of partial rows after them
- * are outside the pair), until the pairs are used up.  csrk_profile_enable(0)
+ * fusedmm_csr call records one pair on the call's stream around ALL kernel launches of
+ * the call (the row analysis, the LDS-tiled kernel when one is tried, the general kernel
+ * behind it - exactly one of the two does the work, the other returns at once - and the
+ * combine pass of partial rows), until the pairs are used up.  csrk_profile_enable(0)
  * destroys the events and switches recording off.
  * csrk_profile_collect waits for the recorded pairs, writes up to `capacity`
  * elapsed times in milliseconds to ms[] and the operation of each to kinds[]

@@ -61,9 +61,8 @@ struct Recorder {
 };
 Recorder g_rec;
 
-// One event pair per call: begin() before the first kernel that may do the call's arithmetic (the
-// tiled kernel if one is tried, else the general kernel), end() after the last (the general kernel),
-// so the pair always contains the kernel that did the work plus at most one that stood down.
+// One event pair per call, around all of its kernels: the row analysis, the tiled kernel with its reduction (if
+// one is tried), the general kernel (which stands down if the tiled one did the call) and the combine step.
 struct CallRecord {
     int slot = -1;
     int kind;
@@ -80,6 +79,7 @@ struct CallRecord {
         if (slot >= 0) (void)hipEventRecord(g_rec.stop[slot], st);
         slot = -2;
     }
+    ~CallRecord() { end(); }    // a call that fails half-way still closes its pair
 };
 
 int env_int(const char *name, int dflt) {
@@ -268,23 +268,29 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
-// Density from which the narrow tiled kernels beat the general path (measured on a grid of M, K, N, density).
-// It depends mostly on how big the gathered dense operand is: the general path gathers at L2 speed while K x N
-// floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not care.
-float narrow_min_density(int K, int N, bool fused) {
+// Density from which the narrow tiled kernels beat the general path, read off grids of (M, K, N, density)
+// measured on MI355X with whole calls timed.  It falls with the size of the gathered dense operand (the general
+// path gathers at L2 speed while K x N floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not
+// care) and with M (every workgroup stages the whole operand through LDS whatever its rows hold: fewer rows per
+// CU, less to spread that over).
+float narrow_min_density(int M, int K, int N, bool fused) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const long long dense_bytes = (long long)K * N * 4;
     if (N <= 32) return fused ? kNarrowMinDensity : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
-    if (dense_bytes >= (8ll << 20)) return 0.03f;
-    if (dense_bytes >= (4ll << 20)) return 0.06f;
-    if (dense_bytes >= (2ll << 20)) return 0.09f;
-    return 0.15f;
+    const int size = dense_bytes >= (8ll << 20) ? 3 : dense_bytes >= (4ll << 20) ? 2 : dense_bytes >= (2ll << 20) ? 1 : 0;
+    const int rows = M < 8192 ? 0 : M < 12288 ? 1 : 2;
+    static const float spmm[3][4] = {{0.17f, 0.17f, 0.15f, 0.06f}, {0.15f, 0.09f, 0.06f, 0.03f}, {0.08f, 0.07f, 0.05f, 0.03f}};
+    static const float fusedmm[3][4] = {{0.17f, 0.15f, 0.09f, 0.04f}, {0.15f, 0.09f, 0.06f, 0.03f}, {0.13f, 0.09f, 0.06f, 0.03f}};
+    if (fused && rows == 2 && size == 0 && N > 64) return 0.08f;
+    return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
 // ... and the tiled SDDMM kernel (64 lanes = 64 entries of one row: short segments waste lanes)
-float sddmm_min_density(int K, int D) {
+float sddmm_min_density(int M, int K, int D) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
-    if (D <= 64) return 0.05f;
-    return (long long)K * D * 4 >= (8ll << 20) ? 0.05f : 0.09f;
+    const bool big = (long long)K * D * 4 >= (8ll << 20);
+    if (M < 8192) return big ? 0.08f : 0.15f;
+    if (M < 12288) return big ? 0.05f : (D > 64 ? 0.09f : 0.08f);
+    return big ? 0.05f : (D > 64 ? 0.09f : 0.05f);
 }
 
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
@@ -307,7 +313,7 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     if (mode == 3 || D % 4 != 0 || D > 128 || D < 4) return false;
     if (mode == 2) return true;
     (void)K;
-    return (long long)M >= 12ll * d.cus;
+    return (long long)M >= 16ll * d.cus;
 }
 
 // the full column-order check that K-split launches need (see order_check_kernel); after launch_analysis
@@ -375,12 +381,13 @@ csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const 
 
 // narrow outputs (N <= 128): G entries side by side per wavefront.  Thresholds below were read off a
 // sweep of the paper's 72 benchmark shapes on MI355X (tiled against general kernel, per shape).
-bool narrow_shape_ok(const DeviceState &d, int M, int N, bool fused) {
+bool narrow_shape_ok(const DeviceState &d, int M, int K, int N, bool fused) {
     const int mode = env_int("CSRK_KTILE", 1);
     if (mode == 3 || N % 4 != 0 || N > 128 || N < 4) return false;
     if (mode == 2) return true;
     const long long rows_per_cu = (long long)M / d.cus;
     if (N <= 32) return rows_per_cu >= (fused ? 96 : 32);   // tiny dense operand: the general path's gathers stay in cache
+    (void)K;
     return rows_per_cu >= 16;                               // at least one workgroup per CU at one row per wavefront
 }
 
@@ -637,10 +644,10 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
-    if (vec4 && narrow_shape_ok(*d, M, N, false)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(K, N, false))) return s;
+    rec.begin();
+    if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, false))) return s;
         gate = tile_flags(*d);
-        rec.begin();
         csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
         if (s) return s;
     } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
@@ -648,12 +655,10 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
         // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
         gate = tile_flags(*d);
-        rec.begin();
         csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
                                  : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
         if (s) return s;
     }
-    rec.begin();
 #define CSRK_SPMM_CASE(V, L, T)                                                                           \
     if (c.vec == V && c.lg == L && c.t == T)                                                              \
         launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row, gate);
@@ -664,9 +669,9 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     CSRK_SPMM_CASE(4, 64, 2)
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
-    rec.end();
     CSRK_HIP(hipGetLastError());
     launch_combine(*d, stream, N, O, gate, vec4);
+    rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
@@ -685,17 +690,16 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     const dim3 grid(d->workers / kWavesPerBlock);
     const int32_t *gate = nullptr;
     CallRecord rec(2, stream);
+    rec.begin();
     if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(K, D))) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(M, K, D))) return s;
         gate = tile_flags(*d);
-        rec.begin();
         csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                         : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                                   : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
         if (s) return s;
     }
-    rec.begin();
 #define CSRK_SDDMM_CASE(V, L, T)                                                        \
     if (c.vec == V && c.lg == L && c.t == T)                                            \
         launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate);
@@ -731,21 +735,19 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     bool done = false;
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
-    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, N, true)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(K, N, true))) return s;
+    rec.begin();
+    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, true))) return s;
         gate = tile_flags(*d);
-        rec.begin();
         csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
         gate = tile_flags(*d);
-        rec.begin();
         csrk_status s = N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
                                  : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     }
-    rec.begin();
 #define CSRK_DOT_CASE(V, L, T)                                                                            \
     if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                  \
         done = launch_fused_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head, \
@@ -757,10 +759,10 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     CSRK_DOT_CASE(4, 64, 0)
     CSRK_DOT_CASE(1, 64, 0)
 #undef CSRK_DOT_CASE
-    rec.end();
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
     launch_combine(*d, stream, N, O, gate, nvec4);
+    rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
