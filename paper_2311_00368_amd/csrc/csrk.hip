@@ -316,13 +316,6 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     return (long long)M >= 16ll * d.cus;
 }
 
-// the full column-order check that K-split launches need (see order_check_kernel); after launch_analysis
-csrk_status launch_order_check(DeviceState &d, hipStream_t st, int M, const int32_t *rp, const int32_t *ci) {
-    hipLaunchKernelGGL(order_check_kernel, dim3(d.cus * 8), dim3(256), 0, st, M, rp, ci, tile_flags(d));
-    CSRK_HIP(hipGetLastError());
-    return CSRK_OK;
-}
-
 // second half of a K-split SPMM / FusedMM call: O = sum of the `ksplit` partial outputs in the scratch
 csrk_status launch_ksplit_reduce(DeviceState &d, hipStream_t st, int M, int N, int ksplit, float *O) {
     const size_t count4 = (size_t)M * (size_t)N / 4;     // tiled kernels run only with N % 4 == 0
@@ -430,7 +423,6 @@ csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int N,
     const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, narrow_kt<G>(), kTileWaves * 4);
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
         return launch_narrow_rows<G, 4>(d, st, M, K, N, rp, ci, v, C, O, ksplit);
     }
     switch (tile_rows_for(d, M)) {
@@ -476,7 +468,6 @@ csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, co
     const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
         return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O, ksplit);
     }
     switch (tile_rows_for(d, M)) {
@@ -520,7 +511,6 @@ csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int
     const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
         return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
     }
     switch (tile_rows_for(d, M)) {
@@ -573,7 +563,6 @@ csrk_status launch_fused_narrow_g(DeviceState &d, hipStream_t st, int M, int K, 
     const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4);
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        if (csrk_status s = launch_order_check(d, st, M, rp, ci)) return s;
         return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
     }
     switch (tile_rows_for(d, M)) {

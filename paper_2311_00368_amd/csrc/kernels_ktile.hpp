@@ -105,31 +105,53 @@ __device__ __forceinline__ unsigned long long descending_lanes(int k) {
     return __ballot(prev > k);
 }
 
-// Full check of the column order of every row: raises flags[0] on a descending pair inside a row.  One thread
-// per stored entry compares it with the entry before it; a descending pair is harmless only if the second entry
-// starts a row, which a binary search of rowptr decides (needed for few entries: about one per row).
-// Needed only by launches that cut K into ranges (K-split): a workgroup then starts inside each row, at a
-// position found by binary search, and the order check built into the tiled kernels sees only the entries it
-// streams - which proves nothing about a row that is not sorted.  Runs after reset_flags_kernel and does
-// nothing if that has already ruled the tiled kernels out.
-__global__ __launch_bounds__(256) void order_check_kernel(int M, const int32_t *__restrict__ rowptr,
-                                                         const int32_t *__restrict__ colidx, int32_t *flags) {
-    if (flags[1] == 0) return;
-    const int nnz = rowptr[M];
+// Full check of the column order of the rows of one row block, done by the workgroups of a K-split launch
+// themselves before they start: the S workgroups that share the block (blockIdx.y = 0 .. S-1) each take every
+// S-th slice of 1024 neighbouring pairs of the block's entries.  A descending pair is harmless only if its second
+// entry is the first of a row; the block's row starts (at most 64) sit one per lane, so that question is one
+// compare and a ballot.  Returns true if this workgroup saw a descending pair inside a row.
+// Needed because a K-split workgroup starts inside each row, at a position found by binary search, and the
+// order check built into the tiled kernels sees only the entries it streams - which proves nothing about a
+// row that is not sorted.  (A separate kernel for this check, one thread per stored entry with a binary search
+// of rowptr per descending pair, cost 10 us at 1.7 M entries - a dozen dependent loads in a few thousand
+// threads; counting descending pairs against row starts with atomics cost 25.)
+template <int RB>
+__device__ __forceinline__ bool ksplit_block_unsorted(int M, const int32_t *__restrict__ rowptr,
+                                                      const int32_t *__restrict__ colidx) {
+    static_assert(RB <= kWave, "one row start per lane");
+    const int lane = lane_id();
+    const int rb0 = blockIdx.x * RB;
+    const int rows = M - rb0 < RB ? M - rb0 : RB;
+    const int e0 = uniform(rowptr[rb0]), e1 = uniform(rowptr[rb0 + rows]);
+    if (e1 - e0 < 2) return false;
+    const int start = rowptr[rb0 + (lane < rows ? lane : 0)];     // row starts of the block (lane 0: e0, never asked for)
+    constexpr int U = 4;                    // pairs requested together per thread (loads under no condition: an entry
+                                            // past the end re-reads the last pair)
+    const int slice = (int)blockDim.x, S = (int)gridDim.y;
     bool bad = false;
-    for (int j = blockIdx.x * blockDim.x + threadIdx.x + 1; j < nnz; j += gridDim.x * blockDim.x) {
-        if (colidx[j - 1] > colidx[j]) {
-            // does some row start at j?  lo = first row index with rowptr[lo] >= j
-            int lo = 0, hi = M;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (rowptr[mid] < j) lo = mid + 1;
-                else hi = mid;
+    for (long long j0 = (long long)e0 + 1 + (long long)blockIdx.y * slice + threadIdx.x; j0 - threadIdx.x < e1;
+         j0 += (long long)S * slice * U) {
+        int before[U], here[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            long long j = j0 + (long long)u * S * slice;
+            j = j < e1 ? j : e1 - 1;
+            before[u] = colidx[j - 1];
+            here[u] = colidx[j];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long j = j0 + (long long)u * S * slice;
+            unsigned long long desc = __ballot(j < e1 && before[u] > here[u]);
+            while (desc) {                  // about one per row boundary that falls into this wavefront's 64 pairs
+                const int l = __builtin_ctzll(desc);
+                desc &= desc - 1;
+                const int jj = __builtin_amdgcn_readlane((int)j, l);
+                if (__ballot(lane < rows && start == jj) == 0) bad = true;
             }
-            bad |= rowptr[lo] != j;
         }
     }
-    if (bad) flags[0] = 1;
+    return bad;
 }
 
 // K-split bookkeeping shared by the tiled kernels.  A launch with gridDim.y = S > 1 gives workgroup (x, y) the
@@ -206,6 +228,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+        if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
+    }
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];

@@ -69,6 +69,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+        if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
+    }
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -423,6 +426,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+        if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
+    }
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];

@@ -51,6 +51,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     const int n = (lane % LN) * 4;          // this lane's first column
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+        if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
+    }
     int pos[ROWS], end[ROWS];
     int kc[ROWS], kc2[ROWS];                // look-ahead: columns of the next 64 entries and of the 64 after them
     float vc[ROWS], vc2[ROWS];              // ... and their values
