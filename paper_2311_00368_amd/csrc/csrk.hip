@@ -47,7 +47,7 @@ struct DeviceState {
     float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way
     int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
     size_t head_floats = 0;
-
+    int pending_ksplit = 0; // > 1: the tiled kernel of the call in progress left that many partial outputs in `head`
 };
 
 DeviceState g_dev[kMaxDevices];
@@ -215,9 +215,14 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
     return false;
 }
 
-void launch_combine(DeviceState &d, hipStream_t st, int N, float *O, const int32_t *gate, bool vec4) {
+// last kernel of an SPMM / FusedMM call: heads of the equal-nonzero split, or the partial outputs of a K-split
+// tiled launch (see combine_heads_kernel)
+void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, const int32_t *gate, bool vec4) {
+    const size_t count4 = (size_t)M * (size_t)N / 4;     // K-split launches run only with N % 4 == 0
     hipLaunchKernelGGL(combine_heads_kernel, dim3((d.workers + kWavesPerBlock - 1) / kWavesPerBlock),
-                       dim3(kBlockThreads), 0, st, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0);
+                       dim3(kBlockThreads), 0, st, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0, count4,
+                       d.pending_ksplit, reinterpret_cast<const float4 *>(d.head));
+    d.pending_ksplit = 0;
 }
 
 // --- LDS-tiled path ---------------------------------------------------------------------
@@ -316,17 +321,6 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     return (long long)M >= 16ll * d.cus;
 }
 
-// second half of a K-split SPMM / FusedMM call: O = sum of the `ksplit` partial outputs in the scratch
-csrk_status launch_ksplit_reduce(DeviceState &d, hipStream_t st, int M, int N, int ksplit, float *O) {
-    const size_t count4 = (size_t)M * (size_t)N / 4;     // tiled kernels run only with N % 4 == 0
-    size_t blocks = (count4 + 255) / 256;
-    if (blocks > (size_t)d.cus * 8) blocks = (size_t)d.cus * 8;
-    hipLaunchKernelGGL(ksplit_reduce_kernel, dim3((unsigned)(blocks > 0 ? blocks : 1)), dim3(256), 0, st, count4, ksplit,
-                       reinterpret_cast<const float4 *>(d.head), reinterpret_cast<float4 *>(O), tile_flags(d));
-    CSRK_HIP(hipGetLastError());
-    return CSRK_OK;
-}
-
 template <int DMAX, int ROWS>
 csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
@@ -411,7 +405,7 @@ csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, C,
                        O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
-    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
+    if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
@@ -458,7 +452,7 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B,
                        O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
-    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
+    if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
@@ -500,7 +494,7 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
                        A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
-    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
+    if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
@@ -551,7 +545,7 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
                        A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
-    if (ksplit > 1) return launch_ksplit_reduce(d, st, M, N, ksplit, O);
+    if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
@@ -626,6 +620,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;
     if (csrk_status s = device_state(&d)) return s;
+    d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     const bool vec4 = (N % 4 == 0) && aligned16(B) && aligned16(O) && aligned16(d->head);
     const WidthCfg c = out_width_cfg(N, vec4);
@@ -659,7 +654,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O, gate, vec4);
+    launch_combine(*d, stream, M, N, O, gate, vec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
@@ -714,6 +709,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;
     if (csrk_status s = device_state(&d)) return s;
+    d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     const bool dvec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const bool nvec4 = (N % 4 == 0) && aligned16(C) && aligned16(O) && aligned16(d->head);
@@ -750,7 +746,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
 #undef CSRK_DOT_CASE
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, N, O, gate, nvec4);
+    launch_combine(*d, stream, M, N, O, gate, nvec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;

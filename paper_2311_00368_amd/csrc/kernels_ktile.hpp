@@ -156,7 +156,7 @@ __device__ __forceinline__ bool ksplit_block_unsorted(int M, const int32_t *__re
 
 // K-split bookkeeping shared by the tiled kernels.  A launch with gridDim.y = S > 1 gives workgroup (x, y) the
 // rows of block x and the columns [kb, ke) of K; it leaves its result rows in `partial` (S x M x N floats) and
-// ksplit_reduce_kernel adds the S partial rows in the order of y: no atomics on floats, same bits every run.
+// ksplit_reduce adds the S partial rows in the order of y: no atomics on floats, same bits every run.
 struct KSplit {
     int kb, ke;
 };
@@ -178,14 +178,12 @@ __device__ __forceinline__ int first_entry_at_or_after(const int32_t *colidx, in
     return p0 + wave_lower_bound(colidx + p0, p1 - p0, kb);
 }
 
-// O = sum over y of partial[y] (S x M x N floats), in the order of y: the second half of a K-split call.  Does
-// nothing if the tiled kernel before it stood down or met unsorted columns (the general kernels, launched after
-// this one, then write O).  A separate launch rather than a "last workgroup adds" inside the tiled kernel: the
-// device-wide fences that needs write back and invalidate an XCD's whole L2 each time, which cost three times
-// what the split gained.
-__global__ __launch_bounds__(256) void ksplit_reduce_kernel(size_t count4, int S, const float4 *__restrict__ partial,
-                                                           float4 *__restrict__ O, const int32_t *flags) {
-    if (!ktile_ok(flags)) return;
+// O = sum over y of partial[y] (S x M x N floats), in the order of y: the second half of a K-split call, run by
+// the whole grid of the call's last kernel (combine_heads_kernel, when the tiled kernel did the call).  A later
+// launch rather than a "last workgroup adds" inside the tiled kernel: the device-wide fences that needs write
+// back and invalidate an XCD's whole L2 each time, which cost three times what the split gained.
+__device__ __forceinline__ void ksplit_reduce(size_t count4, int S, const float4 *__restrict__ partial,
+                                              float4 *__restrict__ O) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count4; i += (size_t)gridDim.x * blockDim.x) {
         float4 sum = partial[i];
         for (int y = 1; y < S; ++y) {

@@ -361,7 +361,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         }
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
@@ -684,7 +684,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
     // add the G partial rows of every row and store
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
 #pragma unroll

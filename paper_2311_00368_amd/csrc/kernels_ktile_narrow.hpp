@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
         const int row = row0 + r;
-        float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce_kernel adds them
+        float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
         if (row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
     }
     if (bad != 0 && lane == 0) flags[0] = 1;

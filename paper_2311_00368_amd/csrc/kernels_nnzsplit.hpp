@@ -200,11 +200,18 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
 // One wavefront per worker, lanes over the output columns; only the first worker of a run does the
 // adding, in worker order, so sums are reproducible.  `vec4`: N is a multiple of 4 and O and head
 // are 16-byte aligned.
+// This is the last kernel of every SPMM / FusedMM call.  If a tiled kernel did the call there are no heads;
+// if that kernel's launch was K-split (S > 1) its S partial outputs (`partial`, count4 float4s each) still
+// have to be added into O, which this grid then does instead.
 __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int W, float *__restrict__ O,
                                                                        const float *__restrict__ head,
                                                                        const int32_t *__restrict__ head_row,
-                                                                       const int32_t *__restrict__ gate, int vec4) {
-    if (gate && ktile_ok(gate)) return;
+                                                                       const int32_t *__restrict__ gate, int vec4,
+                                                                       size_t count4, int S, const float4 *partial) {
+    if (gate && ktile_ok(gate)) {
+        if (S > 1) ksplit_reduce(count4, S, partial, reinterpret_cast<float4 *>(O));
+        return;
+    }
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (w >= W) return;
     const int r = uniform(head_row[w]);
