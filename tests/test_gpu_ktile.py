@@ -219,8 +219,8 @@ def test_ksplit_agrees_with_unsplit_and_repeats_bit_for_bit(csrk, M, K, D, N):
 @pytest.mark.parametrize("kind", ["shuffled", "rotated", "big_first", "one_swap_far_from_range_starts"])
 def test_ksplit_never_trusts_a_binary_search_in_unsorted_rows(csrk, kind):
     """With K cut into ranges a workgroup finds its starting entry in each row by binary search, which means
-    nothing if the row is not sorted; such inputs must be noticed by the full order check that precedes a
-    K-split launch and handed to the general kernels."""
+    nothing if the row is not sorted; such inputs must be noticed by the full order check that the workgroups
+    of a K-split launch make of their row blocks, and handed to the general kernels."""
     rng = np.random.default_rng(len(kind))
     M, K, D, N = 200, 4096, 64, 512
     rows = []
