@@ -317,8 +317,9 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     const int mode = env_int("CSRK_KTILE", 1);
     if (mode == 3 || D % 4 != 0 || D > 128 || D < 4) return false;
     if (mode == 2) return true;
-    (void)K;
-    return (long long)M >= 16ll * d.cus;
+    // below 8 M cells of S a call takes 10-30 us whichever kernel does it, and a failed attempt (row analysis plus
+    // a tiled launch that stands down, about 5 us) costs more than a successful one gains
+    return (long long)M >= 16ll * d.cus && (long long)M * K >= (8ll << 20);
 }
 
 template <int DMAX, int ROWS>
@@ -374,8 +375,8 @@ bool narrow_shape_ok(const DeviceState &d, int M, int K, int N, bool fused) {
     if (mode == 2) return true;
     const long long rows_per_cu = (long long)M / d.cus;
     if (N <= 32) return rows_per_cu >= (fused ? 96 : 32);   // tiny dense operand: the general path's gathers stay in cache
-    (void)K;
-    return rows_per_cu >= 16;                               // at least one workgroup per CU at one row per wavefront
+    // at least one workgroup per CU at one row per wavefront, and enough cells of S (see sddmm_tile_shape_ok)
+    return rows_per_cu >= 16 && (long long)M * K >= (8ll << 20);
 }
 
 // tile height of the narrow SPMM kernel: as high as LDS allows with the 128-entry look-ahead in mind (256 rows
