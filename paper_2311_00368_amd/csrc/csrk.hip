@@ -176,9 +176,9 @@ WidthCfg dot_width_cfg(int D, bool vec4) {
 
 template <int VEC, int LG, int T>
 void launch_spmm(dim3 grid, hipStream_t st, int M, int N, const int32_t *rp, const int32_t *ci, const float *v,
-                 const float *B, float *O, float *head, int32_t *head_row, const int32_t *gate) {
+                 const float *B, float *O, float *head, int32_t *head_row, const int32_t *gate, const int32_t *even) {
     hipLaunchKernelGGL((spmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, N, rp, ci, v, B, O,
-                       head, head_row, gate);
+                       head, head_row, gate, even);
 }
 
 template <int VEC, int LG, int T>
@@ -191,18 +191,18 @@ void launch_sddmm(dim3 grid, hipStream_t st, int M, int D, const int32_t *rp, co
 template <int VD, int LD, int TD, int VN, int LN, int TN>
 void launch_fused(dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp, const int32_t *ci,
                   const float *v, const float *A, const float *B, const float *C, float *O, float *head,
-                  int32_t *head_row, const int32_t *gate) {
+                  int32_t *head_row, const int32_t *gate, const int32_t *even) {
     hipLaunchKernelGGL((fusedmm_nnzsplit_kernel<VD, LD, TD, VN, LN, TN>), grid, dim3(kBlockThreads), 0, st, M, D, N,
-                       rp, ci, v, A, B, C, O, head, head_row, gate);
+                       rp, ci, v, A, B, C, O, head, head_row, gate, even);
 }
 
 template <int VD, int LD, int TD>
 bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp,
                     const int32_t *ci, const float *v, const float *A, const float *B, const float *C, float *O,
-                    float *head, int32_t *head_row, const int32_t *gate) {
+                    float *head, int32_t *head_row, const int32_t *gate, const int32_t *even) {
 #define CSRK_FUSED_CASE(VN, LN, TN)                                                                           \
     if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                          \
-        launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row, gate); \
+        launch_fused<VD, LD, TD, VN, LN, TN>(grid, st, M, D, N, rp, ci, v, A, B, C, O, head, head_row, gate, even); \
         return true;                                                                                          \
     }
     CSRK_FUSED_CASE(4, 8, 1)
@@ -217,12 +217,69 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
 
 // last kernel of an SPMM / FusedMM call: heads of the equal-nonzero split, or the partial outputs of a K-split
 // tiled launch (see combine_heads_kernel)
-void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, const int32_t *gate, bool vec4) {
+void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, const int32_t *gate, const int32_t *even,
+                    bool vec4) {
     const size_t count4 = (size_t)M * (size_t)N / 4;     // K-split launches run only with N % 4 == 0
     hipLaunchKernelGGL(combine_heads_kernel, dim3((d.workers + kWavesPerBlock - 1) / kWavesPerBlock),
                        dim3(kBlockThreads), 0, st, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0, count4,
-                       d.pending_ksplit, reinterpret_cast<const float4 *>(d.head));
+                       d.pending_ksplit, reinterpret_cast<const float4 *>(d.head), even);
     d.pending_ksplit = 0;
+}
+
+// --- one wavefront per row -----------------------------------------------------------------
+// For sparse matrices so small that a call is latency, not throughput: below 8 M cells of S (where no tiled
+// kernel is tried either) and with at most 2048 columns, so that even a full row is at most 32 chunks for its
+// wavefront.  One launch instead of the equal-nonzero split's two (kernel + combine step), and a shorter chain of
+// dependent loads inside it.  A wavefront walks its row alone, 64 / (lanes per entry) entries at a time, so wide
+// outputs (few entries side by side) pay only with enough rows to keep every CU busy meanwhile; measured on the
+// small shapes of the paper's grid: SPMM +14..+89 % except N = 128 with 1-2 k rows (-20 %), FusedMM +5..+60 % at
+// N = 32 and -46..+12 % at N = 128.  CSRK_ROWS=2 forces it for every shape it can run (tests), =3 switches it off.
+bool rows_mode_ok(int M, int K, int N, bool fused) {
+    const int mode = env_int("CSRK_ROWS", 1);
+    if (mode == 3) return false;
+    if (mode == 2) return true;
+    if ((long long)M * K >= (8ll << 20) || K > 2048) return false;
+    (void)N;
+    (void)fused;
+    return true;
+}
+
+// Larger matrices that get no tiled attempt (or whose attempt the device turns down) still gain 10-60 % from whole
+// rows where the rows are even, which only the row analysis can tell: worth its launch (3-6 us) from 32 M cells
+// (measured: -13 % at 4096 x 4096, gains from 12288 x 4096); not beyond 256 K rows, where that single-workgroup
+// kernel itself takes tens of microseconds.
+bool even_rows_worth_asking(int M, int K) {
+    if (env_int("CSRK_ROWS", 1) == 3) return false;
+    return (long long)M * K >= (32ll << 20) && M <= (1 << 18);
+}
+
+// wavefronts per row: enough wavefronts in flight for every CU whatever M is, and more of them where few entries
+// go side by side (wide outputs: a wavefront then walks its part of the row in more steps)
+int rows_wpr(int M, int N) {
+    const int want = N > 64 ? 8192 : 3072;
+    return M >= want ? 1 : (2 * M >= want ? 2 : 4);
+}
+
+dim3 rows_grid(int M, int wpr, int ytiles) {
+    const long long blocks = ((long long)M * wpr + kWavesPerBlock - 1) / kWavesPerBlock;
+    return dim3((unsigned)(blocks < 8192 ? blocks : 8192), ytiles);
+}
+
+template <int VD, int LD, int TD>
+bool launch_fused_rows_n(const WidthCfg &nc, hipStream_t st, int M, int D, int N, const int32_t *rp, const int32_t *ci,
+                         const float *v, const float *A, const float *B, const float *C, float *O) {
+#define CSRK_FUSED_ROWS_CASE(VN, LN, TN)                                                                       \
+    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                           \
+        const int wpr = rows_wpr(M, N);                                                                        \
+        hipLaunchKernelGGL((fusedmm_rows_kernel<VD, LD, TD, VN, LN, TN>), rows_grid(M, wpr, 1), dim3(kBlockThreads), \
+                           0, st, M, D, N, rp, ci, v, A, B, C, O, wpr);                                        \
+        return true;                                                                                           \
+    }
+    CSRK_FUSED_ROWS_CASE(4, 8, 1)
+    CSRK_FUSED_ROWS_CASE(4, 16, 1)
+    CSRK_FUSED_ROWS_CASE(4, 32, 1)
+#undef CSRK_FUSED_ROWS_CASE
+    return false;
 }
 
 // --- LDS-tiled path ---------------------------------------------------------------------
@@ -630,6 +687,23 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     rec.begin();
+    if (vec4 && rows_mode_ok(M, K, N, false)) {
+        const int wpr = rows_wpr(M, N);
+        const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
+#define CSRK_SPMM_ROWS_CASE(V, L, T)                                                                              \
+    if (c.vec == V && c.lg == L && c.t == T)                                                                      \
+        hipLaunchKernelGGL((spmm_rows_kernel<V, L, T>), rgrid, dim3(kBlockThreads), 0, stream, M, N, rowptr, colidx, \
+                           vals, B, O, wpr);
+        CSRK_SPMM_ROWS_CASE(4, 8, 1)
+        CSRK_SPMM_ROWS_CASE(4, 16, 1)
+        CSRK_SPMM_ROWS_CASE(4, 32, 1)
+        CSRK_SPMM_ROWS_CASE(4, 64, 1)
+        CSRK_SPMM_ROWS_CASE(4, 64, 2)
+#undef CSRK_SPMM_ROWS_CASE
+        rec.end();
+        CSRK_HIP(hipGetLastError());
+        return CSRK_OK;
+    }
     if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, false))) return s;
         gate = tile_flags(*d);
@@ -644,9 +718,16 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
                                  : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
         if (s) return s;
     }
+    const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
+    if (gate) {
+        even = tile_flags(*d) + 3;
+    } else if (even_rows_worth_asking(M, K)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
+        even = tile_flags(*d) + 3;
+    }
 #define CSRK_SPMM_CASE(V, L, T)                                                                           \
     if (c.vec == V && c.lg == L && c.t == T)                                                              \
-        launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row, gate);
+        launch_spmm<V, L, T>(grid, stream, M, N, rowptr, colidx, vals, B, O, d->head, d->head_row, gate, even);
     CSRK_SPMM_CASE(4, 8, 1)
     CSRK_SPMM_CASE(4, 16, 1)
     CSRK_SPMM_CASE(4, 32, 1)
@@ -655,7 +736,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, vec4);
+    launch_combine(*d, stream, M, N, O, gate, even, vec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
@@ -722,6 +803,17 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     rec.begin();
+    if (nvec4 && dvec4 && D <= 128 && N <= 128 && rows_mode_ok(M, K, N, true)) {
+        bool launched = false;
+        if (dc.lg == 8) launched = launch_fused_rows_n<4, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
+        if (dc.lg == 16) launched = launch_fused_rows_n<4, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
+        if (dc.lg == 32) launched = launch_fused_rows_n<4, 32, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
+        if (launched) {
+            rec.end();
+            CSRK_HIP(hipGetLastError());
+            return CSRK_OK;
+        }
+    }
     if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, true))) return s;
         gate = tile_flags(*d);
@@ -734,10 +826,17 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
                                  : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     }
+    const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
+    if (gate) {
+        even = tile_flags(*d) + 3;
+    } else if (even_rows_worth_asking(M, K)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
+        even = tile_flags(*d) + 3;
+    }
 #define CSRK_DOT_CASE(V, L, T)                                                                            \
     if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                  \
         done = launch_fused_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head, \
-                                       d->head_row, gate);
+                                       d->head_row, gate, even);
     CSRK_DOT_CASE(4, 8, 1)
     CSRK_DOT_CASE(4, 16, 1)
     CSRK_DOT_CASE(4, 32, 1)
@@ -747,7 +846,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
 #undef CSRK_DOT_CASE
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, nvec4);
+    launch_combine(*d, stream, M, N, O, gate, even, nvec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;

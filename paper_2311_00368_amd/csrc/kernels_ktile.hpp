@@ -96,6 +96,7 @@ __global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const i
         const bool even = (double)longest <= 2.0 * mean + 64.0;
         flags[0] = 0;
         flags[1] = ((dense && even) || min_density < 0.f) ? 1 : 0;
+        flags[3] = even ? 1 : 0;            // for the general kernels: rows can be dealt out whole (no balancing needed)
     }
 }
 

@@ -341,3 +341,33 @@ def test_automatic_kernel_choice_mid_sizes(csrk, shape):
     run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
     run_sddmm(csrk, M, K, D, w.rowptr, w.colidx, w.vals, f["A"], f["B"], rows=rows)
     run_fused(csrk, M, K, D, N, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
+
+
+@pytest.mark.parametrize("shape", [(8192, 2048, 0.05, 32, 32), (4096, 2048, 0.01, 512, 64), (9000, 4096, 0.04, 128, 128),
+                                   (2000, 1000, 0.1, 128, 128), (700, 2048, 0.3, 64, 64), (3500, 900, 0.2, 36, 32)])
+def test_whole_rows_paths_for_even_matrices(csrk, shape):
+    """Matrices whose rows are about equally long are dealt out row by row instead of in equal shares of the
+    stored entries: by the host's choice where S is small (one, two or four wavefronts per row), by the row
+    analysis' verdict where a tiled kernel was tried and turned down (too sparse here) or S is large.  Same
+    arithmetic per row (Algorithms 2 and 3), so the same bar."""
+    M, K, p, N, D = shape
+    w = inputs.custom_workload(M, K, p, N, D, seed=11)
+    rows = np.unique(np.concatenate([np.arange(0, M, 29), [0, 1, M - 2, M - 1]])).astype(np.int32)
+    f = w.ops["fusedmm"]
+    run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
+    run_fused(csrk, M, K, D, N, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
+
+
+def test_whole_rows_forced_on_uneven_and_ragged_inputs(csrk, monkeypatch):
+    """CSRK_ROWS=2 sends every call the row kernels can run through them: empty rows, one dense row, widths that
+    need the tail handling, M below one workgroup."""
+    monkeypatch.setenv("CSRK_ROWS", "2")
+    rng = np.random.default_rng(21)
+    for name, M, K, rp, ci in helpers.edge_patterns(rng):
+        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+        for D, N in [(64, 64), (32, 128), (8, 256), (128, 4)]:
+            A = rng.normal(size=(M, D)).astype(np.float32)
+            B = rng.normal(size=(K, D)).astype(np.float32)
+            C = rng.normal(size=(K, N)).astype(np.float32)
+            run_spmm(csrk, M, K, N, rp, ci, v, C)
+            run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
