@@ -323,15 +323,15 @@ int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per
     return (int)s;
 }
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
-constexpr float kNarrowMinDensity = 0.18f;    // narrow-output tiled kernels (measured cross-over with the general path)
+constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
 
 int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
 float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
-// Density from which the narrow tiled kernels beat the general path, read off grids of (M, K, N, density)
-// measured on MI355X with whole calls timed.  It falls with the size of the gathered dense operand (the general
+// Density from which the narrow tiled kernels beat what runs otherwise (whole rows for even matrices, which
+// is all the tiled kernels take), read off grids of (M, K, N, density) measured on MI355X with whole calls timed.  It falls with the size of the gathered dense operand (the general
 // path gathers at L2 speed while K x N floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not
 // care) and with M (every workgroup stages the whole operand through LDS whatever its rows hold: fewer rows per
 // CU, less to spread that over).
@@ -341,8 +341,8 @@ float narrow_min_density(int M, int K, int N, bool fused) {
     if (N <= 32) return fused ? kNarrowMinDensity : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
     const int size = dense_bytes >= (8ll << 20) ? 3 : dense_bytes >= (4ll << 20) ? 2 : dense_bytes >= (2ll << 20) ? 1 : 0;
     const int rows = M < 8192 ? 0 : M < 12288 ? 1 : 2;
-    static const float spmm[3][4] = {{0.17f, 0.17f, 0.15f, 0.06f}, {0.15f, 0.09f, 0.06f, 0.03f}, {0.08f, 0.07f, 0.05f, 0.03f}};
-    static const float fusedmm[3][4] = {{0.17f, 0.15f, 0.09f, 0.04f}, {0.15f, 0.09f, 0.06f, 0.03f}, {0.13f, 0.09f, 0.06f, 0.03f}};
+    static const float spmm[3][4] = {{0.17f, 0.17f, 0.15f, 0.06f}, {0.15f, 0.09f, 0.08f, 0.05f}, {0.08f, 0.07f, 0.07f, 0.045f}};
+    static const float fusedmm[3][4] = {{0.17f, 0.15f, 0.09f, 0.05f}, {0.15f, 0.09f, 0.09f, 0.05f}, {0.13f, 0.09f, 0.085f, 0.045f}};
     if (fused && rows == 2 && size == 0 && N > 64) return 0.08f;
     return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
