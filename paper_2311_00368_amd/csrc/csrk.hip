@@ -757,6 +757,22 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     const int32_t *gate = nullptr;
     CallRecord rec(2, stream);
     rec.begin();
+    if (vec4 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
+        const int wpr = rows_wpr(M, D);
+        const dim3 rgrid = rows_grid(M, wpr, 1);
+#define CSRK_SDDMM_ROWS_CASE(V, L, T)                                                                               \
+    if (c.vec == V && c.lg == L && c.t == T)                                                                        \
+        hipLaunchKernelGGL((sddmm_rows_kernel<V, L, T>), rgrid, dim3(kBlockThreads), 0, stream, M, D, rowptr, colidx, \
+                           vals, A, B, P, wpr);
+        CSRK_SDDMM_ROWS_CASE(4, 8, 1)
+        CSRK_SDDMM_ROWS_CASE(4, 16, 1)
+        CSRK_SDDMM_ROWS_CASE(4, 32, 1)
+        CSRK_SDDMM_ROWS_CASE(4, 64, 1)
+#undef CSRK_SDDMM_ROWS_CASE
+        rec.end();
+        CSRK_HIP(hipGetLastError());
+        return CSRK_OK;
+    }
     if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(M, K, D))) return s;

@@ -431,6 +431,31 @@ __device__ __forceinline__ void load_a_row(const float *__restrict__ arow, int D
     }
 }
 
+// P[j] = vals[j] * <A[r, :], Bmat[colidx[j], :]> for the stored entries [s0, s1) of row r (Algorithm 1's inner
+// loops), a chunk of 64 entries at a time.  P may alias vals.
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void sddmm_segment(int r, int s0, int s1, const int32_t *__restrict__ colidx,
+                                              const float *vals, const float *__restrict__ A,
+                                              const float *__restrict__ Bmat, float *P, int D, int d, float *slot) {
+    if (s1 <= s0) return;
+    const int lane = lane_id();
+    const float *arow = A + (size_t)r * D;
+    float a[T > 0 ? T : 1][VEC];
+    load_a_row<VEC, LG, T>(arow, D, d, a);
+    for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
+        const int j = base + lane;
+        const bool ok = j >= s0 && j < s1;
+        const int kc = ok ? colidx[j] : 0;
+        const float vc = (ok && vals) ? vals[j] : 1.f;
+        const int t0 = s0 > base ? s0 - base : 0;
+        const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
+        sddmm_chunk<VEC, LG, T>(kc, t0, t1, Bmat, D, d, arow, a, slot);
+        __builtin_amdgcn_wave_barrier();
+        if (ok) P[j] = vc * slot[lane];
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 // P may alias vals, so neither is __restrict__.
 template <int VEC, int LG, int T>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
@@ -457,21 +482,27 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
         const int s0 = rs > sh.lo ? rs : sh.lo;
         const int s1 = re < sh.hi ? re : sh.hi;
         if (s1 <= s0) continue;
-        const float *arow = A + (size_t)r * D;
-        float a[T > 0 ? T : 1][VEC];
-        load_a_row<VEC, LG, T>(arow, D, d, a);
-        for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
-            const int j = base + lane;
-            const bool ok = j >= s0 && j < s1;
-            const int kc = ok ? colidx[j] : 0;
-            const float vc = (ok && vals) ? vals[j] : 1.f;
-            const int t0 = s0 > base ? s0 - base : 0;
-            const int t1 = (s1 - base) < kWave ? (s1 - base) : kWave;
-            sddmm_chunk<VEC, LG, T>(kc, t0, t1, Bmat, D, d, arow, a, slot);
-            __builtin_amdgcn_wave_barrier();
-            if (ok) P[j] = vc * slot[lane];
-            __builtin_amdgcn_wave_barrier();
-        }
+        sddmm_segment<VEC, LG, T>(r, s0, s1, colidx, vals, A, Bmat, P, D, d, slot);
+    }
+}
+
+// SDDMM with a row per 1, 2 or 4 wavefronts (consecutive parts of the row; outputs are per stored entry, so
+// nothing to add up): see spmm_rows_kernel.
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void sddmm_rows_kernel(
+    int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
+    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int wpr) {
+    __shared__ float slots[kWavesPerBlock][kWave];
+    const int lane = lane_id();
+    const int wv = uniform(threadIdx.x >> 6);
+    const int sub = wv % wpr, rows_per_block = kWavesPerBlock / wpr;
+    const int d = (lane % LG) * VEC;
+    for (long long r = (long long)blockIdx.x * rows_per_block + wv / wpr; r < M; r += (long long)gridDim.x * rows_per_block) {
+        const int rs = uniform(rowptr[r]);
+        const int re = uniform(rowptr[r + 1]);
+        int s0, s1;
+        row_part(rs, re, sub, wpr, s0, s1);
+        sddmm_segment<VEC, LG, T>((int)r, s0, s1, colidx, vals, A, Bmat, P, D, d, slots[wv]);
     }
 }
 

@@ -355,6 +355,7 @@ def test_whole_rows_paths_for_even_matrices(csrk, shape):
     rows = np.unique(np.concatenate([np.arange(0, M, 29), [0, 1, M - 2, M - 1]])).astype(np.int32)
     f = w.ops["fusedmm"]
     run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
+    run_sddmm(csrk, M, K, D, w.rowptr, w.colidx, w.vals, f["A"], f["B"], rows=rows)
     run_fused(csrk, M, K, D, N, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
 
 
@@ -371,3 +372,6 @@ def test_whole_rows_forced_on_uneven_and_ragged_inputs(csrk, monkeypatch):
             C = rng.normal(size=(K, N)).astype(np.float32)
             run_spmm(csrk, M, K, N, rp, ci, v, C)
             run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+            if len(ci):
+                run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+                run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
