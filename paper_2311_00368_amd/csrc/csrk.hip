@@ -183,9 +183,9 @@ void launch_spmm(dim3 grid, hipStream_t st, int M, int N, const int32_t *rp, con
 
 template <int VEC, int LG, int T>
 void launch_sddmm(dim3 grid, hipStream_t st, int M, int D, const int32_t *rp, const int32_t *ci, const float *v,
-                  const float *A, const float *B, float *P, const int32_t *gate) {
+                  const float *A, const float *B, float *P, const int32_t *gate, const int32_t *even) {
     hipLaunchKernelGGL((sddmm_nnzsplit_kernel<VEC, LG, T>), grid, dim3(kBlockThreads), 0, st, M, D, rp, ci, v, A, B,
-                       P, gate);
+                       P, gate, even);
 }
 
 template <int VD, int LD, int TD, int VN, int LN, int TN>
@@ -221,7 +221,7 @@ void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, cons
                     bool vec4) {
     const size_t count4 = (size_t)M * (size_t)N / 4;     // K-split launches run only with N % 4 == 0
     hipLaunchKernelGGL(combine_heads_kernel, dim3((d.workers + kWavesPerBlock - 1) / kWavesPerBlock),
-                       dim3(kBlockThreads), 0, st, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0, count4,
+                       dim3(kBlockThreads), 0, st, M, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0, count4,
                        d.pending_ksplit, reinterpret_cast<const float4 *>(d.head), even);
     d.pending_ksplit = 0;
 }
@@ -782,9 +782,10 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
                                   : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
         if (s) return s;
     }
+    const int32_t *even = gate ? tile_flags(*d) + 3 : nullptr;   // device flag: rows even enough to be dealt out whole
 #define CSRK_SDDMM_CASE(V, L, T)                                                        \
     if (c.vec == V && c.lg == L && c.t == T)                                            \
-        launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate);
+        launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate, even);
     CSRK_SDDMM_CASE(4, 8, 1)
     CSRK_SDDMM_CASE(4, 16, 1)
     CSRK_SDDMM_CASE(4, 32, 1)

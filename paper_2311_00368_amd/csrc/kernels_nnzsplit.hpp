@@ -168,10 +168,11 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
     const int W = gridDim.x * kWavesPerBlock;
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     const int n = blockIdx.y * (TW * T) + (lane % LG) * VEC;
-    if (even && *even != 0) {
+    if (even && *even != 0 && 2 * (long long)M > W) {
         // The row analysis found no row much longer than the mean: nothing to balance, so whole rows are dealt out
         // round robin - no search for a share's first row, no heads (combine_heads_kernel stands down on the same
-        // flag).  Measured 10-60 % faster than the equal-nonzero split on such matrices.
+        // condition).  Measured 10-60 % faster than the equal-nonzero split on such matrices, as long as there are
+        // enough rows for the wavefronts (with half as many rows as wavefronts the split was up to 16 % faster).
         for (int r = w; r < M; r += W) {
             const int rs = uniform(rowptr[r]);
             const int re = uniform(rowptr[r + 1]);
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_rows_kernel(
 // This is the last kernel of every SPMM / FusedMM call.  If a tiled kernel did the call there are no heads;
 // if that kernel's launch was K-split (S > 1) its S partial outputs (`partial`, count4 float4s each) still
 // have to be added into O, which this grid then does instead.
-__global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int W, float *__restrict__ O,
+__global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int M, int N, int W, float *__restrict__ O,
                                                                        const float *__restrict__ head,
                                                                        const int32_t *__restrict__ head_row,
                                                                        const int32_t *__restrict__ gate, int vec4,
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int N, int
         if (S > 1) ksplit_reduce(count4, S, partial, reinterpret_cast<float4 *>(O));
         return;
     }
-    if (even && *even != 0) return;         // the general kernel dealt out whole rows: there are no heads
+    if (even && *even != 0 && 2 * (long long)M > W) return;   // the general kernel dealt out whole rows: no heads
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (w >= W) return;
     const int r = uniform(head_row[w]);
@@ -461,7 +462,7 @@ template <int VEC, int LG, int T>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P,
-    const int32_t *__restrict__ gate) {
+    const int32_t *__restrict__ gate, const int32_t *__restrict__ even) {
     __shared__ float slots[kWavesPerBlock][kWave];
     if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
     const int lane = lane_id();
@@ -469,6 +470,12 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     const int wv = threadIdx.x >> 6;
     const int w = uniform(blockIdx.x * kWavesPerBlock + wv);
     const int d = (lane % LG) * VEC;
+    if (even && *even != 0 && 2 * (long long)M > W) {   // whole rows, round robin: see spmm_nnzsplit_kernel
+        for (int r = w; r < M; r += W)
+            sddmm_segment<VEC, LG, T>(r, uniform(rowptr[r]), uniform(rowptr[r + 1]), colidx, vals, A, Bmat, P, D, d,
+                                      slots[wv]);
+        return;
+    }
     const Share sh = make_share(rowptr, M, w, W);
     if (!sh.active || sh.lo >= sh.nnz) return;
     float *slot = slots[wv];
@@ -553,7 +560,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     const int d = (lane % LD) * VD;
     const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
     float *slot = slots[wv];
-    if (even && *even != 0) {               // whole rows, round robin: see spmm_nnzsplit_kernel
+    if (even && *even != 0 && 2 * (long long)M > W) {   // whole rows, round robin: see spmm_nnzsplit_kernel
         for (int r = w; r < M; r += W) {
             const int rs = uniform(rowptr[r]);
             const int re = uniform(rowptr[r + 1]);
