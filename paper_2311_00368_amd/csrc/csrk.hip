@@ -329,7 +329,21 @@ int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
 
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
-float tile_min_density() { return env_int("CSRK_KTILE", 1) == 2 ? -1.f : kTileMinDensity; }
+// Density from which the wide tiled kernels beat what runs otherwise (whole rows; equal shares for FusedMM with few
+// rows), by the size of the gathered dense operand (columns: 2, 4, 8, 16 MB and more) and by M (rows of the table:
+// below 2048, 4096, 8192 rows, and above); 1 = never.  Read off a grid of 100 (M, K, N, density) points with
+// whole calls timed.
+float wide_min_density(int M, int K, int N, bool fused) {
+    if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
+    const long long dense_bytes = (long long)K * N * 4;
+    const int size = dense_bytes >= (16ll << 20) ? 3 : dense_bytes >= (8ll << 20) ? 2 : dense_bytes >= (4ll << 20) ? 1 : 0;
+    const int rows = M < 2048 ? 0 : M < 4096 ? 1 : M < 8192 ? 2 : 3;
+    static const float spmm[4][4] = {{1.f, 1.f, 0.20f, 0.05f}, {1.f, 0.10f, 0.05f, 0.025f}, {0.10f, 0.08f, 0.04f, kTileMinDensity},
+                                     {0.07f, 0.06f, 0.035f, kTileMinDensity}};
+    static const float fusedmm[4][4] = {{1.f, 1.f, 0.08f, 0.04f}, {1.f, 0.08f, 0.035f, kTileMinDensity},
+                                        {0.10f, 0.06f, 0.03f, kTileMinDensity}, {0.075f, 0.05f, 0.04f, kTileMinDensity}};
+    return fused ? fusedmm[rows][size] : spmm[rows][size];
+}
 // Density from which the narrow tiled kernels beat what runs otherwise (whole rows for even matrices, which
 // is all the tiled kernels take), read off grids of (M, K, N, density) measured on MI355X with whole calls timed.  It falls with the size of the gathered dense operand (the general
 // path gathers at L2 speed while K x N floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not
@@ -712,7 +726,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
         // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
         // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, wide_min_density(M, K, N, false))) return s;
         gate = tile_flags(*d);
         csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
                                  : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
@@ -837,7 +851,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
         csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
         if (s) return s;
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, tile_min_density())) return s;
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, wide_min_density(M, K, N, true))) return s;
         gate = tile_flags(*d);
         csrk_status s = N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
                                  : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);

@@ -156,62 +156,6 @@ __device__ __forceinline__ void store_row(float *dst, int N, int n, const float 
     }
 }
 
-template <int VEC, int LG, int T>
-__global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
-    int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O,
-    float *__restrict__ head, int32_t *__restrict__ head_row, const int32_t *__restrict__ gate,
-    const int32_t *__restrict__ even) {
-    constexpr int TW = LG * VEC;
-    if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
-    const int lane = lane_id();
-    const int W = gridDim.x * kWavesPerBlock;
-    const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
-    const int n = blockIdx.y * (TW * T) + (lane % LG) * VEC;
-    if (even && *even != 0 && 2 * (long long)M > W) {
-        // The row analysis found no row much longer than the mean: nothing to balance, so whole rows are dealt out
-        // round robin - no search for a share's first row, no heads (combine_heads_kernel stands down on the same
-        // condition).  Measured 10-60 % faster than the equal-nonzero split on such matrices, as long as there are
-        // enough rows for the wavefronts (with half as many rows as wavefronts the split was up to 16 % faster).
-        for (int r = w; r < M; r += W) {
-            const int rs = uniform(rowptr[r]);
-            const int re = uniform(rowptr[r + 1]);
-            float acc[T][VEC] = {};
-            spmm_segment<VEC, LG, T>(rs, re, colidx, vals, Bmat, N, n, acc);
-            fold_groups<VEC, LG, T>(acc);
-            store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
-        }
-        return;
-    }
-    const Share sh = make_share(rowptr, M, w, W);
-    if (!sh.active) {
-        if (blockIdx.y == 0 && lane == 0) head_row[w] = -1;
-        return;
-    }
-    int r = wave_lower_bound(rowptr, M, sh.lo);
-    int hr = -1;
-    if (sh.lo < sh.nnz) {
-        const int start = uniform(rowptr[r]);      // r <= M and rowptr[M] = nnz
-        if (start != sh.lo) {                      // share begins inside row r-1
-            hr = r - 1;
-            float acc[T][VEC] = {};
-            spmm_segment<VEC, LG, T>(sh.lo, start < sh.hi ? start : sh.hi, colidx, vals, Bmat, N, n, acc);
-            fold_groups<VEC, LG, T>(acc);
-            store_row<VEC, LG, T>(head + (size_t)w * N, N, n, acc);
-        }
-    }
-    if (blockIdx.y == 0 && lane == 0) head_row[w] = hr;
-    for (; r < M; ++r) {
-        const int rs = uniform(rowptr[r]);
-        if (!sh.last && rs >= sh.hi) break;
-        const int re = uniform(rowptr[r + 1]);
-        float acc[T][VEC] = {};
-        spmm_segment<VEC, LG, T>(rs, re < sh.hi ? re : sh.hi, colidx, vals, Bmat, N, n, acc);
-        fold_groups<VEC, LG, T>(acc);
-        store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
-    }
-}
-
 // A row per wavefront - or per 2 or 4 wavefronts of a workgroup (`wpr`), which then take consecutive parts of
 // the row and whose partial rows the first of them adds in order through LDS: the paper's own decomposition (a row
 // per work-item, NT work-items per row for short matrices; Algorithms 1-3 and section "SDDMM").  No shares, no
@@ -261,10 +205,10 @@ __device__ __forceinline__ void add_row_parts(RowParts<VEC, LG, T> &lds, int wv,
 }
 
 template <int VEC, int LG, int T>
-__global__ __launch_bounds__(kBlockThreads) void spmm_rows_kernel(
-    int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O, int wpr) {
-    __shared__ RowParts<VEC, LG, T> lds;
+__device__ __forceinline__ void spmm_rows_body(int M, int N, const int32_t *__restrict__ rowptr,
+                                               const int32_t *__restrict__ colidx, const float *__restrict__ vals,
+                                               const float *__restrict__ Bmat, float *__restrict__ O, int wpr,
+                                               RowParts<VEC, LG, T> &lds) {
     constexpr int TW = LG * VEC;
     const int lane = lane_id();
     const int wv = uniform(threadIdx.x >> 6);
@@ -288,6 +232,72 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_rows_kernel(
     }
 }
 
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void spmm_rows_kernel(
+    int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O, int wpr) {
+    __shared__ RowParts<VEC, LG, T> lds;
+    spmm_rows_body<VEC, LG, T>(M, N, rowptr, colidx, vals, Bmat, O, wpr, lds);
+}
+
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
+    int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O,
+    float *__restrict__ head, int32_t *__restrict__ head_row, const int32_t *__restrict__ gate,
+    const int32_t *__restrict__ even) {
+    constexpr int TW = LG * VEC;
+    if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
+    const int lane = lane_id();
+    const int W = gridDim.x * kWavesPerBlock;
+    const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    const int n = blockIdx.y * (TW * T) + (lane % LG) * VEC;
+    if (even && *even != 0 && 2ll * M > W) {
+        // The row analysis found no row much longer than the mean: nothing to balance, so whole rows are dealt out
+        // round robin - no search for a share's first row, no heads (combine_heads_kernel stands down on the same
+        // condition).  Measured 10-60 % faster than the equal-nonzero split on such matrices, as long as there are
+        // enough rows for the wavefronts (with half as many rows as wavefronts the split was up to 16 % faster; and
+        // sharing rows between wavefronts here, as spmm_rows_kernel does, costs the FusedMM kernel registers that
+        // its equal-share branch - the one skewed matrices take - needs for full occupancy).
+        for (int r = w; r < M; r += W) {
+            const int rs = uniform(rowptr[r]);
+            const int re = uniform(rowptr[r + 1]);
+            float acc[T][VEC] = {};
+            spmm_segment<VEC, LG, T>(rs, re, colidx, vals, Bmat, N, n, acc);
+            fold_groups<VEC, LG, T>(acc);
+            store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
+        }
+        return;
+    }
+    const Share sh = make_share(rowptr, M, w, W);
+    if (!sh.active) {
+        if (blockIdx.y == 0 && lane == 0) head_row[w] = -1;
+        return;
+    }
+    int r = wave_lower_bound(rowptr, M, sh.lo);
+    int hr = -1;
+    if (sh.lo < sh.nnz) {
+        const int start = uniform(rowptr[r]);      // r <= M and rowptr[M] = nnz
+        if (start != sh.lo) {                      // share begins inside row r-1
+            hr = r - 1;
+            float acc[T][VEC] = {};
+            spmm_segment<VEC, LG, T>(sh.lo, start < sh.hi ? start : sh.hi, colidx, vals, Bmat, N, n, acc);
+            fold_groups<VEC, LG, T>(acc);
+            store_row<VEC, LG, T>(head + (size_t)w * N, N, n, acc);
+        }
+    }
+    if (blockIdx.y == 0 && lane == 0) head_row[w] = hr;
+    for (; r < M; ++r) {
+        const int rs = uniform(rowptr[r]);
+        if (!sh.last && rs >= sh.hi) break;
+        const int re = uniform(rowptr[r + 1]);
+        float acc[T][VEC] = {};
+        spmm_segment<VEC, LG, T>(rs, re < sh.hi ? re : sh.hi, colidx, vals, Bmat, N, n, acc);
+        fold_groups<VEC, LG, T>(acc);
+        store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
+    }
+}
+
 // O[r, :] += head[w, :] + head[w+1, :] + ... for the run of workers whose head is row r.
 // One wavefront per worker, lanes over the output columns; only the first worker of a run does the
 // adding, in worker order, so sums are reproducible.  `vec4`: N is a multiple of 4 and O and head
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int M, int
         if (S > 1) ksplit_reduce(count4, S, partial, reinterpret_cast<float4 *>(O));
         return;
     }
-    if (even && *even != 0 && 2 * (long long)M > W) return;   // the general kernel dealt out whole rows: no heads
+    if (even && *even != 0 && 2ll * M > W) return;   // the general kernel dealt out whole rows: there are no heads
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (w >= W) return;
     const int r = uniform(head_row[w]);
@@ -457,6 +467,34 @@ __device__ __forceinline__ void sddmm_segment(int r, int s0, int s1, const int32
     }
 }
 
+// SDDMM with a row per 1, 2 or 4 wavefronts (consecutive parts of the row; outputs are per stored entry, so
+// nothing to add up): see spmm_rows_kernel.
+template <int VEC, int LG, int T>
+__device__ __forceinline__ void sddmm_rows_body(int M, int D, const int32_t *__restrict__ rowptr,
+                                                const int32_t *__restrict__ colidx, const float *vals,
+                                                const float *__restrict__ A, const float *__restrict__ Bmat, float *P,
+                                                int wpr, float *slot) {
+    const int lane = lane_id();
+    const int wv = uniform(threadIdx.x >> 6);
+    const int sub = wv % wpr, rows_per_block = kWavesPerBlock / wpr;
+    const int d = (lane % LG) * VEC;
+    for (long long r = (long long)blockIdx.x * rows_per_block + wv / wpr; r < M; r += (long long)gridDim.x * rows_per_block) {
+        const int rs = uniform(rowptr[r]);
+        const int re = uniform(rowptr[r + 1]);
+        int s0, s1;
+        row_part(rs, re, sub, wpr, s0, s1);
+        sddmm_segment<VEC, LG, T>((int)r, s0, s1, colidx, vals, A, Bmat, P, D, d, slot);
+    }
+}
+
+template <int VEC, int LG, int T>
+__global__ __launch_bounds__(kBlockThreads) void sddmm_rows_kernel(
+    int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
+    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int wpr) {
+    __shared__ float slots[kWavesPerBlock][kWave];
+    sddmm_rows_body<VEC, LG, T>(M, D, rowptr, colidx, vals, A, Bmat, P, wpr, slots[threadIdx.x >> 6]);
+}
+
 // P may alias vals, so neither is __restrict__.
 template <int VEC, int LG, int T>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
@@ -470,7 +508,7 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     const int wv = threadIdx.x >> 6;
     const int w = uniform(blockIdx.x * kWavesPerBlock + wv);
     const int d = (lane % LG) * VEC;
-    if (even && *even != 0 && 2 * (long long)M > W) {   // whole rows, round robin: see spmm_nnzsplit_kernel
+    if (even && *even != 0 && 2ll * M > W) {    // whole rows, round robin: see spmm_nnzsplit_kernel
         for (int r = w; r < M; r += W)
             sddmm_segment<VEC, LG, T>(r, uniform(rowptr[r]), uniform(rowptr[r + 1]), colidx, vals, A, Bmat, P, D, d,
                                       slots[wv]);
@@ -490,26 +528,6 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
         const int s1 = re < sh.hi ? re : sh.hi;
         if (s1 <= s0) continue;
         sddmm_segment<VEC, LG, T>(r, s0, s1, colidx, vals, A, Bmat, P, D, d, slot);
-    }
-}
-
-// SDDMM with a row per 1, 2 or 4 wavefronts (consecutive parts of the row; outputs are per stored entry, so
-// nothing to add up): see spmm_rows_kernel.
-template <int VEC, int LG, int T>
-__global__ __launch_bounds__(kBlockThreads) void sddmm_rows_kernel(
-    int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
-    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int wpr) {
-    __shared__ float slots[kWavesPerBlock][kWave];
-    const int lane = lane_id();
-    const int wv = uniform(threadIdx.x >> 6);
-    const int sub = wv % wpr, rows_per_block = kWavesPerBlock / wpr;
-    const int d = (lane % LG) * VEC;
-    for (long long r = (long long)blockIdx.x * rows_per_block + wv / wpr; r < M; r += (long long)gridDim.x * rows_per_block) {
-        const int rs = uniform(rowptr[r]);
-        const int re = uniform(rowptr[r + 1]);
-        int s0, s1;
-        row_part(rs, re, sub, wpr, s0, s1);
-        sddmm_segment<VEC, LG, T>((int)r, s0, s1, colidx, vals, A, Bmat, P, D, d, slots[wv]);
     }
 }
 
@@ -544,6 +562,49 @@ __device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int
     }
 }
 
+// FusedMM with a row per 1, 2 or 4 wavefronts: see spmm_rows_kernel.
+template <int VD, int LD, int TD, int VN, int LN, int TN>
+__device__ __forceinline__ void fusedmm_rows_body(int M, int D, int N, const int32_t *__restrict__ rowptr,
+                                                  const int32_t *__restrict__ colidx, const float *__restrict__ vals,
+                                                  const float *__restrict__ A, const float *__restrict__ Bmat,
+                                                  const float *__restrict__ Cmat, float *__restrict__ O, int wpr,
+                                                  float *slot, RowParts<VN, LN, TN> &lds) {
+    constexpr int TWN = LN * VN;
+    const int lane = lane_id();
+    const int wv = uniform(threadIdx.x >> 6);
+    const int sub = wv % wpr, rows_per_block = kWavesPerBlock / wpr;
+    const int d = (lane % LD) * VD;
+    const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
+    for (long long r0 = (long long)blockIdx.x * rows_per_block; r0 < M; r0 += (long long)gridDim.x * rows_per_block) {
+        const long long r = r0 + wv / wpr;
+        const bool valid = r < M;
+        const int rs = valid ? uniform(rowptr[r]) : 0;
+        const int re = valid ? uniform(rowptr[r + 1]) : 0;
+        int s0, s1;
+        row_part(rs, re, sub, wpr, s0, s1);
+        float acc[TN][VN] = {};
+        fused_segment<VD, LD, TD, VN, LN, TN>((int)(valid ? r : 0), s0, s1, colidx, vals, A, Bmat, Cmat, D, N, d, n, slot,
+                                              acc);
+        fold_groups<VN, LN, TN>(acc);
+        if (wpr == 1) {
+            if (valid) store_row<VN, LN, TN>(O + (size_t)r * N, N, n, acc);
+        } else {
+            add_row_parts<VN, LN, TN>(lds, wv, sub, wpr, valid, O + (size_t)(valid ? r : 0) * N, N, n, acc);
+        }
+    }
+}
+
+template <int VD, int LD, int TD, int VN, int LN, int TN>
+__global__ __launch_bounds__(kBlockThreads) void fusedmm_rows_kernel(
+    int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
+    const float *__restrict__ Cmat, float *__restrict__ O, int wpr) {
+    __shared__ float slots[kWavesPerBlock][kWave];
+    __shared__ RowParts<VN, LN, TN> lds;
+    fusedmm_rows_body<VD, LD, TD, VN, LN, TN>(M, D, N, rowptr, colidx, vals, A, Bmat, Cmat, O, wpr,
+                                              slots[threadIdx.x >> 6], lds);
+}
+
 template <int VD, int LD, int TD, int VN, int LN, int TN>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
@@ -560,7 +621,7 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     const int d = (lane % LD) * VD;
     const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
     float *slot = slots[wv];
-    if (even && *even != 0 && 2 * (long long)M > W) {   // whole rows, round robin: see spmm_nnzsplit_kernel
+    if (even && *even != 0 && 2ll * M > W) {    // whole rows, round robin: see spmm_nnzsplit_kernel
         for (int r = w; r < M; r += W) {
             const int rs = uniform(rowptr[r]);
             const int re = uniform(rowptr[r + 1]);
@@ -599,39 +660,6 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
                                               n, slot, acc);
         fold_groups<VN, LN, TN>(acc);
         store_row<VN, LN, TN>(O + (size_t)r * N, N, n, acc);
-    }
-}
-
-// FusedMM with a row per 1, 2 or 4 wavefronts: see spmm_rows_kernel.
-template <int VD, int LD, int TD, int VN, int LN, int TN>
-__global__ __launch_bounds__(kBlockThreads) void fusedmm_rows_kernel(
-    int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int wpr) {
-    __shared__ float slots[kWavesPerBlock][kWave];
-    __shared__ RowParts<VN, LN, TN> lds;
-    constexpr int TWN = LN * VN;
-    const int lane = lane_id();
-    const int wv = uniform(threadIdx.x >> 6);
-    const int sub = wv % wpr, rows_per_block = kWavesPerBlock / wpr;
-    const int d = (lane % LD) * VD;
-    const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
-    for (long long r0 = (long long)blockIdx.x * rows_per_block; r0 < M; r0 += (long long)gridDim.x * rows_per_block) {
-        const long long r = r0 + wv / wpr;
-        const bool valid = r < M;
-        const int rs = valid ? uniform(rowptr[r]) : 0;
-        const int re = valid ? uniform(rowptr[r + 1]) : 0;
-        int s0, s1;
-        row_part(rs, re, sub, wpr, s0, s1);
-        float acc[TN][VN] = {};
-        fused_segment<VD, LD, TD, VN, LN, TN>((int)(valid ? r : 0), s0, s1, colidx, vals, A, Bmat, Cmat, D, N, d, n,
-                                              slots[wv], acc);
-        fold_groups<VN, LN, TN>(acc);
-        if (wpr == 1) {
-            if (valid) store_row<VN, LN, TN>(O + (size_t)r * N, N, n, acc);
-        } else {
-            add_row_parts<VN, LN, TN>(lds, wv, sub, wpr, valid, O + (size_t)(valid ? r : 0) * N, N, n, acc);
-        }
     }
 }
 
