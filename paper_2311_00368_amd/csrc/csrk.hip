@@ -218,11 +218,11 @@ bool launch_fused_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D,
 // last kernel of an SPMM / FusedMM call: heads of the equal-nonzero split, or the partial outputs of a K-split
 // tiled launch (see combine_heads_kernel)
 void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, const int32_t *gate, const int32_t *even,
-                    bool vec4) {
+                    bool even_any_m, bool vec4) {
     const size_t count4 = (size_t)M * (size_t)N / 4;     // K-split launches run only with N % 4 == 0
     hipLaunchKernelGGL(combine_heads_kernel, dim3((d.workers + kWavesPerBlock - 1) / kWavesPerBlock),
                        dim3(kBlockThreads), 0, st, M, N, d.workers, O, d.head, d.head_row, gate, vec4 ? 1 : 0, count4,
-                       d.pending_ksplit, reinterpret_cast<const float4 *>(d.head), even);
+                       d.pending_ksplit, reinterpret_cast<const float4 *>(d.head), even, even_any_m ? 1 : 0);
     d.pending_ksplit = 0;
 }
 
@@ -750,7 +750,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, even, vec4);
+    launch_combine(*d, stream, M, N, O, gate, even, c.vec == 4 && c.t == 1, vec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
@@ -877,7 +877,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
 #undef CSRK_DOT_CASE
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, even, nvec4);
+    launch_combine(*d, stream, M, N, O, gate, even, false, nvec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;

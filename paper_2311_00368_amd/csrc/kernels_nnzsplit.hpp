@@ -204,6 +204,14 @@ __device__ __forceinline__ void add_row_parts(RowParts<VEC, LG, T> &lds, int wv,
     __syncthreads();
 }
 
+// instantiations of the general SPMM kernel whose whole-row branch shares rows between wavefronts whatever M is
+template <int VEC, int LG, int T>
+constexpr bool kSpmmRowsAnyM = VEC == 4 && T == 1;
+
+// wavefronts per row when the kernel decides for itself (the whole-row branch of the general SPMM and SDDMM
+// kernels): W is the number of wavefronts in the grid
+__device__ __forceinline__ int rows_wpr_for(int M, int W) { return 2ll * M > W ? 1 : (4ll * M > W ? 2 : 4); }
+
 template <int VEC, int LG, int T>
 __device__ __forceinline__ void spmm_rows_body(int M, int N, const int32_t *__restrict__ rowptr,
                                                const int32_t *__restrict__ colidx, const float *__restrict__ vals,
@@ -252,22 +260,28 @@ __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
     const int W = gridDim.x * kWavesPerBlock;
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     const int n = blockIdx.y * (TW * T) + (lane % LG) * VEC;
-    if (even && *even != 0 && 2ll * M > W) {
+    if (even && *even != 0) {
         // The row analysis found no row much longer than the mean: nothing to balance, so whole rows are dealt out
-        // round robin - no search for a share's first row, no heads (combine_heads_kernel stands down on the same
-        // condition).  Measured 10-60 % faster than the equal-nonzero split on such matrices, as long as there are
-        // enough rows for the wavefronts (with half as many rows as wavefronts the split was up to 16 % faster; and
-        // sharing rows between wavefronts here, as spmm_rows_kernel does, costs the FusedMM kernel registers that
-        // its equal-share branch - the one skewed matrices take - needs for full occupancy).
-        for (int r = w; r < M; r += W) {
-            const int rs = uniform(rowptr[r]);
-            const int re = uniform(rowptr[r + 1]);
-            float acc[T][VEC] = {};
-            spmm_segment<VEC, LG, T>(rs, re, colidx, vals, Bmat, N, n, acc);
-            fold_groups<VEC, LG, T>(acc);
-            store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
+        // (1, 2 or 4 wavefronts per row, whatever keeps the wavefronts of the grid busy) - no search for a share's
+        // first row, no heads (combine_heads_kernel stands down on the same flag).  Measured 10-60 % faster than
+        // the equal-nonzero split on such matrices.
+        // (Sharing rows between wavefronts only where it costs no occupancy: not in the 512-wide instantiation,
+        // 91 -> 99 VGPRs; that one takes whole rows with more than half as many rows as wavefronts.)
+        if constexpr (kSpmmRowsAnyM<VEC, LG, T>) {
+            __shared__ RowParts<VEC, LG, T> lds;
+            spmm_rows_body<VEC, LG, T>(M, N, rowptr, colidx, vals, Bmat, O, rows_wpr_for(M, W), lds);
+            return;
+        } else if (2ll * M > W) {
+            for (int r = w; r < M; r += W) {
+                const int rs = uniform(rowptr[r]);
+                const int re = uniform(rowptr[r + 1]);
+                float acc[T][VEC] = {};
+                spmm_segment<VEC, LG, T>(rs, re, colidx, vals, Bmat, N, n, acc);
+                fold_groups<VEC, LG, T>(acc);
+                store_row<VEC, LG, T>(O + (size_t)r * N, N, n, acc);
+            }
+            return;
         }
-        return;
     }
     const Share sh = make_share(rowptr, M, w, W);
     if (!sh.active) {
@@ -310,12 +324,13 @@ __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int M, int
                                                                        const int32_t *__restrict__ head_row,
                                                                        const int32_t *__restrict__ gate, int vec4,
                                                                        size_t count4, int S, const float4 *partial,
-                                                                       const int32_t *__restrict__ even) {
+                                                                       const int32_t *__restrict__ even, int any_m) {
     if (gate && ktile_ok(gate)) {
         if (S > 1) ksplit_reduce(count4, S, partial, reinterpret_cast<float4 *>(O));
         return;
     }
-    if (even && *even != 0 && 2ll * M > W) return;   // the general kernel dealt out whole rows: there are no heads
+    // the general kernel dealt out whole rows (SPMM: whenever the rows are even; FusedMM: with enough rows too)
+    if (even && *even != 0 && (any_m || 2ll * M > W)) return;
     const int w = uniform(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (w >= W) return;
     const int r = uniform(head_row[w]);
@@ -508,10 +523,8 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     const int wv = threadIdx.x >> 6;
     const int w = uniform(blockIdx.x * kWavesPerBlock + wv);
     const int d = (lane % LG) * VEC;
-    if (even && *even != 0 && 2ll * M > W) {    // whole rows, round robin: see spmm_nnzsplit_kernel
-        for (int r = w; r < M; r += W)
-            sddmm_segment<VEC, LG, T>(r, uniform(rowptr[r]), uniform(rowptr[r + 1]), colidx, vals, A, Bmat, P, D, d,
-                                      slots[wv]);
+    if (even && *even != 0) {               // whole rows: see spmm_nnzsplit_kernel
+        sddmm_rows_body<VEC, LG, T>(M, D, rowptr, colidx, vals, A, Bmat, P, rows_wpr_for(M, W), slots[wv]);
         return;
     }
     const Share sh = make_share(rowptr, M, w, W);
@@ -621,7 +634,10 @@ __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     const int d = (lane % LD) * VD;
     const int n = blockIdx.y * (TWN * TN) + (lane % LN) * VN;
     float *slot = slots[wv];
-    if (even && *even != 0 && 2ll * M > W) {    // whole rows, round robin: see spmm_nnzsplit_kernel
+    // Whole rows, round robin (see spmm_nnzsplit_kernel) - here only with more than half as many rows as wavefronts
+    // and one wavefront per row: sharing rows between wavefronts costs registers that the equal-share branch below,
+    // the one skewed matrices take, needs for full occupancy (62 -> 70 VGPRs, 12 % slower on `fused8k_skew`).
+    if (even && *even != 0 && 2ll * M > W) {
         for (int r = w; r < M; r += W) {
             const int rs = uniform(rowptr[r]);
             const int re = uniform(rowptr[r + 1]);
