@@ -344,7 +344,8 @@ def test_automatic_kernel_choice_mid_sizes(csrk, shape):
 
 
 @pytest.mark.parametrize("shape", [(8192, 2048, 0.05, 32, 32), (4096, 2048, 0.01, 512, 64), (9000, 4096, 0.04, 128, 128),
-                                   (2000, 1000, 0.1, 128, 128), (700, 2048, 0.3, 64, 64), (3500, 900, 0.2, 36, 32)])
+                                   (2000, 1000, 0.1, 128, 128), (700, 2048, 0.3, 64, 64), (3500, 900, 0.2, 36, 32),
+                                   (1024, 8192, 0.1, 256, 64), (3000, 4096, 0.03, 256, 32), (5000, 2048, 0.02, 512, 64)])
 def test_whole_rows_paths_for_even_matrices(csrk, shape):
     """Matrices whose rows are about equally long are dealt out row by row instead of in equal shares of the
     stored entries: by the host's choice where S is small (one, two or four wavefronts per row), by the row
