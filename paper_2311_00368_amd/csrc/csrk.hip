@@ -278,6 +278,8 @@ bool launch_fused_rows_n(const WidthCfg &nc, hipStream_t st, int M, int D, int N
     CSRK_FUSED_ROWS_CASE(4, 8, 1)
     CSRK_FUSED_ROWS_CASE(4, 16, 1)
     CSRK_FUSED_ROWS_CASE(4, 32, 1)
+    CSRK_FUSED_ROWS_CASE(4, 64, 1)
+    CSRK_FUSED_ROWS_CASE(4, 64, 2)
 #undef CSRK_FUSED_ROWS_CASE
     return false;
 }
@@ -834,7 +836,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     rec.begin();
-    if (nvec4 && dvec4 && D <= 128 && N <= 128 && rows_mode_ok(M, K, N, true)) {
+    if (nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N, true)) {
         bool launched = false;
         if (dc.lg == 8) launched = launch_fused_rows_n<4, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
         if (dc.lg == 16) launched = launch_fused_rows_n<4, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
