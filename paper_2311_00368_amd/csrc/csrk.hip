@@ -244,13 +244,14 @@ bool rows_mode_ok(int M, int K, int N, bool fused) {
     return true;
 }
 
-// Larger matrices that get no tiled attempt (or whose attempt the device turns down) still gain 10-60 % from whole
-// rows where the rows are even, which only the row analysis can tell: worth its launch (3-6 us) from 32 M cells
-// (measured: -13 % at 4096 x 4096, gains from 12288 x 4096); not beyond 256 K rows, where that single-workgroup
-// kernel itself takes tens of microseconds.
-bool even_rows_worth_asking(int M, int K) {
+// Larger matrices that get no tiled attempt (or whose attempt the device turns down) still gain from whole rows
+// where the rows are even, which only the row analysis can tell: worth its launch (3-6 us) from 8 M cells, if the
+// kernel can act on the answer (FusedMM's whole-row branch needs more than half as many rows as wavefronts);
+// not beyond 256 K rows, where that single-workgroup kernel itself takes tens of microseconds.
+bool even_rows_worth_asking(const DeviceState &d, int M, int K, bool fused) {
     if (env_int("CSRK_ROWS", 1) == 3) return false;
-    return (long long)M * K >= (32ll << 20) && M <= (1 << 18);
+    if (fused && 2ll * M <= d.workers) return false;
+    return (long long)M * K >= (8ll << 20) && M <= (1 << 18);
 }
 
 // wavefronts per row: enough wavefronts in flight for every CU whatever M is, and more of them where few entries
@@ -737,7 +738,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
     if (gate) {
         even = tile_flags(*d) + 3;
-    } else if (even_rows_worth_asking(M, K)) {
+    } else if (even_rows_worth_asking(*d, M, K, false)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
         even = tile_flags(*d) + 3;
     }
@@ -862,7 +863,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
     if (gate) {
         even = tile_flags(*d) + 3;
-    } else if (even_rows_worth_asking(M, K)) {
+    } else if (even_rows_worth_asking(*d, M, K, true)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
         even = tile_flags(*d) + 3;
     }
