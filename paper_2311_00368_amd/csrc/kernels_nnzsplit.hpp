@@ -1,26 +1,32 @@
-// Row-segment kernels with an equal-nonzero work split (the general path).
+// Row-segment kernels that gather dense rows straight from memory (the general path): every kernel here
+// works on segments of rows - a run of stored entries of one row - and differs only in who gets which segment.
 //
-// Each wavefront ("worker") takes an equal share of S's stored entries, whatever the
-// row lengths are, finds the row its share starts in by a wave-wide search of rowptr
-// and walks the rows it touches.  This is the load balancing for skewed row lengths:
-// a row longer than a share is cut into segments handled by consecutive workers.
+// Two ways of dealing out the work:
 //
-//  - SPMM / FusedMM: a worker writes the rows that START inside its share straight to
-//    O (if such a row continues into later shares this is its first partial sum), and
-//    puts the partial sum of the row that was already running when its share began
-//    (its "head") into a scratch row; `combine_heads_kernel` then adds the heads to
-//    O in worker order, so the result does not depend on timing.
-//  - SDDMM: outputs are per stored entry, segments are disjoint, no combine.
+//  (1) Equal shares of the stored entries (`*_nnzsplit_kernel`).  Each wavefront ("worker") takes an equal
+//      share of S's stored entries, whatever the row lengths are, finds the row its share starts in by a
+//      wave-wide search of rowptr and walks the rows it touches.  This is the load balancing for skewed row
+//      lengths: a row longer than a share is cut into segments handled by consecutive workers.
+//       - SPMM / FusedMM: a worker writes the rows that START inside its share straight to O (if such a row
+//         continues into later shares this is its first partial sum), and puts the partial sum of the row
+//         that was already running when its share began (its "head") into a scratch row;
+//         `combine_heads_kernel` then adds the heads to O in worker order, so the result does not depend on
+//         timing.
+//       - SDDMM: outputs are per stored entry, segments are disjoint, no combine.
 //
-// Inside a segment the column indices and values are streamed in coalesced chunks of
-// 64 (one per lane), the next chunk being loaded while the current one is consumed.
-// A group of LG lanes covers the dense width with VEC floats per lane, so 64/LG
-// entries are processed side by side; their dense rows are gathered with one
-// (128-bit when VEC == 4) load per lane.
+//  (2) Whole rows (`*_rows_kernel`, and a branch of the kernels of (1) taken when the row analysis found the
+//      rows about equally long): the paper's own decomposition, a row per work-item, with 2 or 4 wavefronts
+//      of a workgroup sharing a row where there are few rows (its NT, section "SDDMM").  No search, no heads,
+//      no combine step; faster wherever there is nothing to balance.
 //
-// Paper correspondence: the chunked index stream with look-ahead is the role of the
-// VLC-sized blocks and prefetches in the paper's kernels (section "ESIMD
-// Implementation"); the per-row arithmetic is Algorithms 1-3.
+// Inside a segment the column indices and values are streamed in coalesced chunks of 64 (one per lane), the
+// next chunk being loaded while the current one is consumed.  A group of LG lanes covers the dense width with
+// VEC floats per lane, so 64/LG entries are processed side by side; their dense rows are gathered with one
+// (128-bit when VEC == 4) load per lane, several steps' gathers in flight together (gather_axpy).
+//
+// Paper correspondence: the chunked index stream with look-ahead is the role of the VLC-sized blocks and
+// prefetches in the paper's kernels (section "ESIMD Implementation"); the per-row arithmetic is
+// Algorithms 1-3.
 #pragma once
 #include "device_util.hpp"
 #include "kernels_ktile.hpp"
