@@ -406,6 +406,12 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     constexpr int kBRowBytes = DMAX * 4;
     constexpr int kGroupsPerRow = 4 / ROWS;
     constexpr int kPass = 16 * kGroupsPerRow;      // entries of a row scored per pass
+    // Entries are parked in the order the accumulate stage fetches them back: a round is 4 G entries, group g takes
+    // entries t+g, t+G+g, t+2G+g, t+3G+g of it, and those four pairs sit next to each other (32 bytes), so a lane
+    // gets them with two 128-bit reads instead of four 64-bit ones (the pair reads were half of the accumulate
+    // stage's LDS instructions, and LDS issue is what bounds it).  Needs passes of whole rounds.
+    constexpr bool kPermuted = kPass % (4 * G) == 0;
+    auto parked = [](int q) { return kPermuted ? (q / (4 * G)) * (4 * G) + (q % G) * 4 + (q / G) % 4 : q; };
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;
@@ -564,14 +570,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
                 maxcnt = cnt > maxcnt ? cnt : maxcnt;
                 if (my_r == r) my_cnt = cnt;
                 if (lane >= part && lane < part + SL)
-                    ent[r * SL + lane - part] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
+                    ent[r * SL + parked(lane - part)] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
             }
             for (int base = 0; base < maxcnt; base += kPass) {
                 // ---- score stage: this lane's entry of this pass
                 {
                     const int idx = base + my_first;
                     const bool on = idx < my_cnt;
-                    int2 *mine = ent + my_r * SL + (on ? idx : 0);
+                    int2 *mine = ent + my_r * SL + parked(on ? idx : 0);
                     const int2 kv = *mine;
                     // byte address of piece i16 of the entry's row of B; lanes without an entry walk row 0 of the tile
                     const unsigned row_b = (unsigned)(L::kCFloats * 4) + (on ? (unsigned)(kv.x - k0) * (unsigned)kBRowBytes : 0u) + i16 * 16;
@@ -610,11 +616,26 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
                     const int2 *e = ent + r * SL;
                     const int lim = cnts[r] < base + kPass ? cnts[r] : base + kPass;
                     int t = base;
+                    auto fetch = [&](int2 (&ks4)[4]) {
+                        if constexpr (kPermuted) {
+                            const int4 lo = *reinterpret_cast<const int4 *>(e + t + 4 * g);
+                            const int4 hi = *reinterpret_cast<const int4 *>(e + t + 4 * g + 2);
+                            ks4[0] = make_int2(lo.x, lo.y);
+                            ks4[1] = make_int2(lo.z, lo.w);
+                            ks4[2] = make_int2(hi.x, hi.y);
+                            ks4[3] = make_int2(hi.z, hi.w);
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                const int idx = t + u * G + g;
+                                ks4[u] = e[idx < lim ? idx : base];
+                            }
+                        }
+                    };
                     for (; t + 4 * G <= lim; t += 4 * G) {
                         int2 ks4[4];
                         float c[4][4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) ks4[u] = e[t + u * G + g];
+                        fetch(ks4);
 #pragma unroll
                         for (int u = 0; u < 4; ++u)
                             load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
@@ -630,16 +651,15 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
                     if (t < lim) {                  // last, partial round: lanes whose entry does not exist sit out
                         int2 ks4[4];
                         float c[4][4];
+                        fetch(ks4);
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
-                            const int idx = t + u * G + g;
-                            ks4[u] = e[idx < lim ? idx : base];
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
+                            // an entry that does not exist: read the tile's first row (what its pair holds is anything)
+                            const int col = t + u * G + g < lim ? ks4[u].x : k0;
                             load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
-                                                                        ((unsigned)ks4[u].x * (unsigned)kRowBytes + lb)),
+                                                                        ((unsigned)col * (unsigned)kRowBytes + lb)),
                                         c[u]);
+                        }
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
                             if (t + u * G + g < lim) {

@@ -130,14 +130,24 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         // one chunk's worth of a row: `cnt` leading entries of (kreg, vreg) belong to this tile
         auto process = [&](int r, int slot, int kreg, float vreg, int cnt) {
             int2 *e = ent + slot * kWave;
-            e[lane] = make_int2(kreg, __builtin_bit_cast(int, vreg));
-            // accumulate stage: group g takes entries t+g, t+G+g, t+2G+g, t+3G+g of each round
+            // Entries are parked in the order they are fetched back: a round is 4 G entries, group g takes entries
+            // t+g, t+G+g, t+2G+g, t+3G+g of it, and those four pairs sit next to each other (32 bytes), so a lane
+            // gets them with two 128-bit reads instead of four 64-bit ones (the pair reads were half of the
+            // kernel's LDS instructions, and LDS issue is what bounds it).
+            e[(lane / (4 * G)) * (4 * G) + (lane % G) * 4 + (lane / G) % 4] = make_int2(kreg, __builtin_bit_cast(int, vreg));
             int t = 0;
+            auto fetch = [&](int2 (&ks)[4]) {
+                const int4 lo = *reinterpret_cast<const int4 *>(e + t + 4 * g);
+                const int4 hi = *reinterpret_cast<const int4 *>(e + t + 4 * g + 2);
+                ks[0] = make_int2(lo.x, lo.y);
+                ks[1] = make_int2(lo.z, lo.w);
+                ks[2] = make_int2(hi.x, hi.y);
+                ks[3] = make_int2(hi.z, hi.w);
+            };
             for (; t + 4 * G <= cnt; t += 4 * G) {
                 int2 ks[4];
                 float c[4][4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) ks[u] = e[t + u * G + g];
+                fetch(ks);
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
@@ -150,19 +160,17 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
                     for (int v = 0; v < 4; ++v) acc[r][v] = fmaf(sv, c[u][v], acc[r][v]);
                 }
             }
-            if (t < cnt) {                  // last, partial round: lanes whose entry does not exist sit out
-                int2 ks[4];
+            if (t < cnt) {                  // last, partial round: lanes whose entry does not exist read the tile's
+                int2 ks[4];                 // first row (their pair holds a column beyond the tile) and sit out
                 float c[4][4];
+                fetch(ks);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int idx = t + u * G + g;
-                    ks[u] = e[idx < cnt ? idx : 0];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
+                    const int col = t + u * G + g < cnt ? ks[u].x : k0;
                     load_vec<4>(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ct) +
-                                                                ((unsigned)ks[u].x * (unsigned)kRowBytes + lb)),
+                                                                ((unsigned)col * (unsigned)kRowBytes + lb)),
                                 c[u]);
+                }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     if (t + u * G + g < cnt) {
