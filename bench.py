@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle's timed sample (0 = auto)")
     ap.add_argument("--no-fusion-report", action="store_true")
+    ap.add_argument("--bf16", action="store_true",
+                    help="also time the bfloat16-operand entry points on the same workload, beside the FP32 general "
+                         "path they share their kernels with (adds a `bf16_operands` object to the line)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB before the timed region: "
                          "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -252,6 +255,56 @@ def main():
         result["fusion"] = {"unfused_sddmm_then_spmm_ms": round(tu, 4), "fused_ms": round(tf, 4),
                             "fused_speedup": round(tu / tf, 3),
                             "max_abs_diff": float((Ou - Of).abs().max().item())}
+
+    if args.bf16:
+        # the paper's stated future work: dense operands in bfloat16, FP32 arithmetic.  Same workload; the
+        # bfloat16 calls run the general kernels, so the like-for-like FP32 figure is the general path
+        # (CSRK_KTILE=3, CSRK_ROWS as chosen) - the default FP32 figures above are the LDS-tiled kernels'.
+        def to_dev_bf16(a):
+            bits, _ = inputs.to_bf16(a)
+            return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+        calls16, calls32 = [], []
+        if "spmm" in w.ops:
+            B16 = to_dev_bf16(w.ops["spmm"]["B"])
+            calls16.append(("spmm", lambda: binding.spmm_csr_bf16(w.M, w.K, N, rp, ci, v, B16, O)))
+            calls32.append(("spmm", lambda: binding.spmm_csr(w.M, w.K, N, rp, ci, v, B, O)))
+        if "sddmm" in w.ops:
+            As16, Bs16 = to_dev_bf16(w.ops["sddmm"]["A"]), to_dev_bf16(w.ops["sddmm"]["B"])
+            calls16.append(("sddmm", lambda: binding.sddmm_csr_bf16(w.M, w.K, Ds, rp, ci, v, As16, Bs16, P)))
+            calls32.append(("sddmm", lambda: binding.sddmm_csr(w.M, w.K, Ds, rp, ci, v, As, Bs, P)))
+        if "fusedmm" in w.ops:
+            o = w.ops["fusedmm"]
+            Af16, Bf16, Cf16 = to_dev_bf16(o["A"]), to_dev_bf16(o["B"]), to_dev_bf16(o["C"])
+            calls16.append(("fusedmm", lambda: binding.fusedmm_csr_bf16(w.M, w.K, Df, Nf, rp, ci, v, Af16, Bf16, Cf16, Of)))
+            calls32.append(("fusedmm", lambda: binding.fusedmm_csr(w.M, w.K, Df, Nf, rp, ci, v, Af, Bf, Cf, Of)))
+
+        def time_calls(calls, reps=10):
+            out = {}
+            for name, fn in calls:
+                fn()
+                fn()
+                torch.cuda.synchronize()
+                binding.csrk_profile_enable(reps)
+                for _ in range(reps):
+                    fn()
+                torch.cuda.synchronize()
+                ms = [t for _, t in binding.csrk_profile_collect(reps + 4)]
+                binding.csrk_profile_enable(0)
+                out[name] = {"ms_min": round(min(ms), 4), "ms_avg": round(sum(ms) / len(ms), 4),
+                             "gflops_best": round(flops[name] / (min(ms) * 1e-3) / 1e9, 1)}
+            return out
+
+        r16 = time_calls(calls16)
+        saved = os.environ.get("CSRK_KTILE")
+        os.environ["CSRK_KTILE"] = "3"
+        r32 = time_calls(calls32)
+        if saved is None:
+            os.environ.pop("CSRK_KTILE", None)
+        else:
+            os.environ["CSRK_KTILE"] = saved
+        result["bf16_operands"] = {"bf16": r16, "fp32_general_path": r32,
+                                   "note": "whole calls; bf16 entry points and the FP32 general path share their kernels"}
 
     if not args.no_cpu_baseline:
         import oracle

@@ -96,6 +96,27 @@ csrk_status fusedmm_csr(int M, int K, int D, int N,
                         float *O, hipStream_t stream);
 
 /*
+ * The same three operations with the DENSE operands stored as bfloat16 (the upper 16
+ * bits of an IEEE single, row-major like their FP32 counterparts): the variant the
+ * paper names as future work (section "Conclusion").  The stored values of S, all
+ * arithmetic and the outputs stay FP32: every bfloat16 is widened exactly, products
+ * and sums are FP32 as in the calls above, so the result is what those calls give
+ * on the widened operands.  Same argument rules; B / A, B / A, B, C are device
+ * pointers to uint16_t.  These calls run the general kernels (half the bytes to
+ * gather); there are no LDS-tiled bfloat16 kernels.
+ */
+csrk_status spmm_csr_bf16(int M, int K, int N,
+                          const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                          const uint16_t *B, float *O, hipStream_t stream);
+csrk_status sddmm_csr_bf16(int M, int K, int D,
+                           const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                           const uint16_t *A, const uint16_t *B, float *P, hipStream_t stream);
+csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
+                             const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                             const uint16_t *A, const uint16_t *B, const uint16_t *C,
+                             float *O, hipStream_t stream);
+
+/*
  * Debug helper for untrusted inputs (the paper's storage rules, Fig. 1): checks
  * on the device that rowptr[0] == 0, rowptr is non-decreasing and every colidx
  * is in [0, K).  Synchronises `stream`.  *problems receives a bit mask:
@@ -117,7 +138,7 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
  * destroys the events and switches recording off.
  * csrk_profile_collect waits for the recorded pairs, writes up to `capacity`
  * elapsed times in milliseconds to ms[] and the operation of each to kinds[]
- * (1 SPMM, 2 SDDMM, 3 FusedMM) in call order, stores the number written in *count
+ * (1 SPMM, 2 SDDMM, 3 FusedMM; 11, 12, 13 for the bfloat16 variants) in call order, stores the number written in *count
  * and resets the recorder.  ms, kinds and count are host pointers.
  */
 csrk_status csrk_profile_enable(int max_records);

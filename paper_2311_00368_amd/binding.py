@@ -43,12 +43,16 @@ def load(build_if_missing: bool = True):
     lib.spmm_csr.argtypes = [i, i, i, p, p, p, p, p, p]
     lib.sddmm_csr.argtypes = [i, i, i, p, p, p, p, p, p, p]
     lib.fusedmm_csr.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p]
+    lib.spmm_csr_bf16.argtypes = [i, i, i, p, p, p, p, p, p]
+    lib.sddmm_csr_bf16.argtypes = [i, i, i, p, p, p, p, p, p, p]
+    lib.fusedmm_csr_bf16.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p]
     lib.csrk_validate_csr.argtypes = [i, i, p, p, p, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.csrk_release_workspace.argtypes = []
     lib.csrk_profile_enable.argtypes = [i]
     lib.csrk_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i,
                                          ctypes.POINTER(ctypes.c_int)]
-    for f in (lib.spmm_csr, lib.sddmm_csr, lib.fusedmm_csr, lib.csrk_validate_csr, lib.csrk_release_workspace,
+    for f in (lib.spmm_csr, lib.sddmm_csr, lib.fusedmm_csr, lib.spmm_csr_bf16, lib.sddmm_csr_bf16, lib.fusedmm_csr_bf16,
+              lib.csrk_validate_csr, lib.csrk_release_workspace,
               lib.csrk_profile_enable, lib.csrk_profile_collect):
         f.restype = ctypes.c_int
     lib.csrk_last_error.restype = ctypes.c_char_p
@@ -138,6 +142,45 @@ def fusedmm_csr(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O
                                _dev_ptr(B, "B", torch.float32, (K, D), dev),
                                _dev_ptr(C, "C", torch.float32, (K, N), dev),
                                _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+def spmm_csr_bf16(M: int, K: int, N: int, rowptr, colidx, vals, B, O=None) -> torch.Tensor:
+    """spmm_csr with B stored as bfloat16 (torch.bfloat16, K x N); O and vals are FP32."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.spmm_csr_bf16(M, K, N, rp, ci, va, _dev_ptr(B, "B", torch.bfloat16, (K, N), dev),
+                                 _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+def sddmm_csr_bf16(M: int, K: int, D: int, rowptr, colidx, vals, A, B, P=None) -> torch.Tensor:
+    """sddmm_csr with A (M x D) and B (K x D) stored as bfloat16; P and vals are FP32."""
+    lib = load()
+    dev, nnz, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if P is None:
+        P = torch.empty((nnz,), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.sddmm_csr_bf16(M, K, D, rp, ci, va, _dev_ptr(A, "A", torch.bfloat16, (M, D), dev),
+                                  _dev_ptr(B, "B", torch.bfloat16, (K, D), dev),
+                                  _dev_ptr(P, "P", torch.float32, (nnz,), dev), _stream(dev)))
+    return P
+
+
+def fusedmm_csr_bf16(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O=None) -> torch.Tensor:
+    """fusedmm_csr with A, B (x D) and C (K x N) stored as bfloat16; O and vals are FP32."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.fusedmm_csr_bf16(M, K, D, N, rp, ci, va, _dev_ptr(A, "A", torch.bfloat16, (M, D), dev),
+                                    _dev_ptr(B, "B", torch.bfloat16, (K, D), dev),
+                                    _dev_ptr(C, "C", torch.bfloat16, (K, N), dev),
+                                    _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
     return O
 
 

@@ -678,6 +678,50 @@ __global__ void validate_colidx_kernel(int M, int K, const int32_t *rowptr, cons
     }
 }
 
+// ---- bfloat16 dense operands (stored values and outputs stay FP32, arithmetic is FP32) -------------------
+// The general kernels only (equal shares, or whole rows where the row analysis finds the rows even): a group of
+// LG lanes covers the width with 8 bfloat16 (one 128-bit load) per lane.
+
+WidthCfg out_width_cfg_bf16(int N, bool vec8) {
+    if (vec8) {
+        if (N <= 64) return {8, 8, 1};
+        if (N <= 128) return {8, 16, 1};
+        if (N <= 256) return {8, 32, 1};
+        if (N <= 512) return {8, 64, 1};
+        return {8, 64, 2};
+    }
+    return {1, 64, 1};
+}
+
+WidthCfg dot_width_cfg_bf16(int D, bool vec8) {
+    if (vec8) {
+        if (D <= 64) return {8, 8, 1};
+        if (D <= 128) return {8, 16, 1};
+        return {8, 64, 0};
+    }
+    return {1, 64, 0};
+}
+
+template <int VD, int LD, int TD>
+bool launch_fused_bf16_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp,
+                         const int32_t *ci, const float *v, const bf16_t *A, const bf16_t *B, const bf16_t *C, float *O,
+                         float *head, int32_t *head_row, const int32_t *even) {
+#define CSRK_FUSED_BF16_CASE(VN, LN, TN)                                                                          \
+    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                              \
+        hipLaunchKernelGGL((fusedmm_nnzsplit_kernel<VD, LD, TD, VN, LN, TN, bf16_t>), grid, dim3(kBlockThreads), 0, st, \
+                           M, D, N, rp, ci, v, A, B, C, O, head, head_row, nullptr, even);                        \
+        return true;                                                                                              \
+    }
+    CSRK_FUSED_BF16_CASE(8, 8, 1)
+    CSRK_FUSED_BF16_CASE(8, 16, 1)
+    CSRK_FUSED_BF16_CASE(8, 32, 1)
+    CSRK_FUSED_BF16_CASE(8, 64, 1)
+    CSRK_FUSED_BF16_CASE(8, 64, 2)
+    CSRK_FUSED_BF16_CASE(1, 64, 1)
+#undef CSRK_FUSED_BF16_CASE
+    return false;
+}
+
 }  // namespace
 
 extern "C" {
@@ -753,7 +797,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, even, c.vec == 4 && c.t == 1, vec4);
+    launch_combine(*d, stream, M, N, O, gate, even, c.vec >= 4 && c.t == 1, vec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
@@ -881,6 +925,118 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
     launch_combine(*d, stream, M, N, O, gate, even, false, nvec4);
+    rec.end();
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                          const uint16_t *B, float *O, hipStream_t stream) {
+    if (csrk_status s = check_dims("spmm_csr_bf16", M, K, N, 0)) return s;
+    if (M == 0 || N == 0) return CSRK_OK;
+    if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr_bf16: rowptr and O must not be NULL");
+    if (K > 0 && !B) return fail(CSRK_INVALID_ARG, "spmm_csr_bf16: B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    d->pending_ksplit = 0;
+    if (csrk_status s = ensure_scratch(*d, N)) return s;
+    const bool vec8 = (N % 8 == 0) && aligned16(B) && aligned16(O) && aligned16(d->head);
+    const WidthCfg c = out_width_cfg_bf16(N, vec8);
+    const int tile = c.vec * c.lg * c.t;
+    const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
+    CallRecord rec(11, stream);
+    rec.begin();
+    const int32_t *even = nullptr;
+    if (even_rows_worth_asking(*d, M, K, false)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
+        even = tile_flags(*d) + 3;
+    }
+#define CSRK_SPMM_BF16_CASE(V, L, T)                                                                               \
+    if (c.vec == V && c.lg == L && c.t == T)                                                                       \
+        hipLaunchKernelGGL((spmm_nnzsplit_kernel<V, L, T, bf16_t>), grid, dim3(kBlockThreads), 0, stream, M, N, rowptr, \
+                           colidx, vals, B, O, d->head, d->head_row, nullptr, even);
+    CSRK_SPMM_BF16_CASE(8, 8, 1)
+    CSRK_SPMM_BF16_CASE(8, 16, 1)
+    CSRK_SPMM_BF16_CASE(8, 32, 1)
+    CSRK_SPMM_BF16_CASE(8, 64, 1)
+    CSRK_SPMM_BF16_CASE(8, 64, 2)
+    CSRK_SPMM_BF16_CASE(1, 64, 1)
+#undef CSRK_SPMM_BF16_CASE
+    CSRK_HIP(hipGetLastError());
+    launch_combine(*d, stream, M, N, O, nullptr, even, c.vec >= 4 && c.t == 1, vec8);
+    rec.end();
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status sddmm_csr_bf16(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                           const uint16_t *A, const uint16_t *B, float *P, hipStream_t stream) {
+    if (csrk_status s = check_dims("sddmm_csr_bf16", M, K, D, 0)) return s;
+    if (M == 0 || K == 0) return CSRK_OK;
+    if (!rowptr) return fail(CSRK_INVALID_ARG, "sddmm_csr_bf16: rowptr must not be NULL");
+    if (D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "sddmm_csr_bf16: A and B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    const bool vec8 = (D % 8 == 0) && D > 0 && aligned16(A) && aligned16(B);
+    const WidthCfg c = dot_width_cfg_bf16(D, vec8);
+    const dim3 grid(d->workers / kWavesPerBlock);
+    CallRecord rec(12, stream);
+    rec.begin();
+#define CSRK_SDDMM_BF16_CASE(V, L, T)                                                                              \
+    if (c.vec == V && c.lg == L && c.t == T)                                                                       \
+        hipLaunchKernelGGL((sddmm_nnzsplit_kernel<V, L, T, bf16_t>), grid, dim3(kBlockThreads), 0, stream, M, D, rowptr, \
+                           colidx, vals, A, B, P, nullptr, nullptr);
+    CSRK_SDDMM_BF16_CASE(8, 8, 1)
+    CSRK_SDDMM_BF16_CASE(8, 16, 1)
+    CSRK_SDDMM_BF16_CASE(8, 64, 0)
+    CSRK_SDDMM_BF16_CASE(1, 64, 0)
+#undef CSRK_SDDMM_BF16_CASE
+    rec.end();
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status fusedmm_csr_bf16(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx,
+                             const float *vals, const uint16_t *A, const uint16_t *B, const uint16_t *C, float *O,
+                             hipStream_t stream) {
+    if (csrk_status s = check_dims("fusedmm_csr_bf16", M, K, D, N)) return s;
+    if (M == 0 || N == 0) return CSRK_OK;
+    if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: rowptr and O must not be NULL");
+    if (K > 0 && !C) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: C must not be NULL");
+    if (K > 0 && D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: A and B must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    d->pending_ksplit = 0;
+    if (csrk_status s = ensure_scratch(*d, N)) return s;
+    const bool dvec8 = (D % 8 == 0) && D > 0 && aligned16(A) && aligned16(B);
+    const bool nvec8 = (N % 8 == 0) && aligned16(C) && aligned16(O) && aligned16(d->head);
+    const WidthCfg dc = dot_width_cfg_bf16(D, dvec8);
+    const WidthCfg nc = out_width_cfg_bf16(N, nvec8);
+    const int tile = nc.vec * nc.lg * nc.t;
+    const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
+    CallRecord rec(13, stream);
+    rec.begin();
+    const int32_t *even = nullptr;
+    if (even_rows_worth_asking(*d, M, K, true)) {
+        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
+        even = tile_flags(*d) + 3;
+    }
+    bool done = false;
+#define CSRK_DOT_BF16_CASE(V, L, T)                                                                                \
+    if (!done && dc.vec == V && dc.lg == L && dc.t == T)                                                           \
+        done = launch_fused_bf16_n<V, L, T>(nc, grid, stream, M, D, N, rowptr, colidx, vals, A, B, C, O, d->head,  \
+                                            d->head_row, even);
+    CSRK_DOT_BF16_CASE(8, 8, 1)
+    CSRK_DOT_BF16_CASE(8, 16, 1)
+    CSRK_DOT_BF16_CASE(8, 64, 0)
+    CSRK_DOT_BF16_CASE(1, 64, 0)
+#undef CSRK_DOT_BF16_CASE
+    if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr_bf16: no kernel for D=%d N=%d", D, N);
+    CSRK_HIP(hipGetLastError());
+    launch_combine(*d, stream, M, N, O, nullptr, even, false, nvec8);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;

@@ -61,22 +61,49 @@ __device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
     }
 }
 
-// VEC consecutive floats; VEC == 4 is one 128-bit access (address must be 16-byte aligned).
+// VEC consecutive floats; VEC a multiple of 4: 128-bit accesses (address must be 16-byte aligned).
 template <int VEC>
 __device__ __forceinline__ void load_vec(const float *p, float (&d)[VEC]) {
-    if constexpr (VEC == 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(p);
-        d[0] = t.x; d[1] = t.y; d[2] = t.z; d[3] = t.w;
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(p + i);
+            d[i] = t.x; d[i + 1] = t.y; d[i + 2] = t.z; d[i + 3] = t.w;
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) d[i] = p[i];
     }
 }
 
+// bfloat16 as stored (the upper half of an IEEE single); arithmetic is always done in FP32
+using bf16_t = uint16_t;
+
+// VEC consecutive bfloat16 widened to floats; VEC == 8 is one 128-bit access (16-byte aligned address).
+// Widening is exact: the 16 bits become the upper half of the float.
+template <int VEC>
+__device__ __forceinline__ void load_vec(const bf16_t *p, float (&d)[VEC]) {
+    if constexpr (VEC == 8) {
+        const uint4 t = *reinterpret_cast<const uint4 *>(p);
+        const unsigned w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            d[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+            d[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) d[i] = __builtin_bit_cast(float, (unsigned)p[i] << 16);
+    }
+}
+
+// VEC a multiple of 4: 128-bit accesses (16-byte aligned address)
 template <int VEC>
 __device__ __forceinline__ void store_vec(float *p, const float (&d)[VEC]) {
-    if constexpr (VEC == 4) {
-        *reinterpret_cast<float4 *>(p) = make_float4(d[0], d[1], d[2], d[3]);
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4)
+            *reinterpret_cast<float4 *>(p + i) = make_float4(d[i], d[i + 1], d[i + 2], d[i + 3]);
     } else {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) p[i] = d[i];

@@ -60,8 +60,8 @@ __device__ __forceinline__ void for_unrolled(int t0, int t1, int stride, F &&f) 
 // step, with columns beyond N moved to column 0 and steps beyond the chunk's end moved
 // to entry t0, and the condition is applied to the multiply-adds instead.
 // ---------------------------------------------------------------------------------
-template <int VEC, int LG, int T>
-__device__ __forceinline__ void gather_axpy(int kc, float sc, int t0, int t1, const float *__restrict__ Mat, int N,
+template <int VEC, int LG, int T, typename E>
+__device__ __forceinline__ void gather_axpy(int kc, float sc, int t0, int t1, const E *__restrict__ Mat, int N,
                                             int n, float (&acc)[T][VEC]) {
     constexpr int NPAR = kWave / LG;
     constexpr int TW = LG * VEC;
@@ -94,7 +94,7 @@ __device__ __forceinline__ void gather_axpy(int kc, float sc, int t0, int t1, co
                 k = __shfl(kc, src);
                 s[u] = __shfl(sc, src);
             }
-            const float *row = Mat + (size_t)k * N;
+            const E *row = Mat + (size_t)k * N;
 #pragma unroll
             for (int tt = 0; tt < T; ++tt) load_vec<VEC>(row + off[tt], b[u][tt]);
         }
@@ -115,10 +115,10 @@ __device__ __forceinline__ void gather_axpy(int kc, float sc, int t0, int t1, co
 // ---------------------------------------------------------------------------------
 // SPMM segment: acc[t][v] += sum_{j in [s0,s1)} vals[j] * Bmat[colidx[j], n + t*TW + v]
 // ---------------------------------------------------------------------------------
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E>
 __device__ __forceinline__ void spmm_segment(int s0, int s1, const int32_t *__restrict__ colidx,
                                              const float *__restrict__ vals,
-                                             const float *__restrict__ Bmat, int N, int n,
+                                             const E *__restrict__ Bmat, int N, int n,
                                              float (&acc)[T][VEC]) {
     const int lane = lane_id();
     if (s1 <= s0) return;
@@ -212,16 +212,16 @@ __device__ __forceinline__ void add_row_parts(RowParts<VEC, LG, T> &lds, int wv,
 
 // instantiations of the general SPMM kernel whose whole-row branch shares rows between wavefronts whatever M is
 template <int VEC, int LG, int T>
-constexpr bool kSpmmRowsAnyM = VEC == 4 && T == 1;
+constexpr bool kSpmmRowsAnyM = VEC >= 4 && T == 1;
 
 // wavefronts per row when the kernel decides for itself (the whole-row branch of the general SPMM and SDDMM
 // kernels): W is the number of wavefronts in the grid
 __device__ __forceinline__ int rows_wpr_for(int M, int W) { return 2ll * M > W ? 1 : (4ll * M > W ? 2 : 4); }
 
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E>
 __device__ __forceinline__ void spmm_rows_body(int M, int N, const int32_t *__restrict__ rowptr,
                                                const int32_t *__restrict__ colidx, const float *__restrict__ vals,
-                                               const float *__restrict__ Bmat, float *__restrict__ O, int wpr,
+                                               const E *__restrict__ Bmat, float *__restrict__ O, int wpr,
                                                RowParts<VEC, LG, T> &lds) {
     constexpr int TW = LG * VEC;
     const int lane = lane_id();
@@ -246,18 +246,18 @@ __device__ __forceinline__ void spmm_rows_body(int M, int N, const int32_t *__re
     }
 }
 
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void spmm_rows_kernel(
     int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O, int wpr) {
+    const float *__restrict__ vals, const E *__restrict__ Bmat, float *__restrict__ O, int wpr) {
     __shared__ RowParts<VEC, LG, T> lds;
     spmm_rows_body<VEC, LG, T>(M, N, rowptr, colidx, vals, Bmat, O, wpr, lds);
 }
 
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void spmm_nnzsplit_kernel(
     int M, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ Bmat, float *__restrict__ O,
+    const float *__restrict__ vals, const E *__restrict__ Bmat, float *__restrict__ O,
     float *__restrict__ head, int32_t *__restrict__ head_row, const int32_t *__restrict__ gate,
     const int32_t *__restrict__ even) {
     constexpr int TW = LG * VEC;
@@ -373,9 +373,9 @@ __global__ __launch_bounds__(kBlockThreads) void combine_heads_kernel(int M, int
 // ---------------------------------------------------------------------------------
 // T > 0: the A row sits in registers (`a`, T tiles of LG*VEC columns).  T == 0: any D,
 // tiles are walked at run time and the A row is re-read from memory (it stays in L1).
-template <int VEC, int LG, int T>
-__device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float *__restrict__ Bmat, int D,
-                                            int d, const float *__restrict__ arow,
+template <int VEC, int LG, int T, typename E>
+__device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const E *__restrict__ Bmat, int D,
+                                            int d, const E *__restrict__ arow,
                                             const float (&a)[T > 0 ? T : 1][VEC], float *slot) {
     constexpr int NPAR = kWave / LG;
     constexpr int TW = LG * VEC;
@@ -400,7 +400,7 @@ __device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float 
                 const int idx = t + u * NPAR + g;
                 const int src = (idx >= t0 && idx < t1) ? idx : t0;
                 const int k = (NPAR == 1) ? __builtin_amdgcn_readlane(kc, uniform(src)) : __shfl(kc, src);
-                const float *brow = Bmat + (size_t)k * D;
+                const E *brow = Bmat + (size_t)k * D;
 #pragma unroll
                 for (int tt = 0; tt < T; ++tt) load_vec<VEC>(brow + off[tt], b[u][tt]);
             }
@@ -428,7 +428,7 @@ __device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float 
             const bool act = idx >= t0 && idx < t1;
             float part = 0.f;
             if (act) {
-                const float *brow = Bmat + (size_t)k * D + d;
+                const E *brow = Bmat + (size_t)k * D + d;
                 for (int dd = 0; d + dd < D; dd += TW) {
                     float b[VEC], av[VEC];
                     load_vec<VEC>(brow + dd, b);
@@ -443,8 +443,8 @@ __device__ __forceinline__ void sddmm_chunk(int kc, int t0, int t1, const float 
     }
 }
 
-template <int VEC, int LG, int T>
-__device__ __forceinline__ void load_a_row(const float *__restrict__ arow, int D, int d,
+template <int VEC, int LG, int T, typename E>
+__device__ __forceinline__ void load_a_row(const E *__restrict__ arow, int D, int d,
                                            float (&a)[T > 0 ? T : 1][VEC]) {
     constexpr int TW = LG * VEC;
     if constexpr (T > 0) {
@@ -465,13 +465,13 @@ __device__ __forceinline__ void load_a_row(const float *__restrict__ arow, int D
 
 // P[j] = vals[j] * <A[r, :], Bmat[colidx[j], :]> for the stored entries [s0, s1) of row r (Algorithm 1's inner
 // loops), a chunk of 64 entries at a time.  P may alias vals.
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E>
 __device__ __forceinline__ void sddmm_segment(int r, int s0, int s1, const int32_t *__restrict__ colidx,
-                                              const float *vals, const float *__restrict__ A,
-                                              const float *__restrict__ Bmat, float *P, int D, int d, float *slot) {
+                                              const float *vals, const E *__restrict__ A,
+                                              const E *__restrict__ Bmat, float *P, int D, int d, float *slot) {
     if (s1 <= s0) return;
     const int lane = lane_id();
-    const float *arow = A + (size_t)r * D;
+    const E *arow = A + (size_t)r * D;
     float a[T > 0 ? T : 1][VEC];
     load_a_row<VEC, LG, T>(arow, D, d, a);
     for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
@@ -490,10 +490,10 @@ __device__ __forceinline__ void sddmm_segment(int r, int s0, int s1, const int32
 
 // SDDMM with a row per 1, 2 or 4 wavefronts (consecutive parts of the row; outputs are per stored entry, so
 // nothing to add up): see spmm_rows_kernel.
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E>
 __device__ __forceinline__ void sddmm_rows_body(int M, int D, const int32_t *__restrict__ rowptr,
                                                 const int32_t *__restrict__ colidx, const float *vals,
-                                                const float *__restrict__ A, const float *__restrict__ Bmat, float *P,
+                                                const E *__restrict__ A, const E *__restrict__ Bmat, float *P,
                                                 int wpr, float *slot) {
     const int lane = lane_id();
     const int wv = uniform(threadIdx.x >> 6);
@@ -508,19 +508,19 @@ __device__ __forceinline__ void sddmm_rows_body(int M, int D, const int32_t *__r
     }
 }
 
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_rows_kernel(
     int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
-    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int wpr) {
+    const E *__restrict__ A, const E *__restrict__ Bmat, float *P, int wpr) {
     __shared__ float slots[kWavesPerBlock][kWave];
     sddmm_rows_body<VEC, LG, T>(M, D, rowptr, colidx, vals, A, Bmat, P, wpr, slots[threadIdx.x >> 6]);
 }
 
 // P may alias vals, so neither is __restrict__.
-template <int VEC, int LG, int T>
+template <int VEC, int LG, int T, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
     int M, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P,
+    const float *vals, const E *__restrict__ A, const E *__restrict__ Bmat, float *P,
     const int32_t *__restrict__ gate, const int32_t *__restrict__ even) {
     __shared__ float slots[kWavesPerBlock][kWave];
     if (gate && ktile_ok(gate)) return;     // the LDS-tiled kernel has done this call
@@ -556,14 +556,14 @@ __global__ __launch_bounds__(kBlockThreads) void sddmm_nnzsplit_kernel(
 // them from there; scores never reach device memory (Algorithm 3's `arow`).
 // Dot stage uses (VD, LD, TD) over D, the accumulate stage (VN, LN, TN) over N.
 // ---------------------------------------------------------------------------------
-template <int VD, int LD, int TD, int VN, int LN, int TN>
+template <int VD, int LD, int TD, int VN, int LN, int TN, typename E>
 __device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int32_t *__restrict__ colidx,
-                                              const float *__restrict__ vals, const float *__restrict__ A,
-                                              const float *__restrict__ Bmat, const float *__restrict__ Cmat,
+                                              const float *__restrict__ vals, const E *__restrict__ A,
+                                              const E *__restrict__ Bmat, const E *__restrict__ Cmat,
                                               int D, int N, int d, int n, float *slot, float (&acc)[TN][VN]) {
     if (s1 <= s0) return;
     const int lane = lane_id();
-    const float *arow = A + (size_t)row * D;
+    const E *arow = A + (size_t)row * D;
     float a[TD > 0 ? TD : 1][VD];
     load_a_row<VD, LD, TD>(arow, D, d, a);
     for (int base = s0 & ~(kWave - 1); base < s1; base += kWave) {
@@ -582,11 +582,11 @@ __device__ __forceinline__ void fused_segment(int row, int s0, int s1, const int
 }
 
 // FusedMM with a row per 1, 2 or 4 wavefronts: see spmm_rows_kernel.
-template <int VD, int LD, int TD, int VN, int LN, int TN>
+template <int VD, int LD, int TD, int VN, int LN, int TN, typename E>
 __device__ __forceinline__ void fusedmm_rows_body(int M, int D, int N, const int32_t *__restrict__ rowptr,
                                                   const int32_t *__restrict__ colidx, const float *__restrict__ vals,
-                                                  const float *__restrict__ A, const float *__restrict__ Bmat,
-                                                  const float *__restrict__ Cmat, float *__restrict__ O, int wpr,
+                                                  const E *__restrict__ A, const E *__restrict__ Bmat,
+                                                  const E *__restrict__ Cmat, float *__restrict__ O, int wpr,
                                                   float *slot, RowParts<VN, LN, TN> &lds) {
     constexpr int TWN = LN * VN;
     const int lane = lane_id();
@@ -613,22 +613,22 @@ __device__ __forceinline__ void fusedmm_rows_body(int M, int D, int N, const int
     }
 }
 
-template <int VD, int LD, int TD, int VN, int LN, int TN>
+template <int VD, int LD, int TD, int VN, int LN, int TN, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_rows_kernel(
     int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int wpr) {
+    const float *__restrict__ vals, const E *__restrict__ A, const E *__restrict__ Bmat,
+    const E *__restrict__ Cmat, float *__restrict__ O, int wpr) {
     __shared__ float slots[kWavesPerBlock][kWave];
     __shared__ RowParts<VN, LN, TN> lds;
     fusedmm_rows_body<VD, LD, TD, VN, LN, TN>(M, D, N, rowptr, colidx, vals, A, Bmat, Cmat, O, wpr,
                                               slots[threadIdx.x >> 6], lds);
 }
 
-template <int VD, int LD, int TD, int VN, int LN, int TN>
+template <int VD, int LD, int TD, int VN, int LN, int TN, typename E = float>
 __global__ __launch_bounds__(kBlockThreads) void fusedmm_nnzsplit_kernel(
     int M, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-    const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, float *__restrict__ head,
+    const float *__restrict__ vals, const E *__restrict__ A, const E *__restrict__ Bmat,
+    const E *__restrict__ Cmat, float *__restrict__ O, float *__restrict__ head,
     int32_t *__restrict__ head_row, const int32_t *__restrict__ gate, const int32_t *__restrict__ even) {
     __shared__ float slots[kWavesPerBlock][kWave];
     constexpr int TWN = LN * VN;

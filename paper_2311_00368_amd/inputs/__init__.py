@@ -110,6 +110,19 @@ def lognormal_csr(seed: int, M: int, K: int, mean: float, sigma: float,
 # values in row-major order, rowptr has M+1 entries with rowptr[M] = nnz)
 # ---------------------------------------------------------------------------
 
+def to_bf16(a: np.ndarray):
+    """Round an FP32 array to bfloat16 (round to nearest, ties to even; NaN stays NaN).  Returns
+    (bits, widened): the uint16 bit patterns, and the same values widened back to FP32 - what a consumer
+    of the bfloat16 array sees.  Input preparation for the bfloat16 entry points, no arithmetic of the method."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32)
+    rounded = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)
+    nan = np.isnan(a)
+    bits = np.where(nan, (u >> np.uint32(16)) | np.uint32(0x40), rounded).astype(np.uint16)
+    widened = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return bits, widened.reshape(a.shape)
+
+
 def csr_from_dense(dense: np.ndarray):
     """Store the entries of `dense` that are != 0, row by row, columns ascending."""
     dense = np.asarray(dense)

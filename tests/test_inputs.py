@@ -99,3 +99,12 @@ def test_workload_shapes_scaled():
     assert w.M == 512 and w.ops["spmm"]["B"].shape == (512, 512)
     assert w.ops["fusedmm"]["A"].shape == (512, 64) and w.ops["fusedmm"]["B"].shape == (512, 64)
     assert abs(w.nnz / (w.M * w.K) - 0.2) < 0.01
+
+
+def test_rounding_helper_matches_the_definition():
+    # bfloat16 = the upper 16 bits of a single, round to nearest even: spot values with known patterns
+    a = np.array([1.0, -2.0, 0.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -8, 3.0e38, np.inf],
+                 dtype=np.float32)
+    bits, w = inputs.to_bf16(a)
+    assert bits.tolist() == [0x3F80, 0xC000, 0x0000, 0x3F80, 0x3F81, 0x3F82, 0x7F62, 0x7F80]
+    assert w[3] == 1.0 and w[4] == np.float32(1.0 + 2.0 ** -7)
