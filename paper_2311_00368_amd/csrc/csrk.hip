@@ -703,6 +703,25 @@ WidthCfg dot_width_cfg_bf16(int D, bool vec8) {
 }
 
 template <int VD, int LD, int TD>
+bool launch_fused_rows_bf16_n(const WidthCfg &nc, hipStream_t st, int M, int D, int N, const int32_t *rp,
+                              const int32_t *ci, const float *v, const bf16_t *A, const bf16_t *B, const bf16_t *C,
+                              float *O) {
+#define CSRK_FUSED_ROWS_BF16_CASE(VN, LN, TN)                                                                     \
+    if (nc.vec == VN && nc.lg == LN && nc.t == TN) {                                                              \
+        const int wpr = rows_wpr(M, N);                                                                           \
+        hipLaunchKernelGGL((fusedmm_rows_kernel<VD, LD, TD, VN, LN, TN, bf16_t>), rows_grid(M, wpr, 1),            \
+                           dim3(kBlockThreads), 0, st, M, D, N, rp, ci, v, A, B, C, O, wpr);                      \
+        return true;                                                                                              \
+    }
+    CSRK_FUSED_ROWS_BF16_CASE(8, 8, 1)
+    CSRK_FUSED_ROWS_BF16_CASE(8, 16, 1)
+    CSRK_FUSED_ROWS_BF16_CASE(8, 32, 1)
+    CSRK_FUSED_ROWS_BF16_CASE(8, 64, 1)
+#undef CSRK_FUSED_ROWS_BF16_CASE
+    return false;
+}
+
+template <int VD, int LD, int TD>
 bool launch_fused_bf16_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, int D, int N, const int32_t *rp,
                          const int32_t *ci, const float *v, const bf16_t *A, const bf16_t *B, const bf16_t *C, float *O,
                          float *head, int32_t *head_row, const int32_t *even) {
@@ -947,6 +966,23 @@ csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int3
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     CallRecord rec(11, stream);
     rec.begin();
+    if (vec8 && rows_mode_ok(M, K, N, false)) {     // small S: a row per 1, 2 or 4 wavefronts, one launch
+        const int wpr = rows_wpr(M, N);
+        const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
+#define CSRK_SPMM_ROWS_BF16_CASE(V, L, T)                                                                          \
+    if (c.vec == V && c.lg == L && c.t == T)                                                                       \
+        hipLaunchKernelGGL((spmm_rows_kernel<V, L, T, bf16_t>), rgrid, dim3(kBlockThreads), 0, stream, M, N, rowptr, \
+                           colidx, vals, B, O, wpr);
+        CSRK_SPMM_ROWS_BF16_CASE(8, 8, 1)
+        CSRK_SPMM_ROWS_BF16_CASE(8, 16, 1)
+        CSRK_SPMM_ROWS_BF16_CASE(8, 32, 1)
+        CSRK_SPMM_ROWS_BF16_CASE(8, 64, 1)
+        CSRK_SPMM_ROWS_BF16_CASE(8, 64, 2)
+#undef CSRK_SPMM_ROWS_BF16_CASE
+        rec.end();
+        CSRK_HIP(hipGetLastError());
+        return CSRK_OK;
+    }
     const int32_t *even = nullptr;
     if (even_rows_worth_asking(*d, M, K, false)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
@@ -984,6 +1020,19 @@ csrk_status sddmm_csr_bf16(int M, int K, int D, const int32_t *rowptr, const int
     const dim3 grid(d->workers / kWavesPerBlock);
     CallRecord rec(12, stream);
     rec.begin();
+    if (vec8 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
+        const int wpr = rows_wpr(M, D);
+        const dim3 rgrid = rows_grid(M, wpr, 1);
+        if (c.lg == 8)
+            hipLaunchKernelGGL((sddmm_rows_kernel<8, 8, 1, bf16_t>), rgrid, dim3(kBlockThreads), 0, stream, M, D, rowptr,
+                               colidx, vals, A, B, P, wpr);
+        else
+            hipLaunchKernelGGL((sddmm_rows_kernel<8, 16, 1, bf16_t>), rgrid, dim3(kBlockThreads), 0, stream, M, D, rowptr,
+                               colidx, vals, A, B, P, wpr);
+        rec.end();
+        CSRK_HIP(hipGetLastError());
+        return CSRK_OK;
+    }
 #define CSRK_SDDMM_BF16_CASE(V, L, T)                                                                              \
     if (c.vec == V && c.lg == L && c.t == T)                                                                       \
         hipLaunchKernelGGL((sddmm_nnzsplit_kernel<V, L, T, bf16_t>), grid, dim3(kBlockThreads), 0, stream, M, D, rowptr, \
@@ -1019,6 +1068,16 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N, const int32_t *rowptr, 
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     CallRecord rec(13, stream);
     rec.begin();
+    if (nvec8 && dvec8 && dc.t == 1 && N <= 512 && rows_mode_ok(M, K, N, true)) {
+        const bool launched =
+            dc.lg == 8 ? launch_fused_rows_bf16_n<8, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O)
+                       : launch_fused_rows_bf16_n<8, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
+        if (launched) {
+            rec.end();
+            CSRK_HIP(hipGetLastError());
+            return CSRK_OK;
+        }
+    }
     const int32_t *even = nullptr;
     if (even_rows_worth_asking(*d, M, K, true)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;

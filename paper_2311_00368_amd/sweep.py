@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "sweep72.md"))
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--limit", type=int, default=0, help="only the first LIMIT grid points (debug)")
+    ap.add_argument("--bf16", action="store_true",
+                    help="dense operands rounded to bfloat16 and the *_csr_bf16 entry points instead of the FP32 ones")
     args = ap.parse_args()
 
     import torch
@@ -81,6 +83,15 @@ def main():
             "spmm": (lambda: binding.spmm_csr(M, K, n, rp, ci, v, C, O), 2.0 * nnz * n),
             "fusedmm": (lambda: binding.fusedmm_csr(M, K, D, n, rp, ci, v, A, B, C, O), 2.0 * nnz * (D + n)),
         }
+        if args.bf16:
+            import numpy as np
+            h = lambda a: torch.from_numpy(inputs.to_bf16(a)[0].view(np.int16)).cuda().view(torch.bfloat16)
+            A16, B16, C16 = h(w.ops["fusedmm"]["A"]), h(w.ops["fusedmm"]["B"]), h(w.ops["fusedmm"]["C"])
+            calls = {
+                "sddmm": (lambda: binding.sddmm_csr_bf16(M, K, D, rp, ci, v, A16, B16, P), 2.0 * nnz * D),
+                "spmm": (lambda: binding.spmm_csr_bf16(M, K, n, rp, ci, v, C16, O), 2.0 * nnz * n),
+                "fusedmm": (lambda: binding.fusedmm_csr_bf16(M, K, D, n, rp, ci, v, A16, B16, C16, O), 2.0 * nnz * (D + n)),
+            }
         res = {}
         for name, (fn, flops) in calls.items():
             fn()
