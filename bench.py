@@ -72,7 +72,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus N with N > 1 is not supported "
-              "(row-sharding across GPUs is described in DESIGN.md but not built).", file=sys.stderr)
+              "(row-sharding across GPUs is a design note only, not built).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

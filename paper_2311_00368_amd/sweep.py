@@ -1,6 +1,6 @@
 """The paper's 72-shape benchmark grid as synthetic inputs, on one MI355X.
 
-    python -m paper_2311_00368_amd.sweep [--out gpurun_out/sweep72.md] [--iters 10]
+    python -m paper_2311_00368_amd.sweep [--out sweep72.md] [--iters 10] [--bf16]
 
 The grid is the one on the x axes of the paper's benchmark figures: 12 (M, K) pairs x sparsity
 70 / 80 / 90 % x N in {32, 128}, with D = N as in the paper.  The paper's own matrices (the
@@ -10,19 +10,15 @@ point SPMM, SDDMM and FusedMM run `iters` times after two warm-ups; the time is 
 the runs (the paper's protocol: minimum of 20 back-to-back runs) of the HIP-event pair the
 library records around each call's kernels.  Gflop/s use 2*nnz*N, 2*nnz*D and 2*nnz*(D+N).
 
-The output is a markdown table.  If the repository's benchmark is present its table of the
-paper's bars (Intel Data Center GPU Max 1550, one stack; other hardware, context only) is put
-next to the measured numbers.
+The output is a markdown table; the bars of the paper's figures (Intel Data Center GPU Max 1550,
+one stack; other hardware, context only; `paper_grid_bars.txt`) are put next to the measured numbers.
 """
 from __future__ import annotations
 
 import argparse
 import os
-import re
 import sys
 import time
-
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 MK = [(1, 1), (3, 1), (4, 1), (2, 2), (6, 2), (8, 2), (4, 4), (12, 4), (16, 4), (8, 8), (24, 8), (32, 8)]
 SPARSITY = [70, 80, 90]
@@ -30,26 +26,20 @@ WIDTHS = [32, 128]
 
 
 def paper_bars():
-    """{(Mk, Kk, sparsity): [sddmm32, sddmm128, spmm32, spmm128, fused32, fused128]} from BASELINE.md."""
-    path = os.path.join(ROOT, "BASELINE.md")
+    """{(Mk, Kk, sparsity): [sddmm32, sddmm128, spmm32, spmm128, fused32, fused128]}: the bars of the paper's
+    benchmark figures (section "Performance results"), from the text file next to this module."""
     out = {}
-    try:
-        text = open(path).read()
-    except OSError:
-        return out
-    for line in text.splitlines():
-        m = re.match(r"\|\s*\d+\s*\|\s*(\d+)k/(\d+)k/(\d+)%\s*\|(.*)\|\s*$", line)
-        if m:
-            cells = [c.strip() for c in m.group(4).split("|")]
-            vals = [int(re.match(r"(\d+)", c).group(1)) for c in cells if re.match(r"\d+", c)]
-            if len(vals) == 6:
-                out[(int(m.group(1)), int(m.group(2)), int(m.group(3)))] = vals
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_grid_bars.txt")) as f:
+        for line in f:
+            cells = line.split("#")[0].split()
+            if len(cells) == 9:
+                out[(int(cells[0]), int(cells[1]), int(cells[2]))] = [int(c) for c in cells[3:]]
     return out
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "sweep72.md"))
+    ap.add_argument("--out", default="sweep72.md")
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--limit", type=int, default=0, help="only the first LIMIT grid points (debug)")
     ap.add_argument("--bf16", action="store_true",
@@ -110,7 +100,7 @@ def main():
     wall = time.time() - t_start
 
     col = {"sddmm": 0, "spmm": 2, "fusedmm": 4}
-    os.makedirs(os.path.dirname(args.out), exist_ok=True)
+    os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
     with open(args.out, "w") as f:
         f.write("| M/K/N/sparsity | nnz | SDDMM | SPMM | FusedMM | paper SDDMM | paper SPMM | paper FusedMM |\n")
         f.write("|---|---|---|---|---|---|---|---|\n")
