@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle's timed sample (0 = auto)")
     ap.add_argument("--no-fusion-report", action="store_true")
+    ap.add_argument("--plan", action="store_true",
+                    help="also time the planned calls (pattern analysed once with csrk_plan_create, then "
+                         "*_csr_plan): adds a `planned` object to the line")
     ap.add_argument("--bf16", action="store_true",
                     help="also time the bfloat16-operand entry points on the same workload, beside the FP32 general "
                          "path they share their kernels with (adds a `bf16_operands` object to the line)")
@@ -255,6 +258,40 @@ def main():
         result["fusion"] = {"unfused_sddmm_then_spmm_ms": round(tu, 4), "fused_ms": round(tf, 4),
                             "fused_speedup": round(tu / tf, 3),
                             "max_abs_diff": float((Ou - Of).abs().max().item())}
+
+    if args.plan:
+        # a caller that reuses the pattern: analysis once, then calls that launch only the kernel that does the work
+        t0 = time.perf_counter()
+        plan = binding.csrk_plan_create(w.M, w.K, rp, ci)
+        torch.cuda.synchronize()
+        create_ms = (time.perf_counter() - t0) * 1e3
+        pcalls = []
+        if "spmm" in w.ops:
+            pcalls.append(("spmm", lambda: binding.spmm_csr_plan(plan, N, v, B, O)))
+        if "sddmm" in w.ops:
+            pcalls.append(("sddmm", lambda: binding.sddmm_csr_plan(plan, Ds, v, As, Bs, P)))
+        if "fusedmm" in w.ops:
+            pcalls.append(("fusedmm", lambda: binding.fusedmm_csr_plan(plan, Df, Nf, v, Af, Bf, Cf, Of)))
+        planned = {}
+        for name, fn in pcalls:
+            fn()
+            fn()
+            torch.cuda.synchronize()
+            binding.csrk_profile_enable(args.steps)
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            ms = [t for _, t in binding.csrk_profile_collect(args.steps + 4)]
+            binding.csrk_profile_enable(0)
+            planned[name] = {"ms_min": round(min(ms), 4), "ms_avg": round(sum(ms) / len(ms), 4),
+                             "gflops_avg": round(flops[name] / (sum(ms) / len(ms) * 1e-3) / 1e9, 1),
+                             "unplanned_ms_avg": result["ops"][name]["kernel_ms_avg"]}
+        nnz_p, sorted_p, even_p = binding.csrk_plan_info(plan)
+        binding.csrk_plan_destroy(plan)
+        result["planned"] = {"ops": planned, "plan_create_wall_ms": round(create_ms, 3),
+                             "columns_ascending": sorted_p, "rows_even": even_p,
+                             "note": "whole calls, same event pair as `ops`; the plan replaces the per-call row "
+                                     "analysis and the stand-by launches behind a tiled kernel"}
 
     if args.bf16:
         # the paper's stated future work: dense operands in bfloat16, FP32 arithmetic.  Same workload; the

@@ -117,6 +117,42 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
                              float *O, hipStream_t stream);
 
 /*
+ * Plans: the sparsity pattern analysed once, for callers that use one pattern many
+ * times (training loops; the paper's row analysis - nnzr, NT, nchunks of sections
+ * "SDDMM" and "SPMM" - depends on the pattern alone).  The calls above look at the
+ * pattern on the device on every call: a row-analysis launch (density, longest row)
+ * ahead of an LDS-tiled kernel, a column-order check inside it, and the general
+ * kernel plus combine step launched behind it in case the device turns the tiled
+ * kernel down.  A plan answers those questions once, on the host, so that a planned
+ * call launches only the kernel that does the work (plus the combine step where the
+ * method needs one).  Results are those of the unplanned calls.
+ *
+ * csrk_plan_create checks the structure like csrk_validate_csr (a pattern with
+ * problems is refused with CSRK_INVALID_ARG), finds out whether every row's columns
+ * are strictly ascending and whether the rows are even in length, and SYNCHRONISES
+ * `stream`.  rowptr and colidx (device pointers, not copied) must stay alive and
+ * UNCHANGED for as long as the plan is used; a planned call on a pattern changed
+ * since has undefined results.  *out (host pointer) receives the plan, owned by the
+ * caller until csrk_plan_destroy (NULL is accepted there).  A plan belongs to the
+ * device that was current when it was made; it holds 32 bytes of device memory.
+ * csrk_plan_info reports what was found (any of the three host pointers may be
+ * NULL).  The planned calls take the pattern and M, K from the plan; all other
+ * arguments are as in spmm_csr / sddmm_csr / fusedmm_csr.
+ */
+typedef struct csrk_plan_s csrk_plan;
+csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t *colidx,
+                             hipStream_t stream, csrk_plan **out);
+csrk_status csrk_plan_destroy(csrk_plan *plan);
+csrk_status csrk_plan_info(const csrk_plan *plan, long long *nnz, int *sorted, int *even);
+csrk_status spmm_csr_plan(const csrk_plan *plan, int N, const float *vals,
+                          const float *B, float *O, hipStream_t stream);
+csrk_status sddmm_csr_plan(const csrk_plan *plan, int D, const float *vals,
+                           const float *A, const float *B, float *P, hipStream_t stream);
+csrk_status fusedmm_csr_plan(const csrk_plan *plan, int D, int N, const float *vals,
+                             const float *A, const float *B, const float *C,
+                             float *O, hipStream_t stream);
+
+/*
  * Debug helper for untrusted inputs (the paper's storage rules, Fig. 1): checks
  * on the device that rowptr[0] == 0, rowptr is non-decreasing and every colidx
  * is in [0, K).  Synchronises `stream`.  *problems receives a bit mask:
@@ -131,7 +167,7 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
  * Benchmark aid (not part of the paper's method; it mirrors the paper's practice of
  * timing each kernel on its own, section "Experiments").  csrk_profile_enable(n)
  * with n > 0 creates n pairs of HIP events; from then on every spmm_csr / sddmm_csr /
- * fusedmm_csr call records one pair on the call's stream around ALL kernel launches of
+ * fusedmm_csr call (planned or not) records one pair on the call's stream around ALL kernel launches of
  * the call (the row analysis, the LDS-tiled kernel when one is tried, the general kernel
  * behind it - exactly one of the two does the work, the other returns at once - and the
  * combine pass of partial rows), until the pairs are used up.  csrk_profile_enable(0)

@@ -47,12 +47,20 @@ def load(build_if_missing: bool = True):
     lib.sddmm_csr_bf16.argtypes = [i, i, i, p, p, p, p, p, p, p]
     lib.fusedmm_csr_bf16.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p]
     lib.csrk_validate_csr.argtypes = [i, i, p, p, p, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.csrk_plan_create.argtypes = [i, i, p, p, p, ctypes.POINTER(ctypes.c_void_p)]
+    lib.csrk_plan_destroy.argtypes = [p]
+    lib.csrk_plan_info.argtypes = [p, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ctypes.c_int),
+                                   ctypes.POINTER(ctypes.c_int)]
+    lib.spmm_csr_plan.argtypes = [p, i, p, p, p, p]
+    lib.sddmm_csr_plan.argtypes = [p, i, p, p, p, p, p]
+    lib.fusedmm_csr_plan.argtypes = [p, i, i, p, p, p, p, p, p]
     lib.csrk_release_workspace.argtypes = []
     lib.csrk_profile_enable.argtypes = [i]
     lib.csrk_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i,
                                          ctypes.POINTER(ctypes.c_int)]
     for f in (lib.spmm_csr, lib.sddmm_csr, lib.fusedmm_csr, lib.spmm_csr_bf16, lib.sddmm_csr_bf16, lib.fusedmm_csr_bf16,
-              lib.csrk_validate_csr, lib.csrk_release_workspace,
+              lib.csrk_validate_csr, lib.csrk_release_workspace, lib.csrk_plan_create, lib.csrk_plan_destroy,
+              lib.csrk_plan_info, lib.spmm_csr_plan, lib.sddmm_csr_plan, lib.fusedmm_csr_plan,
               lib.csrk_profile_enable, lib.csrk_profile_collect):
         f.restype = ctypes.c_int
     lib.csrk_last_error.restype = ctypes.c_char_p
@@ -180,6 +188,91 @@ def fusedmm_csr_bf16(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B,
         _check(lib.fusedmm_csr_bf16(M, K, D, N, rp, ci, va, _dev_ptr(A, "A", torch.bfloat16, (M, D), dev),
                                     _dev_ptr(B, "B", torch.bfloat16, (K, D), dev),
                                     _dev_ptr(C, "C", torch.bfloat16, (K, N), dev),
+                                    _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+class Plan:
+    """A csrk_plan and the tensors it refers to (kept alive here; they must not be modified while the plan is
+    in use).  Made by `csrk_plan_create`; destroyed with `csrk_plan_destroy` or when collected."""
+
+    def __init__(self, handle, M, K, rowptr, colidx):
+        self.handle, self.M, self.K, self.rowptr, self.colidx = handle, M, K, rowptr, colidx
+
+    @property
+    def device(self):
+        return self.rowptr.device
+
+    @property
+    def nnz(self) -> int:
+        return self.colidx.numel()
+
+    def __del__(self):
+        try:
+            csrk_plan_destroy(self)
+        except Exception:
+            pass
+
+
+def csrk_plan_create(M: int, K: int, rowptr, colidx) -> Plan:
+    """Analyse the pattern once (synchronises the current stream); returns a Plan for the *_csr_plan calls."""
+    lib = load()
+    dev, _, rp, ci, _ = _csr_ptrs(M, rowptr, colidx, None, False)
+    handle = ctypes.c_void_p(None)
+    with torch.cuda.device(dev):
+        _check(lib.csrk_plan_create(M, K, rp, ci, _stream(dev), ctypes.byref(handle)))
+    return Plan(handle, M, K, rowptr, colidx)
+
+
+def csrk_plan_destroy(plan: Plan) -> None:
+    if plan.handle is not None and plan.handle.value:
+        handle, plan.handle = plan.handle, None
+        with torch.cuda.device(plan.device):
+            _check(load().csrk_plan_destroy(handle))
+
+
+def csrk_plan_info(plan: Plan):
+    """(stored entries, columns strictly ascending in every row, rows even in length) as found at creation."""
+    nnz, srt, even = ctypes.c_longlong(0), ctypes.c_int(0), ctypes.c_int(0)
+    _check(load().csrk_plan_info(plan.handle, ctypes.byref(nnz), ctypes.byref(srt), ctypes.byref(even)))
+    return nnz.value, bool(srt.value), bool(even.value)
+
+
+def spmm_csr_plan(plan: Plan, N: int, vals, B, O=None) -> torch.Tensor:
+    """spmm_csr on the plan's pattern."""
+    lib, dev, M, K = load(), plan.device, plan.M, plan.K
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.spmm_csr_plan(plan.handle, N, _dev_ptr(vals, "vals", torch.float32, (plan.nnz,), dev),
+                                 _dev_ptr(B, "B", torch.float32, (K, N), dev),
+                                 _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
+    return O
+
+
+def sddmm_csr_plan(plan: Plan, D: int, vals, A, B, P=None) -> torch.Tensor:
+    """sddmm_csr on the plan's pattern."""
+    lib, dev, M, K = load(), plan.device, plan.M, plan.K
+    if P is None:
+        P = torch.empty((plan.nnz,), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.sddmm_csr_plan(plan.handle, D, _dev_ptr(vals, "vals", torch.float32, (plan.nnz,), dev),
+                                  _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                                  _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                                  _dev_ptr(P, "P", torch.float32, (plan.nnz,), dev), _stream(dev)))
+    return P
+
+
+def fusedmm_csr_plan(plan: Plan, D: int, N: int, vals, A, B, C, O=None) -> torch.Tensor:
+    """fusedmm_csr on the plan's pattern."""
+    lib, dev, M, K = load(), plan.device, plan.M, plan.K
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib.fusedmm_csr_plan(plan.handle, D, N, _dev_ptr(vals, "vals", torch.float32, (plan.nnz,), dev),
+                                    _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                                    _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                                    _dev_ptr(C, "C", torch.float32, (K, N), dev),
                                     _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
     return O
 

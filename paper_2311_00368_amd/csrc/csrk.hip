@@ -16,6 +16,17 @@
 #include "kernels_ktile_narrow.hpp"
 #include "kernels_nnzsplit.hpp"
 
+// What csrk_plan_create found out about a pattern (see include/csrk.h).
+struct csrk_plan_s {
+    int dev;                  // device the plan was made on
+    int M, K;
+    long long nnz;
+    const int32_t *rowptr, *colidx;   // the caller's arrays (not copied)
+    bool sorted;              // columns non-decreasing inside every row
+    bool even;                // longest row <= 2 * mean + 64 (what the per-call row analysis asks)
+    int32_t *dflags;          // 8 device words laid out like the per-call flags: {0, 1, 0, even, ...}
+};
+
 namespace {
 
 using namespace csrk;
@@ -48,6 +59,7 @@ struct DeviceState {
     int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
     size_t head_floats = 0;
     int pending_ksplit = 0; // > 1: the tiled kernel of the call in progress left that many partial outputs in `head`
+    int32_t *plan_flags = nullptr;  // flag words of the plan the call in progress runs under (instead of the per-call ones)
 };
 
 DeviceState g_dev[kMaxDevices];
@@ -328,7 +340,7 @@ int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
 constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
 
-int32_t *tile_flags(DeviceState &d) { return d.head_row + d.workers + 8; }
+int32_t *tile_flags(DeviceState &d) { return d.plan_flags ? d.plan_flags : d.head_row + d.workers + 8; }
 
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
@@ -440,6 +452,45 @@ csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const 
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
+
+// Row analysis for a tiled attempt.  Without a plan: the analysis kernel, and the attempt always goes ahead (the
+// device has the last word).  With a plan the answer is known on the host: what the analysis kernel and the
+// kernels' own order check would find was found when the plan was made.
+csrk_status tiled_attempt(DeviceState &d, const csrk_plan_s *plan, hipStream_t st, int M, int K, const int32_t *rp,
+                          float min_density, bool *go) {
+    if (!plan) {
+        *go = true;
+        return launch_analysis(d, st, M, K, rp, min_density);
+    }
+    const bool dense = (double)plan->nnz >= (double)min_density * (double)M * (double)K;
+    *go = plan->sorted && (min_density < 0.f || (dense && plan->even));
+    return CSRK_OK;
+}
+
+// Planned calls on a small S (below 8 M cells, where unplanned calls take the whole-row kernels because a tiled
+// attempt costs three more launches than it gains): with a plan either way is ONE launch, and the narrow LDS-tiled
+// kernels then win from about 12 rows per CU on dense enough patterns.  Measured with planned calls on the small
+// shapes of the paper's grid, tiled against whole rows: at 3-4 k rows and K = 1024, SDDMM 1.09-1.45x at 20-30 %
+// (0.86-1.06 at 10 %), SPMM 1.12-1.55x at width 128 and 20-30 % (width 32: 1.04-1.12 at 30 % only), FusedMM
+// 1.08-1.49x at width 128 and 30 %, and at 20 % with 4 k rows (1.14; 0.86 with 3 k); with 1-2 k rows the tiled
+// kernels lose throughout (0.3-0.9).  `kind`: 0 SPMM, 1 SDDMM, 2 FusedMM; W: output width (dot length for SDDMM).
+bool plan_small_tiled(const DeviceState &d, const csrk_plan_s *plan, int M, int K, int W, int kind) {
+    if (!plan || !plan->sorted || !plan->even || env_int("CSRK_KTILE", 1) != 1 || env_int("CSRK_ROWS", 1) != 1)
+        return false;
+    if (W % 4 != 0 || W < 4 || W > 128) return false;
+    if ((long long)M * K >= (8ll << 20) || K > 2048 || M < 12 * d.cus) return false;
+    const double density = (double)plan->nnz / ((double)M * (double)K);
+    if (kind == 1) return density >= 0.15;
+    if (kind == 0) return W > 64 ? density >= 0.15 : density >= 0.25;
+    return W > 64 && (density >= 0.25 || (M >= 16 * d.cus && density >= 0.15));
+}
+
+// sets the flag words a planned call runs under for the duration of the call
+struct PlanScope {
+    DeviceState &d;
+    PlanScope(DeviceState &dev, const csrk_plan_s *plan) : d(dev) { d.plan_flags = plan ? plan->dflags : nullptr; }
+    ~PlanScope() { d.plan_flags = nullptr; }
+};
 
 // narrow outputs (N <= 128): G entries side by side per wavefront.  Thresholds below were read off a
 // sweep of the paper's 72 benchmark shapes on MI355X (tiled against general kernel, per shape).
@@ -749,8 +800,8 @@ const char *csrk_last_error(void) { return g_err; }
 
 const char *csrk_version(void) { return "csrk 0.1 gfx950"; }
 
-csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
-                     const float *B, float *O, hipStream_t stream) {
+static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const int32_t *rowptr,
+                            const int32_t *colidx, const float *vals, const float *B, float *O, hipStream_t stream) {
     if (csrk_status s = check_dims("spmm_csr", M, K, N, 0)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr: rowptr and O must not be NULL");
@@ -760,6 +811,7 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     if (csrk_status s = device_state(&d)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
+    PlanScope scope(*d, plan);
     const bool vec4 = (N % 4 == 0) && aligned16(B) && aligned16(O) && aligned16(d->head);
     const WidthCfg c = out_width_cfg(N, vec4);
     const int tile = c.vec * c.lg * c.t;
@@ -767,7 +819,8 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     rec.begin();
-    if (vec4 && rows_mode_ok(M, K, N, false)) {
+    const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, N, 0);
+    if (!small_tiled && vec4 && rows_mode_ok(M, K, N, false)) {
         const int wpr = rows_wpr(M, N);
         const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
 #define CSRK_SPMM_ROWS_CASE(V, L, T)                                                                              \
@@ -784,22 +837,39 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
         CSRK_HIP(hipGetLastError());
         return CSRK_OK;
     }
-    if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, false))) return s;
+    bool go = false;
+    if (small_tiled) {
         gate = tile_flags(*d);
-        csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
-        if (s) return s;
+        if (csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O)) return s;
+    } else if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, false), &go))
+            return s;
+        if (go) {
+            gate = tile_flags(*d);
+            if (csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O)) return s;
+        }
     } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
         // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
         // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, wide_min_density(M, K, N, false))) return s;
-        gate = tile_flags(*d);
-        csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
-                                 : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
-        if (s) return s;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, false), &go))
+            return s;
+        if (go) {
+            gate = tile_flags(*d);
+            csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
+                                     : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
+            if (s) return s;
+        }
     }
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
-    if (gate) {
+    if (plan) {
+        if (gate) {     // the plan vouches for the pattern: the tiled kernel has done the call
+            if (d->pending_ksplit > 1) launch_combine(*d, stream, M, N, O, gate, gate + 3, c.vec >= 4 && c.t == 1, vec4);
+            rec.end();
+            CSRK_HIP(hipGetLastError());
+            return CSRK_OK;
+        }
+        even = plan->even ? plan->dflags + 3 : nullptr;
+    } else if (gate) {
         even = tile_flags(*d) + 3;
     } else if (even_rows_worth_asking(*d, M, K, false)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
@@ -822,8 +892,9 @@ csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *
     return CSRK_OK;
 }
 
-csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
-                      const float *A, const float *B, float *P, hipStream_t stream) {
+static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const int32_t *rowptr,
+                             const int32_t *colidx, const float *vals, const float *A, const float *B, float *P,
+                             hipStream_t stream) {
     if (csrk_status s = check_dims("sddmm_csr", M, K, D, 0)) return s;
     if (M == 0 || K == 0) return CSRK_OK;
     if (!rowptr) return fail(CSRK_INVALID_ARG, "sddmm_csr: rowptr must not be NULL");
@@ -831,13 +902,15 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *d = nullptr;
     if (csrk_status s = device_state(&d)) return s;
+    PlanScope scope(*d, plan);
     const bool vec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const WidthCfg c = dot_width_cfg(D, vec4);
     const dim3 grid(d->workers / kWavesPerBlock);
     const int32_t *gate = nullptr;
     CallRecord rec(2, stream);
     rec.begin();
-    if (vec4 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
+    const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, D, 1);
+    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
         const int wpr = rows_wpr(M, D);
         const dim3 rgrid = rows_grid(M, wpr, 1);
 #define CSRK_SDDMM_ROWS_CASE(V, L, T)                                                                               \
@@ -853,16 +926,26 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
         CSRK_HIP(hipGetLastError());
         return CSRK_OK;
     }
-    if (vec4 && sddmm_tile_shape_ok(*d, M, K, D)) {
+    if (small_tiled || (vec4 && sddmm_tile_shape_ok(*d, M, K, D))) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, sddmm_min_density(M, K, D))) return s;
-        gate = tile_flags(*d);
-        csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
-                        : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
-                                  : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
-        if (s) return s;
+        bool go = small_tiled;
+        if (!go)
+            if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, sddmm_min_density(M, K, D), &go)) return s;
+        if (go) {
+            gate = tile_flags(*d);
+            csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
+                            : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
+                                      : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
+            if (s) return s;
+        }
     }
-    const int32_t *even = gate ? tile_flags(*d) + 3 : nullptr;   // device flag: rows even enough to be dealt out whole
+    if (plan && gate) {     // the plan vouches for the pattern: the tiled kernel has done the call
+        rec.end();
+        CSRK_HIP(hipGetLastError());
+        return CSRK_OK;
+    }
+    // device flag: rows even enough to be dealt out whole
+    const int32_t *even = plan ? (plan->even ? plan->dflags + 3 : nullptr) : gate ? tile_flags(*d) + 3 : nullptr;
 #define CSRK_SDDMM_CASE(V, L, T)                                                        \
     if (c.vec == V && c.lg == L && c.t == T)                                            \
         launch_sddmm<V, L, T>(grid, stream, M, D, rowptr, colidx, vals, A, B, P, gate, even);
@@ -878,8 +961,9 @@ csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t 
     return CSRK_OK;
 }
 
-csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
-                        const float *A, const float *B, const float *C, float *O, hipStream_t stream) {
+static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int N, const int32_t *rowptr,
+                               const int32_t *colidx, const float *vals, const float *A, const float *B,
+                               const float *C, float *O, hipStream_t stream) {
     if (csrk_status s = check_dims("fusedmm_csr", M, K, D, N)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr: rowptr and O must not be NULL");
@@ -890,6 +974,7 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     if (csrk_status s = device_state(&d)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
+    PlanScope scope(*d, plan);
     const bool dvec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const bool nvec4 = (N % 4 == 0) && aligned16(C) && aligned16(O) && aligned16(d->head);
     const WidthCfg dc = dot_width_cfg(D, dvec4);
@@ -900,7 +985,8 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     rec.begin();
-    if (nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N, true)) {
+    const bool small_tiled = nvec4 && dvec4 && D <= 128 && plan_small_tiled(*d, plan, M, K, N, 2);
+    if (!small_tiled && nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N, true)) {
         bool launched = false;
         if (dc.lg == 8) launched = launch_fused_rows_n<4, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
         if (dc.lg == 16) launched = launch_fused_rows_n<4, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
@@ -911,20 +997,38 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
             return CSRK_OK;
         }
     }
-    if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, narrow_min_density(M, K, N, true))) return s;
+    bool go = false;
+    if (small_tiled) {
         gate = tile_flags(*d);
-        csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
-        if (s) return s;
+        if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
+    } else if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, true), &go))
+            return s;
+        if (go) {
+            gate = tile_flags(*d);
+            if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
+        }
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
-        if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, wide_min_density(M, K, N, true))) return s;
-        gate = tile_flags(*d);
-        csrk_status s = N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
-                                 : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
-        if (s) return s;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, true), &go))
+            return s;
+        if (go) {
+            gate = tile_flags(*d);
+            csrk_status s =
+                N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
+                         : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
+            if (s) return s;
+        }
     }
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
-    if (gate) {
+    if (plan) {
+        if (gate) {     // the plan vouches for the pattern: the tiled kernel has done the call
+            if (d->pending_ksplit > 1) launch_combine(*d, stream, M, N, O, gate, gate + 3, false, nvec4);
+            rec.end();
+            CSRK_HIP(hipGetLastError());
+            return CSRK_OK;
+        }
+        even = plan->even ? plan->dflags + 3 : nullptr;
+    } else if (gate) {
         even = tile_flags(*d) + 3;
     } else if (even_rows_worth_asking(*d, M, K, true)) {
         if (csrk_status s = launch_analysis(*d, stream, M, K, rowptr, 2.f)) return s;
@@ -947,6 +1051,117 @@ csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
+}
+
+csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                     const float *B, float *O, hipStream_t stream) {
+    return spmm_run(nullptr, M, K, N, rowptr, colidx, vals, B, O, stream);
+}
+
+csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                      const float *A, const float *B, float *P, hipStream_t stream) {
+    return sddmm_run(nullptr, M, K, D, rowptr, colidx, vals, A, B, P, stream);
+}
+
+csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *A, const float *B, const float *C, float *O, hipStream_t stream) {
+    return fusedmm_run(nullptr, M, K, D, N, rowptr, colidx, vals, A, B, C, O, stream);
+}
+
+// --- plans: the pattern analysed once, calls without per-call analysis or stand-by launches ---------------
+
+static csrk_status plan_usable(const char *who, const csrk_plan_s *plan) {
+    if (!plan) return fail(CSRK_INVALID_ARG, "%s: plan must not be NULL", who);
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (dev != plan->dev) return fail(CSRK_INVALID_ARG, "%s: plan was made on device %d, current device is %d", who, plan->dev, dev);
+    return CSRK_OK;
+}
+
+csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t *colidx, hipStream_t stream,
+                             csrk_plan **out) {
+    if (!out) return fail(CSRK_INVALID_ARG, "csrk_plan_create: out must not be NULL");
+    *out = nullptr;
+    if (M < 0 || K < 0) return fail(CSRK_INVALID_ARG, "csrk_plan_create: negative dimension");
+    if (!rowptr) return fail(CSRK_INVALID_ARG, "csrk_plan_create: rowptr must not be NULL");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *d = nullptr;
+    if (csrk_status s = device_state(&d)) return s;
+    if (csrk_status s = ensure_scratch(*d, 1)) return s;
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    // structure first (the walk over colidx needs a sane rowptr), then column order, then row lengths
+    int32_t *vflags = d->head_row + d->workers;   // two spare words behind the worker table
+    int32_t host[2] = {0, 0};
+    int32_t nnz = 0;
+    CSRK_HIP(hipMemcpyAsync(vflags, host, sizeof(host), hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(validate_rowptr_kernel, dim3(M / 256 + 1), dim3(256), 0, stream, M, rowptr, vflags);
+    CSRK_HIP(hipGetLastError());
+    CSRK_HIP(hipMemcpyAsync(host, vflags, sizeof(host), hipMemcpyDeviceToHost, stream));
+    CSRK_HIP(hipMemcpyAsync(&nnz, rowptr + M, sizeof(nnz), hipMemcpyDeviceToHost, stream));
+    CSRK_HIP(hipStreamSynchronize(stream));
+    if (host[0] != 0) return fail(CSRK_INVALID_ARG, "csrk_plan_create: rowptr is not a valid row pointer array");
+    if (nnz > 0 && !colidx) return fail(CSRK_INVALID_ARG, "csrk_plan_create: colidx must not be NULL");
+    int32_t analysis[8] = {0, 0, 0, 1, 0, 0, 0, 0};
+    if (M > 0 && nnz > 0) {
+        hipLaunchKernelGGL(validate_colidx_kernel, dim3(1024), dim3(256), 0, stream, M, K, rowptr, colidx, vflags);
+        CSRK_HIP(hipGetLastError());
+        CSRK_HIP(hipMemcpyAsync(host, vflags, sizeof(host), hipMemcpyDeviceToHost, stream));
+        hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, stream, M, K, rowptr, 0.f, tile_flags(*d));
+        CSRK_HIP(hipGetLastError());
+        CSRK_HIP(hipMemcpyAsync(analysis, tile_flags(*d), 4 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        CSRK_HIP(hipStreamSynchronize(stream));
+        if (host[0] != 0) return fail(CSRK_INVALID_ARG, "csrk_plan_create: colidx holds columns outside [0, K)");
+    }
+    csrk_plan_s *plan = new csrk_plan_s{dev, M, K, (long long)nnz, rowptr, colidx, host[1] == 0, analysis[3] != 0, nullptr};
+    if (hipMalloc(&plan->dflags, 8 * sizeof(int32_t)) != hipSuccess) {
+        delete plan;
+        return fail(CSRK_HIP_ERROR, "csrk_plan_create: hipMalloc of the plan's flag words failed");
+    }
+    const int32_t words[8] = {0, 1, 0, plan->even ? 1 : 0, 0, 0, 0, 0};
+    if (hipMemcpyAsync(plan->dflags, words, sizeof(words), hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+        (void)hipFree(plan->dflags);
+        delete plan;
+        return fail(CSRK_HIP_ERROR, "csrk_plan_create: copying the plan's flag words failed");
+    }
+    *out = plan;
+    return CSRK_OK;
+}
+
+csrk_status csrk_plan_destroy(csrk_plan *plan) {
+    if (!plan) return CSRK_OK;
+    std::lock_guard<std::mutex> lock(g_mu);
+    const hipError_t e = hipFree(plan->dflags);
+    delete plan;
+    if (e != hipSuccess) return fail(CSRK_HIP_ERROR, "csrk_plan_destroy: hipFree: %s", hipGetErrorString(e));
+    return CSRK_OK;
+}
+
+csrk_status csrk_plan_info(const csrk_plan *plan, long long *nnz, int *sorted, int *even) {
+    if (!plan) return fail(CSRK_INVALID_ARG, "csrk_plan_info: plan must not be NULL");
+    if (nnz) *nnz = plan->nnz;
+    if (sorted) *sorted = plan->sorted ? 1 : 0;
+    if (even) *even = plan->even ? 1 : 0;
+    return CSRK_OK;
+}
+
+csrk_status spmm_csr_plan(const csrk_plan *plan, int N, const float *vals, const float *B, float *O,
+                          hipStream_t stream) {
+    if (csrk_status s = plan_usable("spmm_csr_plan", plan)) return s;
+    return spmm_run(plan, plan->M, plan->K, N, plan->rowptr, plan->colidx, vals, B, O, stream);
+}
+
+csrk_status sddmm_csr_plan(const csrk_plan *plan, int D, const float *vals, const float *A, const float *B, float *P,
+                           hipStream_t stream) {
+    if (csrk_status s = plan_usable("sddmm_csr_plan", plan)) return s;
+    return sddmm_run(plan, plan->M, plan->K, D, plan->rowptr, plan->colidx, vals, A, B, P, stream);
+}
+
+csrk_status fusedmm_csr_plan(const csrk_plan *plan, int D, int N, const float *vals, const float *A, const float *B,
+                             const float *C, float *O, hipStream_t stream) {
+    if (csrk_status s = plan_usable("fusedmm_csr_plan", plan)) return s;
+    return fusedmm_run(plan, plan->M, plan->K, D, N, plan->rowptr, plan->colidx, vals, A, B, C, O, stream);
 }
 
 csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,

@@ -1,6 +1,6 @@
 """The paper's 72-shape benchmark grid as synthetic inputs, on one MI355X.
 
-    python -m paper_2311_00368_amd.sweep [--out sweep72.md] [--iters 10] [--bf16]
+    python -m paper_2311_00368_amd.sweep [--out sweep72.md] [--iters 10] [--bf16 | --plan]
 
 The grid is the one on the x axes of the paper's benchmark figures: 12 (M, K) pairs x sparsity
 70 / 80 / 90 % x N in {32, 128}, with D = N as in the paper.  The paper's own matrices (the
@@ -44,7 +44,12 @@ def main():
     ap.add_argument("--limit", type=int, default=0, help="only the first LIMIT grid points (debug)")
     ap.add_argument("--bf16", action="store_true",
                     help="dense operands rounded to bfloat16 and the *_csr_bf16 entry points instead of the FP32 ones")
+    ap.add_argument("--plan", action="store_true",
+                    help="the pattern analysed once per shape (csrk_plan_create) and the *_csr_plan entry points: the "
+                         "caller that reuses a pattern, and the paper's own protocol, which times kernels only")
     args = ap.parse_args()
+    if args.plan and args.bf16:
+        sys.exit("--plan and --bf16 exclude each other (there are no planned bfloat16 calls)")
 
     import torch
 
@@ -82,6 +87,14 @@ def main():
                 "spmm": (lambda: binding.spmm_csr_bf16(M, K, n, rp, ci, v, C16, O), 2.0 * nnz * n),
                 "fusedmm": (lambda: binding.fusedmm_csr_bf16(M, K, D, n, rp, ci, v, A16, B16, C16, O), 2.0 * nnz * (D + n)),
             }
+        plan = None
+        if args.plan:
+            plan = binding.csrk_plan_create(M, K, rp, ci)
+            calls = {
+                "sddmm": (lambda: binding.sddmm_csr_plan(plan, D, v, A, B, P), 2.0 * nnz * D),
+                "spmm": (lambda: binding.spmm_csr_plan(plan, n, v, C, O), 2.0 * nnz * n),
+                "fusedmm": (lambda: binding.fusedmm_csr_plan(plan, D, n, v, A, B, C, O), 2.0 * nnz * (D + n)),
+            }
         res = {}
         for name, (fn, flops) in calls.items():
             fn()
@@ -96,6 +109,8 @@ def main():
             res[name] = flops / min(times) / 1e6          # Gflop/s
         rows.append(((mk, kk, sp, n), nnz, res))
         print(f"{mk}k/{kk}k/{n}/{sp}%  nnz={nnz}  " + "  ".join(f"{k} {x:8.0f}" for k, x in res.items()), flush=True)
+        if plan is not None:
+            binding.csrk_plan_destroy(plan)
         del rp, ci, v, A, B, C, O, P
     wall = time.time() - t_start
 
