@@ -303,10 +303,13 @@ bool launch_fused_rows_n(const WidthCfg &nc, hipStream_t st, int M, int D, int N
 // time): 4, 2 or 1.  More rows spread the per-tile work (staging, barriers) over more entries, but the grid
 // runs in rounds of `CUs` workgroups and a last round that is mostly empty costs as much as a full one:
 // pick the count with the least rounds x (rows + one half row's worth of per-tile work); ties go to more rows.
-int tile_rows_for(const DeviceState &d, int M, int max_rows = 4) {
+// `three`: the kernel also comes with 3 rows per wavefront (for FusedMM, whose score stage maps its four groups of
+// 16 lanes onto 1, 2 or 4 rows, it is the 4-row layout with one row left empty): 12 k rows are 256 workgroups of
+// 48 rows, one full round, where 64 rows leave a quarter of the CUs without work and 32 rows take two rounds.
+int tile_rows_for(const DeviceState &d, int M, int max_rows = 4, bool three = false) {
     int best = max_rows;
     long long best_cost = -1;
-    for (int rows = max_rows; rows >= 1; rows >>= 1) {
+    for (int rows = max_rows; rows >= 1; rows = (rows == 4 && three) ? 3 : (rows == 3 ? 2 : rows >> 1)) {
         const long long blocks = ((long long)M + kTileWaves * rows - 1) / (kTileWaves * rows);
         const long long rounds = (blocks + d.cus - 1) / d.cus;
         const long long cost = rounds * (2 * rows + 1);
@@ -436,9 +439,12 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     // rows per wavefront by the same rule as SPMM / FusedMM (the 128-wide kernel takes at most two: its score loop
     // is twice as long and four rows would spill)
     constexpr int kMaxRows = DMAX <= 64 ? 4 : 2;
-    switch (tile_rows_for(d, M, kMaxRows)) {
+    switch (tile_rows_for(d, M, kMaxRows, true)) {
         case 4:
             if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
+            [[fallthrough]];
+        case 3:
+            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 3>(d, st, M, K, D, rp, ci, v, A, B, P);
             [[fallthrough]];
         case 2: return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
         default: return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
@@ -545,8 +551,9 @@ csrk_status launch_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int N,
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_narrow_rows<G, 4>(d, st, M, K, N, rp, ci, v, C, O, ksplit);
     }
-    switch (tile_rows_for(d, M)) {
+    switch (tile_rows_for(d, M, 4, true)) {
         case 4: return launch_narrow_rows<G, 4>(d, st, M, K, N, rp, ci, v, C, O);
+        case 3: return launch_narrow_rows<G, 3>(d, st, M, K, N, rp, ci, v, C, O);
         case 2: return launch_narrow_rows<G, 2>(d, st, M, K, N, rp, ci, v, C, O);
         default: return launch_narrow_rows<G, 1>(d, st, M, K, N, rp, ci, v, C, O);
     }
@@ -590,14 +597,22 @@ csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, co
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O, ksplit);
     }
-    switch (tile_rows_for(d, M)) {
+    switch (tile_rows_for(d, M, 4, true)) {
         case 4: return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O);
+        case 3: return launch_ktile_rows<T, KT, 3>(d, st, M, K, N, rp, ci, v, B, O);
         case 2: return launch_ktile_rows<T, KT, 2>(d, st, M, K, N, rp, ci, v, B, O);
         default: return launch_ktile_rows<T, KT, 1>(d, st, M, K, N, rp, ci, v, B, O);
     }
 }
 
-template <int T, int KT, int ROWS, int SL>
+// FusedMM's 3-row version carries the score-stage work and registers of four rows, so it pays only where 48-row
+// workgroups save a whole round of the grid against 32-row ones and the accumulate stage is long: measured at
+// 24 k rows +10 % at width 128 and -3 % at width 32; at 12 k rows (one round either way) -1..-2 %.
+bool fused_three_rows(const DeviceState &d, int M, int N) {
+    return N > 64 && (long long)M > 64ll * d.cus;
+}
+
+template <int T, int KT, int ROWS, int SL, int LIVE = ROWS>
 csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                     const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                                     float *O, int ksplit = 1) {
@@ -608,7 +623,7 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 3 of 8 for two)
     constexpr int kPer = KT * T * 64 / kTileThreads;
     constexpr int kPrefetch = T == 2 ? 3 : kPer - 1;
-    auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch>;
+    auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch, LIVE>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -616,7 +631,7 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
         CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
         attr_set[dev] = true;
     }
-    const int rb = kTileWaves * ROWS;
+    const int rb = kTileWaves * LIVE;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
                        A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
@@ -633,8 +648,10 @@ csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
     }
-    switch (tile_rows_for(d, M)) {
+    // 3 rows per wavefront: the kernel laid out for 4, the fourth row of every wavefront empty (see fused_three_rows)
+    switch (tile_rows_for(d, M, 4, fused_three_rows(d, M, N))) {
         case 4: return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 3: return launch_fused_ktile_rows<T, KT, 4, SL, 3>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
         case 2: return launch_fused_ktile_rows<T, KT, 2, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
         default: return launch_fused_ktile_rows<T, KT, 1, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
     }
@@ -647,7 +664,7 @@ constexpr int fused_narrow_kt() {
     return (G == 2 && DMAX == 64) ? 160 : 128;
 }
 
-template <int G, int ROWS, int DMAX>
+template <int G, int ROWS, int DMAX, int LIVE = ROWS>
 csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                      const int32_t *ci, const float *v, const float *A, const float *B,
                                      const float *C, float *O, int ksplit = 1) {
@@ -659,7 +676,7 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
     // stage (which is twice as long for 128-float rows of B)
     constexpr int kPer = KT / (kTileThreads / (64 / G));
     constexpr int kPrefetch = DMAX == 128 ? (kPer - 1 < 2 ? kPer - 1 : 2) : (kPer <= 2 ? kPer : kPer - 1);
-    auto kern = fused_narrow_kernel<G, KT, ROWS, SL, DMAX, kPrefetch>;
+    auto kern = fused_narrow_kernel<G, KT, ROWS, SL, DMAX, kPrefetch, LIVE>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -667,7 +684,7 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
         CSRK_HIP(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes));
         attr_set[dev] = true;
     }
-    const int rb = kTileWaves * ROWS;
+    const int rb = kTileWaves * LIVE;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
                        A, B, C, O, tile_flags(d), d.head);
     CSRK_HIP(hipGetLastError());
@@ -685,8 +702,9 @@ csrk_status launch_fused_narrow_g(DeviceState &d, hipStream_t st, int M, int K, 
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
     }
-    switch (tile_rows_for(d, M)) {
+    switch (tile_rows_for(d, M, 4, fused_three_rows(d, M, N))) {
         case 4: return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 3: return launch_fused_narrow_rows<G, 4, DMAX, 3>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
         case 2: return launch_fused_narrow_rows<G, 2, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
         default: return launch_fused_narrow_rows<G, 1, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
     }

@@ -36,7 +36,9 @@ struct FusedTileLds {
 
 // PF: how many of a thread's kPer loads of the next C tile are issued one tile ahead; the rest and the
 // B tile are loaded at the start of their own tile (all of it ahead, B included, when PF == kPer).
-template <int T, int KT, int ROWS, int SL, int PF>
+// LIVE: rows a wavefront really owns.  LIVE = 3 with ROWS = 4 is the 48-rows-per-workgroup version (see
+// tile_rows_for on the host): laid out for four rows, the fourth one of every wavefront empty.
+template <int T, int KT, int ROWS, int SL, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
@@ -63,13 +65,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         return;
     }
 
-    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
+    const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide piece of the output
     const int my_r = (lane >> 4) / kGroupsPerRow;       // the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * LIVE>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
     int pos[ROWS], end[ROWS];
@@ -80,8 +83,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
-        pos[r] = row < M ? uniform(rowptr[row]) : 0;
-        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        const bool live = r < LIVE && row < M;
+        pos[r] = live ? uniform(rowptr[row]) : 0;
+        end[r] = live ? uniform(rowptr[row + 1]) : 0;
         if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             for (int v = 0; v < 4; ++v) acc[r][t][v] = 0.f;
     }
     float a[4] = {0.f, 0.f, 0.f, 0.f};      // piece i16 of this group's row of A, zero beyond D
-    if (row0 + my_r < M && i16 * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + i16 * 4, a);
+    if (my_r < LIVE && row0 + my_r < M && i16 * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + i16 * 4, a);
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
     const int n4 = N >> 2;                  // float4s per row of C
@@ -365,7 +369,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
-        if (row < M) {
+        if (r < LIVE && row < M) {
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
                 if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * N + n + tt * 256, acc[r][tt]);
@@ -389,7 +393,7 @@ struct FusedNarrowLds {
     static constexpr int kBytes = (kCFloats + kBFloats + kEntFloats) * 4;
 };
 
-template <int G, int KT, int ROWS, int SL, int DMAX, int PF>
+template <int G, int KT, int ROWS, int SL, int DMAX, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
@@ -425,14 +429,15 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
         return;
     }
 
-    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
+    const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;
     const int g = lane / LN;                // accumulate stage: which of the G side-by-side entries
     const int n = (lane % LN) * 4;          // accumulate stage: this lane's first column
     const int my_r = (lane >> 4) / kGroupsPerRow;       // score stage: the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * LIVE>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
     int pos[ROWS], end[ROWS];
@@ -443,8 +448,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
-        pos[r] = row < M ? uniform(rowptr[row]) : 0;
-        end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
+        const bool live = r < LIVE && row < M;
+        pos[r] = live ? uniform(rowptr[row]) : 0;
+        end[r] = live ? uniform(rowptr[row + 1]) : 0;
         if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
@@ -456,7 +462,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         a[h][0] = a[h][1] = a[h][2] = a[h][3] = 0.f;
-        if (row0 + my_r < M && (h * 16 + i16) * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + (h * 16 + i16) * 4, a[h]);
+        if (my_r < LIVE && row0 + my_r < M && (h * 16 + i16) * 4 < D)
+            load_vec<4>(A + (size_t)(row0 + my_r) * D + (h * 16 + i16) * 4, a[h]);
     }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
@@ -712,7 +719,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
         const int row = row0 + r;
-        if (row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
+        if (r < LIVE && row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
     }
 }
 

@@ -56,6 +56,36 @@ def test_fusedmm_ktile(csrk, M, K, D, N, p):
     run_fused(csrk, M, K, D, N, rp, ci, None, A, B, C)
 
 
+@pytest.mark.parametrize("N,D", [(32, 32), (64, 64), (128, 16), (256, 8), (512, 64), (64, 128), (128, 100)])
+def test_three_rows_per_wavefront(csrk, N, D):
+    # between 8193 and 12288 rows (and between 16385 and 24576) the SPMM and SDDMM tiled kernels run with 3 rows per
+    # wavefront, 48 per workgroup: here with a ragged last workgroup and a last partial tile
+    M, K = 9001, 300
+    rng = np.random.default_rng(N + D)
+    rp, ci = inputs.bernoulli_csr(N, M, K, 0.3)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
+@pytest.mark.parametrize("N,D", [(128, 32), (256, 64), (100, 128)])
+def test_three_rows_per_wavefront_fused(csrk, N, D):
+    # FusedMM takes its 3-row version (the 4-row layout, fourth row empty) only above 16384 rows and 64 columns
+    M, K = 16500, 150
+    rng = np.random.default_rng(N * 7 + D)
+    rp, ci = inputs.bernoulli_csr(D, M, K, 0.3)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_fused(csrk, M, K, D, N, rp, ci, None, A, B, C)
+
+
 @pytest.mark.parametrize("M,K,D", [(64, 64, 64), (100, 257, 128), (333, 417, 4), (1000, 1300, 32), (65, 3000, 100),
                                    (2048, 2048, 64), (130, 70, 60), (4096, 600, 128)])
 @pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
