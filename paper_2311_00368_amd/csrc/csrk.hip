@@ -246,14 +246,17 @@ void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, cons
 // outputs (few entries side by side) pay only with enough rows to keep every CU busy meanwhile; measured on the
 // small shapes of the paper's grid: SPMM +14..+89 % except N = 128 with 1-2 k rows (-20 %), FusedMM +5..+60 % at
 // N = 32 and -46..+12 % at N = 128.  CSRK_ROWS=2 forces it for every shape it can run (tests), =3 switches it off.
-bool rows_mode_ok(int M, int K, int N, bool fused) {
+bool rows_mode_ok(int M, int K, int N, bool fused, bool wider_for_narrow = true) {
     const int mode = env_int("CSRK_ROWS", 1);
     if (mode == 3) return false;
     if (mode == 2) return true;
-    if ((long long)M * K >= (8ll << 20) || K > 2048) return false;
-    (void)N;
     (void)fused;
-    return true;
+    if (K > 2048) return false;
+    // outputs of 32 columns or fewer: up to 16 M cells (measured at 6k/2k on the paper's grid against what ran
+    // before, the narrow tiled kernel at 20-30 % density and the failed attempt at 10 %: +7..+42 % in all three
+    // operations; at 16 M cells, 8k/2k, the tiled kernel is ahead again at 30 %)
+    // (not for planned SDDMM calls: with the attempt's extra launches gone the tiled kernel stays 12 % ahead there)
+    return (long long)M * K < ((N <= 32 && wider_for_narrow ? 16ll : 8ll) << 20);
 }
 
 // Larger matrices that get no tiled attempt (or whose attempt the device turns down) still gain from whole rows
@@ -928,7 +931,7 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const
     CallRecord rec(2, stream);
     rec.begin();
     const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, D, 1);
-    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
+    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, false, plan == nullptr)) {
         const int wpr = rows_wpr(M, D);
         const dim3 rgrid = rows_grid(M, wpr, 1);
 #define CSRK_SDDMM_ROWS_CASE(V, L, T)                                                                               \
