@@ -12,6 +12,7 @@ import helpers
 import oracle
 from paper_2311_00368_amd import inputs
 from test_gpu_parity import check, csrk, dev  # noqa: F401  (csrk is a fixture)
+from test_gpu_random import CASES_PER_SEED, random_case
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -184,3 +185,22 @@ def test_plan_creation_refuses_broken_patterns_and_empty_ones_work(csrk):
     assert torch.count_nonzero(O).item() == 0
     csrk.csrk_plan_destroy(plan)
     csrk.csrk_plan_destroy(plan)        # a second destroy of the wrapper is a no-op
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_planned_calls_on_random_shapes(csrk, monkeypatch, seed):
+    # the randomised run of test_gpu_random.py (shapes, widths, densities, row-length mixes, kernel-family
+    # settings) through plans
+    for c in range(CASES_PER_SEED):
+        what, env_vars, (M, K, D, N), (rp, ci, v), (A, B, C) = random_case(seed, c)
+        for name, value in env_vars.items():
+            monkeypatch.setenv(name, value)
+        pl = Planned(csrk, M, K, rp, ci)
+        try:
+            pl.spmm(N, v, C)
+            pl.fused(D, N, v, A, B, C)
+            if len(ci):
+                pl.sddmm(D, v, A, B)
+        except AssertionError as e:
+            raise AssertionError(f"{what}: {e}") from e
+        pl.close()

@@ -17,41 +17,47 @@ WIDTHS = [4, 8, 16, 32, 36, 64, 100, 128, 132, 256, 260, 384, 512]
 CASES_PER_SEED = 40
 
 
+def random_case(seed, c):
+    """Case number c of a seed: environment settings, sizes, pattern and operands."""
+    rng = np.random.default_rng(seed * 100000 + c)
+    mode = ["1", "2", "2", "3"][c % 4]
+    ksplit = ["1", "1", "2"][c % 3]
+    rows_mode = ["1", "2", "1", "3", "2"][c % 5]
+    M = int(rng.choice([1, 17, 64, 65, 200, 500, 1024, 1500, 2048, 3000, 4096, 5000]))
+    K = int(rng.choice([1, 63, 64, 65, 130, 500, 1024, 2048, 3000, 4096, 6000]))
+    N = int(rng.choice(WIDTHS))
+    D = int(rng.choice([4, 16, 32, 60, 64, 68, 128]))
+    p = float(rng.choice([0.0, 0.01, 0.05, 0.1, 0.2, 0.3, 0.6, 1.0]))
+    if M * K * p > 4e6:
+        p = 4e6 / (M * K)
+    kind = c % 5
+    what = f"seed {seed} case {c}: KTILE={mode} KSPLIT={ksplit} ROWS={rows_mode} M={M} K={K} N={N} D={D} p={p:.3f} kind={kind}"
+    if kind < 3:
+        rp, ci = inputs.bernoulli_csr(c + 7, M, K, p)
+    else:
+        # mixed row lengths: empty, single, short, about K*p, one chunk and a bit, full; sorted; repeats when kind == 4
+        rows = []
+        for _ in range(M):
+            length = int(rng.choice([0, 1, 3, int(K * p) + 1, min(K, 70), K]))
+            if M * K > 2e6:
+                length = min(length, int(K * p) + 5)
+            cols = rng.integers(0, K, size=length) if kind == 4 else rng.permutation(K)[:length]
+            rows.append(sorted(int(x) for x in cols))
+        rp, ci = helpers.csr_from_rows(rows, K)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    env = {"CSRK_KTILE": mode, "CSRK_KSPLIT": ksplit, "CSRK_ROWS": rows_mode}
+    return what, env, (M, K, D, N), (rp, ci, v), (A, B, C)
+
+
 @pytest.mark.parametrize("seed", [101, 102, 103, 104])
 def test_random_shapes_all_kernel_families(csrk, monkeypatch, seed):
     for c in range(CASES_PER_SEED):
-        rng = np.random.default_rng(seed * 100000 + c)
-        mode = ["1", "2", "2", "3"][c % 4]
-        ksplit = ["1", "1", "2"][c % 3]
-        rows_mode = ["1", "2", "1", "3", "2"][c % 5]
-        M = int(rng.choice([1, 17, 64, 65, 200, 500, 1024, 1500, 2048, 3000, 4096, 5000]))
-        K = int(rng.choice([1, 63, 64, 65, 130, 500, 1024, 2048, 3000, 4096, 6000]))
-        N = int(rng.choice(WIDTHS))
-        D = int(rng.choice([4, 16, 32, 60, 64, 68, 128]))
-        p = float(rng.choice([0.0, 0.01, 0.05, 0.1, 0.2, 0.3, 0.6, 1.0]))
-        if M * K * p > 4e6:
-            p = 4e6 / (M * K)
-        kind = c % 5
-        what = f"seed {seed} case {c}: KTILE={mode} KSPLIT={ksplit} ROWS={rows_mode} M={M} K={K} N={N} D={D} p={p:.3f} kind={kind}"
-        monkeypatch.setenv("CSRK_KTILE", mode)
-        monkeypatch.setenv("CSRK_KSPLIT", ksplit)
-        monkeypatch.setenv("CSRK_ROWS", rows_mode)
-        if kind < 3:
-            rp, ci = inputs.bernoulli_csr(c + 7, M, K, p)
-        else:
-            # mixed row lengths: empty, single, short, about K*p, one chunk and a bit, full; sorted; repeats when kind == 4
-            rows = []
-            for _ in range(M):
-                length = int(rng.choice([0, 1, 3, int(K * p) + 1, min(K, 70), K]))
-                if M * K > 2e6:
-                    length = min(length, int(K * p) + 5)
-                cols = rng.integers(0, K, size=length) if kind == 4 else rng.permutation(K)[:length]
-                rows.append(sorted(int(x) for x in cols))
-            rp, ci = helpers.csr_from_rows(rows, K)
-        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
-        A = rng.normal(size=(M, D)).astype(np.float32)
-        B = rng.normal(size=(K, D)).astype(np.float32)
-        C = rng.normal(size=(K, N)).astype(np.float32)
+        what, env, (M, K, D, N), (rp, ci, v), (A, B, C) = random_case(seed, c)
+        for name, value in env.items():
+            monkeypatch.setenv(name, value)
         try:
             run_spmm(csrk, M, K, N, rp, ci, v, C)
             run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
