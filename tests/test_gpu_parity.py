@@ -161,6 +161,21 @@ def test_one_dense_row_spans_many_workers(csrk):
     run_sddmm(csrk, 3, K, D, rp, ci, v, A, B)
 
 
+@pytest.mark.parametrize("N,D", [(32, 16), (128, 64)])
+def test_very_many_short_rows(csrk, N, D):
+    # more rows than the wave-wide row search covers in three rounds (64^3) and than the row analysis is asked for
+    M, K = 300_000, 64
+    rng = np.random.default_rng(N)
+    rp, ci = inputs.bernoulli_csr(1, M, K, 0.1)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
 def test_nan_in_unreferenced_row_does_not_leak(csrk):
     rng = np.random.default_rng(4)
     M, K, N = 64, 64, 64

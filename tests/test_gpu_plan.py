@@ -106,6 +106,16 @@ def test_planned_calls_with_tiled_kernels_forced(csrk, env, shape):
     pl.close()
 
 
+def test_planned_calls_with_very_many_short_rows(csrk):
+    M, K = 300_000, 64
+    rng = np.random.default_rng(5)
+    rp, ci = inputs.bernoulli_csr(1, M, K, 0.1)
+    pl = Planned(csrk, M, K, rp, ci)
+    pl.all_ops(rng, 16, 32)
+    pl.all_ops(rng, 64, 128)
+    pl.close()
+
+
 def test_one_plan_serves_many_widths_and_repeated_calls(csrk):
     M, K = 4096, 4096
     rng = np.random.default_rng(11)
