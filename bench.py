@@ -17,6 +17,8 @@ workload is the 16384 x 16384, 20 %-dense configuration the benchmark spec's target is
                a 1 GiB buffer) and the wall time of the very first call (workspace allocation included)
   roofline     the dominant kernel against MI355X's FP32 vector peak (157.3 TFLOP/s)
   cpu_baseline the FP64 CPU oracle timed on a sample of the rows of the same workload
+  planned      the same three calls through a plan (pattern analysed once, outside the timing), timed after
+               the main region and not part of `value`
 
 Only one GPU is used; --gpus N with N > 1 is refused.
 """
@@ -63,9 +65,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows in the oracle's timed sample (0 = auto)")
     ap.add_argument("--no-fusion-report", action="store_true")
-    ap.add_argument("--plan", action="store_true",
-                    help="also time the planned calls (pattern analysed once with csrk_plan_create, then "
-                         "*_csr_plan): adds a `planned` object to the line")
+    ap.add_argument("--no-plan", dest="plan", action="store_false",
+                    help="skip the `planned` object (the same calls with the pattern analysed once by "
+                         "csrk_plan_create, then *_csr_plan; timed after the main region, not part of `value`)")
+    ap.add_argument("--plan", dest="plan", action="store_true", help="(default) include the `planned` object")
+    ap.set_defaults(plan=True)
     ap.add_argument("--bf16", action="store_true",
                     help="also time the bfloat16-operand entry points on the same workload, beside the FP32 general "
                          "path they share their kernels with (adds a `bf16_operands` object to the line)")
