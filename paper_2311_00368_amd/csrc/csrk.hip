@@ -661,10 +661,14 @@ csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int
 }
 
 // --- narrow FusedMM (N <= 128, D <= 128): fused_narrow_kernel -------------------------------------------
-// tile height: 128 rows (C and B tiles plus 64-entry slots fit 160 KB at any width), 160 where both are narrow
+// tile height: as many rows as the C and B tiles plus the 64-entry slots (32 KB) leave room for in 160 KB, in whole
+// rounds of the staging loop: 160 / 192 / 256 rows for outputs up to 128 / 64 / 32 columns with dot lengths up to 64
+// (measured against 128 rows: 32k/8k and 8k/8k at width 64 +10..+13 %, 24k/8k at width 32 +23 %, the rest level);
+// 128 rows with 128-float rows of B
 template <int G, int DMAX>
 constexpr int fused_narrow_kt() {
-    return (G == 2 && DMAX == 64) ? 160 : 128;
+    if (DMAX == 64) return G == 2 ? 160 : (G == 4 ? 192 : 256);
+    return 128;
 }
 
 template <int G, int ROWS, int DMAX, int LIVE = ROWS>
