@@ -246,11 +246,10 @@ void launch_combine(DeviceState &d, hipStream_t st, int M, int N, float *O, cons
 // outputs (few entries side by side) pay only with enough rows to keep every CU busy meanwhile; measured on the
 // small shapes of the paper's grid: SPMM +14..+89 % except N = 128 with 1-2 k rows (-20 %), FusedMM +5..+60 % at
 // N = 32 and -46..+12 % at N = 128.  CSRK_ROWS=2 forces it for every shape it can run (tests), =3 switches it off.
-bool rows_mode_ok(int M, int K, int N, bool fused, bool wider_for_narrow = true) {
+bool rows_mode_ok(int M, int K, int N, bool wider_for_narrow = true) {
     const int mode = env_int("CSRK_ROWS", 1);
     if (mode == 3) return false;
     if (mode == 2) return true;
-    (void)fused;
     if (K > 2048) return false;
     // outputs of 32 columns or fewer: up to 16 M cells (measured at 6k/2k on the paper's grid against what ran
     // before, the narrow tiled kernel at 20-30 % density and the failed attempt at 10 %: +7..+42 % in all three
@@ -845,7 +844,7 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
     CallRecord rec(1, stream);
     rec.begin();
     const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, N, 0);
-    if (!small_tiled && vec4 && rows_mode_ok(M, K, N, false)) {
+    if (!small_tiled && vec4 && rows_mode_ok(M, K, N)) {
         const int wpr = rows_wpr(M, N);
         const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
 #define CSRK_SPMM_ROWS_CASE(V, L, T)                                                                              \
@@ -935,7 +934,7 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const
     CallRecord rec(2, stream);
     rec.begin();
     const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, D, 1);
-    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, false, plan == nullptr)) {
+    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, plan == nullptr)) {
         const int wpr = rows_wpr(M, D);
         const dim3 rgrid = rows_grid(M, wpr, 1);
 #define CSRK_SDDMM_ROWS_CASE(V, L, T)                                                                               \
@@ -1011,7 +1010,7 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
     CallRecord rec(3, stream);
     rec.begin();
     const bool small_tiled = nvec4 && dvec4 && D <= 128 && plan_small_tiled(*d, plan, M, K, N, 2);
-    if (!small_tiled && nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N, true)) {
+    if (!small_tiled && nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N)) {
         bool launched = false;
         if (dc.lg == 8) launched = launch_fused_rows_n<4, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
         if (dc.lg == 16) launched = launch_fused_rows_n<4, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
@@ -1206,7 +1205,7 @@ csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int3
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     CallRecord rec(11, stream);
     rec.begin();
-    if (vec8 && rows_mode_ok(M, K, N, false)) {     // small S: a row per 1, 2 or 4 wavefronts, one launch
+    if (vec8 && rows_mode_ok(M, K, N)) {     // small S: a row per 1, 2 or 4 wavefronts, one launch
         const int wpr = rows_wpr(M, N);
         const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
 #define CSRK_SPMM_ROWS_BF16_CASE(V, L, T)                                                                          \
@@ -1260,7 +1259,7 @@ csrk_status sddmm_csr_bf16(int M, int K, int D, const int32_t *rowptr, const int
     const dim3 grid(d->workers / kWavesPerBlock);
     CallRecord rec(12, stream);
     rec.begin();
-    if (vec8 && c.t == 1 && rows_mode_ok(M, K, D, false)) {
+    if (vec8 && c.t == 1 && rows_mode_ok(M, K, D)) {
         const int wpr = rows_wpr(M, D);
         const dim3 rgrid = rows_grid(M, wpr, 1);
         if (c.lg == 8)
@@ -1308,7 +1307,7 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N, const int32_t *rowptr, 
     const dim3 grid(d->workers / kWavesPerBlock, (N + tile - 1) / tile);
     CallRecord rec(13, stream);
     rec.begin();
-    if (nvec8 && dvec8 && dc.t == 1 && N <= 512 && rows_mode_ok(M, K, N, true)) {
+    if (nvec8 && dvec8 && dc.t == 1 && N <= 512 && rows_mode_ok(M, K, N)) {
         const bool launched =
             dc.lg == 8 ? launch_fused_rows_bf16_n<8, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O)
                        : launch_fused_rows_bf16_n<8, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
