@@ -910,7 +910,11 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
     CSRK_SPMM_CASE(1, 64, 1)
 #undef CSRK_SPMM_CASE
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, even, c.vec >= 4 && c.t == 1, vec4);
+    // a planned call knows on the host what the combine step would find on the device: whole rows were dealt out
+    // (same condition as in the kernels), there are no partial rows to add, and the launch is left out
+    const bool any_m = c.vec >= 4 && c.t == 1;
+    if (!(plan && even && (any_m || 2ll * M > d->workers)))
+        launch_combine(*d, stream, M, N, O, gate, even, any_m, vec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
@@ -1071,7 +1075,8 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
 #undef CSRK_DOT_CASE
     if (!done) return fail(CSRK_UNSUPPORTED, "fusedmm_csr: no kernel for D=%d N=%d", D, N);
     CSRK_HIP(hipGetLastError());
-    launch_combine(*d, stream, M, N, O, gate, even, false, nvec4);
+    if (!(plan && even && 2ll * M > d->workers))     // planned call, whole rows: no partial rows to add
+        launch_combine(*d, stream, M, N, O, gate, even, false, nvec4);
     rec.end();
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
