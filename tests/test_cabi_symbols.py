@@ -43,3 +43,24 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".c")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "csr_oracle" not in src, f
+
+
+def test_argument_errors_are_reported_before_any_device_work():
+    # calls that must fail on their arguments alone: they return a status and a message without touching a GPU
+    from paper_2311_00368_amd import binding
+    lib = binding.load()
+    null = ctypes.c_void_p(None)
+    invalid = 1     # CSRK_INVALID_ARG
+    assert lib.spmm_csr(-1, 4, 4, null, null, null, null, null, null) == invalid
+    assert "spmm_csr" in binding.csrk_last_error()
+    assert lib.sddmm_csr(4, -2, 4, null, null, null, null, null, null, null) == invalid
+    assert lib.fusedmm_csr(4, 4, 4, -1, null, null, null, null, null, null, null, null) == invalid
+    assert lib.spmm_csr(4, 4, 4, null, null, null, null, null, null) == invalid          # rowptr and O are NULL
+    assert lib.spmm_csr(0, 4, 4, null, null, null, null, null, null) == 0                # no rows: nothing to do
+    assert lib.csrk_plan_create(4, 4, null, null, null, None) == invalid                 # nowhere to put the plan
+    assert lib.csrk_plan_destroy(null) == 0
+    assert lib.csrk_plan_info(null, None, None, None) == invalid
+    assert lib.spmm_csr_plan(null, 4, null, null, null, null) == invalid
+    assert lib.sddmm_csr_plan(null, 4, null, null, null, null, null) == invalid
+    assert lib.fusedmm_csr_plan(null, 4, 4, null, null, null, null, null, null) == invalid
+    assert "plan" in binding.csrk_last_error()
