@@ -60,6 +60,9 @@ struct DeviceState {
     size_t head_floats = 0;
     int pending_ksplit = 0; // > 1: the tiled kernel of the call in progress left that many partial outputs in `head`
     int32_t *plan_flags = nullptr;  // flag words of the plan the call in progress runs under (instead of the per-call ones)
+    int flag_set = 0;       // which of the two sets of per-call flag words the next tiled attempt uses (see tile_go)
+    float inline_density = __builtin_nanf("");   // not NaN: the tiled kernel of the call in progress analyses the rows itself
+    bool attempted = false; // the call in progress has made an unplanned tiled attempt (its set of flag words is used up)
 };
 
 DeviceState g_dev[kMaxDevices];
@@ -126,10 +129,14 @@ csrk_status ensure_scratch(DeviceState &d, int width, size_t min_floats = 0) {
     size_t need = (size_t)d.workers * (size_t)width;
     if (min_floats > need) need = min_floats;
     if (!d.head_row) {
-        if (hipMalloc((void **)&d.head_row, sizeof(int32_t) * ((size_t)d.workers + 16)) != hipSuccess) {
+        const size_t bytes = sizeof(int32_t) * ((size_t)d.workers + 8 + 2 * 8);   // worker table, spare words, two sets of flags
+        if (hipMalloc((void **)&d.head_row, bytes) != hipSuccess) {
             d.head_row = nullptr;
-            return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", sizeof(int32_t) * ((size_t)d.workers + 16));
+            return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", bytes);
         }
+        // both sets start with a clear ordering flag; from then on each tiled attempt clears the other set's
+        CSRK_HIP(hipMemset(d.head_row, 0, bytes));
+        d.flag_set = 0;
     }
     if (need > d.head_floats) {
         if (d.head) {
@@ -345,7 +352,9 @@ int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
 constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
 
-int32_t *tile_flags(DeviceState &d) { return d.plan_flags ? d.plan_flags : d.head_row + d.workers + 8; }
+int32_t *tile_flags(DeviceState &d) { return d.plan_flags ? d.plan_flags : d.head_row + d.workers + 8 + 8 * d.flag_set; }
+// the set of flag words the next unplanned tiled attempt will use (nothing to look after under a plan)
+int32_t *other_flags(DeviceState &d) { return d.plan_flags ? nullptr : d.head_row + d.workers + 8 + 8 * (1 - d.flag_set); }
 
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
@@ -428,7 +437,7 @@ csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int
     }
     const int rb = kTileWaves * ROWS;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, rp, ci, v, A, B, P,
-                       tile_flags(d));
+                       tile_flags(d), d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
@@ -456,10 +465,14 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
 csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, float min_density) {
     int32_t *flags = tile_flags(d);
     // column order is verified inside the tiled kernels themselves
-    hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, st, M, K, rp, min_density, flags);
+    hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, st, M, K, rp, min_density, flags, other_flags(d));
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
+
+// Up to this many rows the tiled kernels do the row analysis themselves: every workgroup reads rowptr (32 KB at
+// the limit, from L2) for a microsecond or two, against 3-6 us and a kernel boundary for the analysis launch.
+constexpr int kInlineAnalysisMaxRows = 8192;
 
 // Row analysis for a tiled attempt.  Without a plan: the analysis kernel, and the attempt always goes ahead (the
 // device has the last word).  With a plan the answer is known on the host: what the analysis kernel and the
@@ -468,6 +481,11 @@ csrk_status tiled_attempt(DeviceState &d, const csrk_plan_s *plan, hipStream_t s
                           float min_density, bool *go) {
     if (!plan) {
         *go = true;
+        d.attempted = true;
+        if (M <= kInlineAnalysisMaxRows) {      // the tiled kernel's workgroups read rowptr themselves (tile_go)
+            d.inline_density = min_density;
+            return CSRK_OK;
+        }
         return launch_analysis(d, st, M, K, rp, min_density);
     }
     const bool dense = (double)plan->nnz >= (double)min_density * (double)M * (double)K;
@@ -493,11 +511,21 @@ bool plan_small_tiled(const DeviceState &d, const csrk_plan_s *plan, int M, int 
     return W > 64 && (density >= 0.25 || (M >= 16 * d.cus && density >= 0.15));
 }
 
-// sets the flag words a planned call runs under for the duration of the call
+// per-call state of the flag words: a plan's own words for the duration of a planned call; after an unplanned tiled
+// attempt the two per-call sets change places
 struct PlanScope {
     DeviceState &d;
-    PlanScope(DeviceState &dev, const csrk_plan_s *plan) : d(dev) { d.plan_flags = plan ? plan->dflags : nullptr; }
-    ~PlanScope() { d.plan_flags = nullptr; }
+    PlanScope(DeviceState &dev, const csrk_plan_s *plan) : d(dev) {
+        d.plan_flags = plan ? plan->dflags : nullptr;
+        d.inline_density = __builtin_nanf("");
+        d.attempted = false;
+    }
+    ~PlanScope() {
+        d.plan_flags = nullptr;
+        d.inline_density = __builtin_nanf("");
+        if (d.attempted) d.flag_set ^= 1;      // the next attempt takes the set this one has cleared
+        d.attempted = false;
+    }
 };
 
 // narrow outputs (N <= 128): G entries side by side per wavefront.  Thresholds below were read off a
@@ -537,7 +565,7 @@ csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int
     }
     const int rb = kTileWaves * ROWS;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, C,
-                       O, tile_flags(d), d.head);
+                       O, tile_flags(d), d.head, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -585,7 +613,7 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     }
     const int rb = kTileWaves * ROWS;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B,
-                       O, tile_flags(d), d.head);
+                       O, tile_flags(d), d.head, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -635,7 +663,7 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     }
     const int rb = kTileWaves * LIVE;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
-                       A, B, C, O, tile_flags(d), d.head);
+                       A, B, C, O, tile_flags(d), d.head, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -692,7 +720,7 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
     }
     const int rb = kTileWaves * LIVE;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
-                       A, B, C, O, tile_flags(d), d.head);
+                       A, B, C, O, tile_flags(d), d.head, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -1136,7 +1164,8 @@ csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t 
         hipLaunchKernelGGL(validate_colidx_kernel, dim3(1024), dim3(256), 0, stream, M, K, rowptr, colidx, vflags);
         CSRK_HIP(hipGetLastError());
         CSRK_HIP(hipMemcpyAsync(host, vflags, sizeof(host), hipMemcpyDeviceToHost, stream));
-        hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, stream, M, K, rowptr, 0.f, tile_flags(*d));
+        hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(1024), 0, stream, M, K, rowptr, 0.f, tile_flags(*d),
+                           (int32_t *)nullptr);
         CSRK_HIP(hipGetLastError());
         CSRK_HIP(hipMemcpyAsync(analysis, tile_flags(*d), 4 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
         CSRK_HIP(hipStreamSynchronize(stream));

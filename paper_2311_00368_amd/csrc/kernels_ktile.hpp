@@ -32,7 +32,7 @@
 //    tile barrier: no vector-memory wait ever sits inside the arithmetic.
 //
 // Requirements: columns of every row non-decreasing; S dense enough for the LDS copy to
-// pay.  Density and row-length spread are read off rowptr by reset_flags_kernel beforehand.  Ordering is
+// pay.  Density and row-length spread are read off rowptr first (tile_go below).  Ordering is
 // verified by the tiled kernels themselves at no extra memory traffic: every look-ahead
 // chunk they load is compared lane against neighbouring lane (one DPP shift and a
 // compare), and chunks overlap, so every adjacent pair of a row passes through the check.
@@ -57,15 +57,16 @@ constexpr int kTileWaves = kTileThreads / kWave;
 // flags[0] != 0: some row has descending columns.  flags[1] != 0: dense enough.
 __device__ __forceinline__ bool ktile_ok(const int32_t *flags) { return flags[0] == 0 && flags[1] != 0; }
 
-// The per-call row analysis that has to precede the tiled kernels (one workgroup): clears the
-// ordering flag and decides from rowptr alone whether the tiled kernels suit S: nnz = rowptr[M]
-// must reach `min_density` of M*K, and no row may be much longer than the mean row (the tiled
-// kernels give every wavefront a fixed set of rows and synchronise per tile, so skewed row
-// lengths are left to the equal-nonzero split of the general kernels).  A negative `min_density`
-// switches both criteria off (used by tests to reach the tiled kernels with any pattern).
-__global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const int32_t *__restrict__ rowptr,
-                                                          float min_density, int32_t *flags) {
-    __shared__ int wave_max[16];
+// The per-call row analysis of the tiled kernels: decides from rowptr alone whether the tiled kernels suit S.
+// nnz = rowptr[M] must reach `min_density` of M*K, and no row may be much longer than the mean row (the tiled
+// kernels give every wavefront a fixed set of rows and synchronise per tile, so skewed row lengths are left to
+// the equal-nonzero split of the general kernels).  A negative `min_density` switches both criteria off (used
+// by tests to reach the tiled kernels with any pattern).
+//
+// Run by a whole workgroup of up to 1024 threads; `red` is room for 16 ints in LDS.  Returns, in every thread,
+// bit 0: the tiled kernel may run, bit 1: rows even (for the general kernels: rows can be dealt out whole).
+__device__ __forceinline__ int row_analysis(int M, int K, const int32_t *__restrict__ rowptr, float min_density,
+                                            int *red) {
     int longest = 0;
     constexpr int U = 8;                     // row lengths requested together per thread
     for (long long r0 = threadIdx.x; r0 < M; r0 += blockDim.x * U) {
@@ -86,18 +87,51 @@ __global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const i
         const int o = __shfl_xor(longest, off);
         longest = o > longest ? o : longest;
     }
-    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = longest;
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = longest;
     __syncthreads();
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) longest = red[w] > longest ? red[w] : longest;
+    const double nnz = (double)rowptr[M];
+    const double mean = M > 0 ? nnz / (double)M : 0.0;
+    const bool dense = nnz >= (double)min_density * (double)M * (double)K;
+    const bool even = (double)longest <= 2.0 * mean + 64.0;
+    __syncthreads();                         // `red` may be reused by the caller
+    return (((dense && even) || min_density < 0.f) ? 1 : 0) | (even ? 2 : 0);
+}
+
+// The analysis as a launch of its own (one workgroup), ahead of tiled kernels on matrices with so many rows that
+// every workgroup of the tiled kernel reading all of rowptr itself would cost more than this launch, and for the
+// general kernels where only they run.  Leaves flags[1] (tiled kernel may run) and flags[3] (rows even), clears
+// the ordering flag of this set of flag words and of the other set (see tile_go).
+__global__ __launch_bounds__(1024) void reset_flags_kernel(int M, int K, const int32_t *__restrict__ rowptr,
+                                                          float min_density, int32_t *flags, int32_t *other) {
+    __shared__ int red[16];
+    const int verdict = row_analysis(M, K, rowptr, min_density, red);
     if (threadIdx.x == 0) {
-        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) longest = wave_max[w] > longest ? wave_max[w] : longest;
-        const double nnz = (double)rowptr[M];
-        const double mean = M > 0 ? nnz / (double)M : 0.0;
-        const bool dense = nnz >= (double)min_density * (double)M * (double)K;
-        const bool even = (double)longest <= 2.0 * mean + 64.0;
         flags[0] = 0;
-        flags[1] = ((dense && even) || min_density < 0.f) ? 1 : 0;
-        flags[3] = even ? 1 : 0;            // for the general kernels: rows can be dealt out whole (no balancing needed)
+        flags[1] = verdict & 1;
+        flags[3] = (verdict >> 1) & 1;
+        if (other) other[0] = 0;
     }
+}
+
+// First thing in every tiled kernel: may it run?  Two ways of knowing.  `inline_density` is a number (not NaN): the
+// kernel does the row analysis itself - every workgroup reads rowptr and reaches the same verdict, workgroup 0
+// leaves it in flags[1] and flags[3] for the kernels launched behind this one - which saves the analysis launch
+// (3-6 us and a kernel boundary) where M is small enough for that to be cheap.  Otherwise the verdict is already in
+// `flags` (reset_flags_kernel ran, or a plan made them).
+// The ordering flag flags[0] cannot be cleared here (a workgroup that starts late would wipe out another's report),
+// so the library keeps two sets of flag words and alternates between them: whoever analyses for a call on one set
+// clears flags[0] of the OTHER set, which the next call will use.
+__device__ __forceinline__ bool tile_go(int M, int K, const int32_t *__restrict__ rowptr, float inline_density,
+                                        int32_t *flags, int32_t *other, int *red) {
+    if (inline_density != inline_density) return ktile_ok(flags);
+    const int verdict = row_analysis(M, K, rowptr, inline_density, red);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        flags[1] = verdict & 1;
+        flags[3] = (verdict >> 1) & 1;
+        if (other) other[0] = 0;
+    }
+    return (verdict & 1) != 0;
 }
 
 // Lanes whose column is smaller than the column in the lane before them (lane 0 compares with itself).
@@ -213,10 +247,10 @@ template <int T, int KT, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
-    float *partial) {
+    float *partial, float inline_density, int32_t *other_flags) {
     using L = KTileLds<T, KT>;
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    if (!ktile_ok(flags)) return;
+    if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     constexpr int kRowBytes = L::kRowFloats * 4;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
@@ -450,7 +484,8 @@ struct SddmmTileLds {
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     int M, int K, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
-    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags) {
+    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags, float inline_density,
+    int32_t *other_flags) {
     using L = SddmmTileLds<DMAX, ROWS>;
     constexpr int KT = L::kKT;
     constexpr int C = L::kPieces;
@@ -460,7 +495,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     constexpr int NG = S * H / GL;
     static_assert(S * H % GL == 0, "whole groups of reads");
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    if (!ktile_ok(flags)) return;
+    if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;

@@ -42,12 +42,13 @@ template <int T, int KT, int ROWS, int SL, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
+    int32_t *other_flags) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(SL == 32 || SL == 64, "slot sizes");
     static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    if (!ktile_ok(flags)) return;
+    if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     constexpr int kRowBytes = L::kRowFloats * 4;
     constexpr int kGroupsPerRow = 4 / ROWS;
     constexpr int kPass = 16 * kGroupsPerRow;      // entries of a row scored per pass
@@ -397,13 +398,14 @@ template <int G, int KT, int ROWS, int SL, int DMAX, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
-    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial) {
+    const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
+    int32_t *other_flags) {
     using L = FusedNarrowLds<G, KT, ROWS, SL, DMAX>;
     static_assert(SL == 32 || SL == 64, "slot sizes");
     static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
     static_assert(DMAX == 64 || DMAX == 128, "dot lengths the score stage is laid out for");
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    if (!ktile_ok(flags)) return;
+    if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     constexpr int LN = kWave / G;           // lanes per entry in the accumulate stage
     constexpr int H = DMAX / 64;            // 16-piece halves of a row of B
     constexpr int kRowBytes = L::kRowFloats * 4;

@@ -35,12 +35,12 @@ template <int G, int KT, int ROWS, int PF>
 __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
-    float *partial) {
+    float *partial, float inline_density, int32_t *other_flags) {
     using L = NarrowLds<G, KT>;
     constexpr int LN = kWave / G;           // lanes per entry
     constexpr int kRowBytes = L::kRowFloats * 4;
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    if (!ktile_ok(flags)) return;
+    if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;

@@ -277,3 +277,21 @@ def test_ksplit_never_trusts_a_binary_search_in_unsorted_rows(csrk, kind):
     run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
     run_spmm(csrk, M, K, 128, rp, ci, v, C[:, :128].copy())
     run_fused(csrk, M, K, D, 128, rp, ci, v, A, B, C[:, :128].copy())
+
+
+def test_unsorted_and_sorted_patterns_in_turn(csrk):
+    # The ordering flag lives in two sets of flag words that take turns from one tiled attempt to the next; a report
+    # of descending columns in one call must neither be lost nor leak into the calls after it, whatever the operation.
+    rng = np.random.default_rng(77)
+    M, K, N, D = 700, 900, 128, 32
+    rp, ci = inputs.bernoulli_csr(3, M, K, 0.2)
+    ci_bad = ci.copy()
+    ci_bad[rp[300]:rp[301]] = ci_bad[rp[300]:rp[301]][::-1]
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    for cols in (ci_bad, ci, ci, ci_bad, ci_bad, ci, ci_bad, ci):
+        run_spmm(csrk, M, K, N, rp, cols, v, C)
+        run_fused(csrk, M, K, D, N, rp, cols, v, A, B, C)
+        run_sddmm(csrk, M, K, D, rp, cols, v, A, B)
