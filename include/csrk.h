@@ -120,8 +120,8 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
  * Plans: the sparsity pattern analysed once, for callers that use one pattern many
  * times (training loops; the paper's row analysis - nnzr, NT, nchunks of sections
  * "SDDMM" and "SPMM" - depends on the pattern alone).  The calls above look at the
- * pattern on the device on every call: a row-analysis launch (density, longest row)
- * ahead of an LDS-tiled kernel, a column-order check inside it, and the general
+ * pattern on the device on every call: a row analysis (density, longest row) ahead
+ * of or inside an LDS-tiled kernel, a column-order check inside it, and the general
  * kernel plus combine step launched behind it in case the device turns the tiled
  * kernel down.  A plan answers those questions once, on the host, so that a planned
  * call launches only the kernel that does the work (plus the combine step where the
