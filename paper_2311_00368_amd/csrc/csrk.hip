@@ -381,11 +381,17 @@ float wide_min_density(int M, int K, int N, bool fused) {
 float narrow_min_density(int M, int K, int N, bool fused) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const long long dense_bytes = (long long)K * N * 4;
-    if (N <= 32) return fused ? kNarrowMinDensity : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
+    // (FusedMM at 32 columns: the tiled kernel passes whole rows at 20 % only on the largest shapes, 24k/8k and 32k/8k)
+    if (N <= 32)
+        return fused ? ((M >= 24576 && K >= 8192) ? 0.18f : kNarrowMinDensity) : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
     const int size = dense_bytes >= (8ll << 20) ? 3 : dense_bytes >= (4ll << 20) ? 2 : dense_bytes >= (2ll << 20) ? 1 : 0;
     const int rows = M < 8192 ? 0 : M < 12288 ? 1 : 2;
-    static const float spmm[3][4] = {{0.17f, 0.17f, 0.15f, 0.06f}, {0.15f, 0.09f, 0.08f, 0.05f}, {0.08f, 0.07f, 0.07f, 0.045f}};
-    static const float fusedmm[3][4] = {{0.17f, 0.15f, 0.09f, 0.05f}, {0.15f, 0.09f, 0.09f, 0.05f}, {0.13f, 0.09f, 0.085f, 0.045f}};
+    // (below 8192 rows the attempt got cheaper when the row analysis moved into the tiled kernel: 4k/4k/128 at 10 %
+    // is now 9-13 % faster tiled, hence 0.095 from 2 MB; 12288 rows - 3 rows per wavefront - need 11 % at 2 MB,
+    // where 16384 rows win from 7 %)
+    static const float spmm[3][4] = {{0.17f, 0.095f, 0.095f, 0.06f}, {0.15f, 0.09f, 0.08f, 0.05f}, {0.08f, 0.07f, 0.07f, 0.045f}};
+    static const float fusedmm[3][4] = {{0.17f, 0.095f, 0.09f, 0.05f}, {0.15f, 0.09f, 0.09f, 0.05f}, {0.13f, 0.09f, 0.085f, 0.045f}};
+    if (rows == 2 && size == 1 && M < 16384) return 0.11f;
     if (fused && rows == 2 && size == 0 && N > 64) return 0.08f;
     return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
@@ -393,6 +399,8 @@ float narrow_min_density(int M, int K, int N, bool fused) {
 float sddmm_min_density(int M, int K, int D) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const bool big = (long long)K * D * 4 >= (8ll << 20);
+    // rows of B of more than 64 floats in an operand below 4 MB: whole rows keep up to 10 % (12k/4k/128: +37 %)
+    if (M >= 8192 && D > 64 && (long long)K * D * 4 < (4ll << 20)) return 0.12f;
     if (M < 8192) return big ? 0.08f : 0.15f;
     if (M < 12288) return big ? 0.05f : (D > 64 ? 0.09f : 0.08f);
     return big ? 0.05f : (D > 64 ? 0.09f : 0.05f);
