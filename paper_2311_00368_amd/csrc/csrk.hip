@@ -135,7 +135,11 @@ csrk_status ensure_scratch(DeviceState &d, int width, size_t min_floats = 0) {
             return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", bytes);
         }
         // both sets start with a clear ordering flag; from then on each tiled attempt clears the other set's
-        CSRK_HIP(hipMemset(d.head_row, 0, bytes));
+        if (hipMemset(d.head_row, 0, bytes) != hipSuccess) {
+            (void)hipFree(d.head_row);
+            d.head_row = nullptr;
+            return fail(CSRK_HIP_ERROR, "cannot clear the flag words of the scratch area");
+        }
         d.flag_set = 0;
     }
     if (need > d.head_floats) {
