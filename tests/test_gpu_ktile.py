@@ -295,3 +295,20 @@ def test_unsorted_and_sorted_patterns_in_turn(csrk):
         run_spmm(csrk, M, K, N, rp, cols, v, C)
         run_fused(csrk, M, K, D, N, rp, cols, v, A, B, C)
         run_sddmm(csrk, M, K, D, rp, cols, v, A, B)
+
+
+def test_released_workspace_is_rebuilt_with_clear_flags(csrk):
+    # the flag words live in the workspace: after a release the next tiled attempt must find them cleared again,
+    # also when the call before the release had reported descending columns
+    rng = np.random.default_rng(5)
+    M, K, N = 300, 400, 256
+    rp, ci = inputs.bernoulli_csr(8, M, K, 0.25)
+    ci_bad = ci.copy()
+    ci_bad[rp[10]:rp[11]] = ci_bad[rp[10]:rp[11]][::-1]
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    for cols in (ci_bad, ci, ci_bad, ci):
+        run_spmm(csrk, M, K, N, rp, cols, v, C)
+        torch.cuda.synchronize()
+        csrk.csrk_release_workspace()
+        run_spmm(csrk, M, K, N, rp, ci, v, C)
