@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -333,25 +334,39 @@ int tile_rows_for(const DeviceState &d, int M, int max_rows = 4, bool three = fa
     }
     return best;
 }
-// K-split (the small-M regime): when even one row per wavefront would leave CUs without a workgroup of the
-// tiled kernels, keep 4 rows per wavefront and cut K into S ranges instead, one workgroup per (row block,
-// range) - the counterpart, for the reduction dimension, of the paper's NT work-items per row (section
-// "SDDMM", the NT heuristic).  Returns S (1 = no split).  Every range keeps at least four tiles (with fewer the
-// split measured slower than one row per wavefront over the whole of K).
-int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block) {
+// K-split (the small-M regime): when 64-row workgroups leave CUs without work, keep 4 rows per wavefront and cut K
+// into S ranges instead, one workgroup per (row block, range) - the counterpart, for the reduction dimension, of
+// the paper's NT work-items per row (section "SDDMM", the NT heuristic).  Returns S (1 = no split).  Every range
+// keeps at least four tiles (with fewer the split measured slower than one row per wavefront over the whole of K).
+// The choice is by the cost model of tile_rows_for, rounds of `CUs` workgroups x per-workgroup work: without a
+// split rounds x (2 rows + 1) for 4, 3, 2 or 1 rows per wavefront, with S ranges rounds x 9 / S, marked up by 3 %
+// per range for the partial outputs that are written and added up; the cheapest wins.  Measured over S = 1..8 at
+// 3072 / 5000 / 6144 / 7168 / 10000 / 12288 rows (four shapes each, SPMM and FusedMM) the best S was
+// 5 / 3 / 5 / 2 / 3 / 4; "as many ranges as it takes to reach the CU count" (6 / 4 / 3 / 3 / 2 / 2) put a nearly
+// empty second round behind the first and cost 25-40 %.
+int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block, bool three = true) {
     if (env_int("CSRK_KSPLIT", 1) == 2) return 1;                  // 2 = off (tests and measurements)
+    const long long tiles = ((long long)K + tile_height - 1) / tile_height;
+    if (const int forced = env_int("CSRK_KSPLIT_S", 0))            // measurements: this many ranges if K allows
+        return forced <= tiles && forced <= kMaxKSplit ? forced : 1;
     const long long blocks = ((long long)M + rows_per_block - 1) / rows_per_block;
     if (blocks >= d.cus) return 1;
-    long long s = (d.cus + blocks - 1) / blocks;
-    const long long tiles = ((long long)K + tile_height - 1) / tile_height;
-    if (s > tiles / 4) s = tiles / 4;
-    if (s > kMaxKSplit) s = kMaxKSplit;
-    if (s < 2) return 1;
-    // worth it only if the split grid fills the CUs, or at least offers more workgroups than one row per
-    // wavefront over the whole of K would
-    const long long blocks1 = ((long long)M + kTileWaves - 1) / kTileWaves;
-    if (blocks * s < d.cus && blocks * s <= blocks1) return 1;
-    return (int)s;
+    auto rounds_of = [&](long long groups) { return (double)((groups + d.cus - 1) / d.cus); };
+    double best_cost = 1e30;
+    for (int rows = 4; rows >= 1; --rows)                          // no split (`three`: the kernel has a 3-row version here)
+        if (rows != 3 || three)
+            best_cost = fmin(best_cost, rounds_of(((long long)M + kTileWaves * rows - 1) / (kTileWaves * rows)) * (2 * rows + 1));
+    long long smax = tiles / 4;
+    if (smax > kMaxKSplit) smax = kMaxKSplit;
+    int best = 1;
+    for (long long s = 2; s <= smax; ++s) {
+        const double cost = rounds_of(blocks * s) * 9.0 / (double)s / (1.0 - 0.03 * (double)s);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = (int)s;
+        }
+    }
+    return best;
 }
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
 constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
@@ -371,10 +386,14 @@ float wide_min_density(int M, int K, int N, bool fused) {
     const long long dense_bytes = (long long)K * N * 4;
     const int size = dense_bytes >= (16ll << 20) ? 3 : dense_bytes >= (8ll << 20) ? 2 : dense_bytes >= (4ll << 20) ? 1 : 0;
     const int rows = M < 2048 ? 0 : M < 4096 ? 1 : M < 8192 ? 2 : 3;
-    static const float spmm[4][4] = {{1.f, 1.f, 0.20f, 0.05f}, {1.f, 0.10f, 0.05f, 0.025f}, {0.10f, 0.08f, 0.04f, kTileMinDensity},
+    static const float spmm[4][4] = {{1.f, 1.f, 0.20f, 0.05f}, {1.f, 0.10f, 0.05f, 0.025f}, {0.10f, 0.08f, 0.06f, kTileMinDensity},
                                      {0.07f, 0.06f, 0.035f, kTileMinDensity}};
     static const float fusedmm[4][4] = {{1.f, 1.f, 0.08f, 0.04f}, {1.f, 0.08f, 0.035f, kTileMinDensity},
-                                        {0.10f, 0.06f, 0.03f, kTileMinDensity}, {0.075f, 0.05f, 0.04f, kTileMinDensity}};
+                                        {0.10f, 0.06f, 0.06f, kTileMinDensity}, {0.075f, 0.05f, 0.04f, kTileMinDensity}};
+    // (4096 to 8191 rows, re-measured at 4096 and 6144 rows with the K ranges chosen as they are now: at 8 MB whole rows
+    // keep up to 5 % - level at 4096 rows, 11-20 % ahead at 6144 - and at 16 MB to 2 %; from 32 MB the tiled kernel is
+    // 38 % ahead at 2 %)
+    if (rows == 2 && size == 3 && dense_bytes < (32ll << 20)) return 0.03f;
     return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
 // Density from which the narrow tiled kernels beat what runs otherwise (whole rows for even matrices, which
@@ -685,7 +704,7 @@ template <int T, int KT, int SL>
 csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                                float *O) {
-    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
+    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4, fused_three_rows(d, M, N));
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
@@ -743,7 +762,7 @@ csrk_status launch_fused_narrow_g(DeviceState &d, hipStream_t st, int M, int K, 
                                   const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
                                   float *O) {
     // small M: keep 4 rows per wavefront and cut K into ranges (not for outputs of 32 columns or fewer)
-    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4);
+    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4, fused_three_rows(d, M, N));
     if (ksplit > 1) {
         if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
         return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
