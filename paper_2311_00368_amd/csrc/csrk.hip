@@ -344,31 +344,42 @@ int tile_rows_for(const DeviceState &d, int M, int max_rows = 4, bool three = fa
 // 3072 / 5000 / 6144 / 7168 / 10000 / 12288 rows (four shapes each, SPMM and FusedMM) the best S was
 // 5 / 3 / 5 / 2 / 3 / 4; "as many ranges as it takes to reach the CU count" (6 / 4 / 3 / 3 / 2 / 2) put a nearly
 // empty second round behind the first and cost 25-40 %.
-int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block, bool three = true) {
-    if (env_int("CSRK_KSPLIT", 1) == 2) return 1;                  // 2 = off (tests and measurements)
+struct TileGrid {
+    int ksplit;      // ranges of K (1 = no split)
+    double fill;     // work of the grid / capacity of the rounds it takes, by the cost model (1 = no CU ever idle)
+};
+TileGrid tile_grid_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block, bool three = true) {
     const long long tiles = ((long long)K + tile_height - 1) / tile_height;
-    if (const int forced = env_int("CSRK_KSPLIT_S", 0))            // measurements: this many ranges if K allows
-        return forced <= tiles && forced <= kMaxKSplit ? forced : 1;
     const long long blocks = ((long long)M + rows_per_block - 1) / rows_per_block;
-    if (blocks >= d.cus) return 1;
     auto rounds_of = [&](long long groups) { return (double)((groups + d.cus - 1) / d.cus); };
     double best_cost = 1e30;
     for (int rows = 4; rows >= 1; --rows)                          // no split (`three`: the kernel has a 3-row version here)
         if (rows != 3 || three)
             best_cost = fmin(best_cost, rounds_of(((long long)M + kTileWaves * rows - 1) / (kTileWaves * rows)) * (2 * rows + 1));
-    long long smax = tiles / 4;
-    if (smax > kMaxKSplit) smax = kMaxKSplit;
     int best = 1;
-    for (long long s = 2; s <= smax; ++s) {
-        const double cost = rounds_of(blocks * s) * 9.0 / (double)s / (1.0 - 0.03 * (double)s);
-        if (cost < best_cost) {
-            best_cost = cost;
-            best = (int)s;
+    const int mode = env_int("CSRK_KSPLIT", 1);                    // 2 = off (tests and measurements)
+    const int forced = env_int("CSRK_KSPLIT_S", 0);                // measurements: this many ranges if K allows
+    if (forced) {
+        if (forced <= tiles && forced <= kMaxKSplit) best = forced;
+    } else if (mode != 2 && blocks < d.cus) {
+        long long smax = tiles / 4;
+        if (smax > kMaxKSplit) smax = kMaxKSplit;
+        for (long long s = 2; s <= smax; ++s) {
+            const double cost = rounds_of(blocks * s) * 9.0 / (double)s / (1.0 - 0.03 * (double)s);
+            if (cost < best_cost) {
+                best_cost = cost;
+                best = (int)s;
+            }
         }
     }
-    return best;
+    const double ideal = (double)M / 64.0 * 9.0 / (double)d.cus;   // 4 rows per wavefront on every CU all the time
+    return {best, ideal / best_cost};
+}
+int ksplit_for(const DeviceState &d, int M, int K, int tile_height, int rows_per_block, bool three = true) {
+    return tile_grid_for(d, M, K, tile_height, rows_per_block, three).ksplit;
 }
 constexpr float kTileMinDensity = 0.02f;      // wide tiled kernels and tiled SDDMM
+constexpr double kWellFilled = 0.87;          // TileGrid::fill from which a grid counts as filling the CUs
 constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
 
 int32_t *tile_flags(DeviceState &d) { return d.plan_flags ? d.plan_flags : d.head_row + d.workers + 8 + 8 * d.flag_set; }
@@ -401,7 +412,7 @@ float wide_min_density(int M, int K, int N, bool fused) {
 // path gathers at L2 speed while K x N floats fit an XCD's 4 MB L2 and collapses beyond, the tiled kernels do not
 // care) and with M (every workgroup stages the whole operand through LDS whatever its rows hold: fewer rows per
 // CU, less to spread that over).
-float narrow_min_density(int M, int K, int N, bool fused) {
+float narrow_min_density(int M, int K, int N, bool fused, bool well_filled = false) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const long long dense_bytes = (long long)K * N * 4;
     // (FusedMM at 32 columns: the tiled kernel passes whole rows at 20 % only on the largest shapes, 24k/8k and 32k/8k)
@@ -409,12 +420,15 @@ float narrow_min_density(int M, int K, int N, bool fused) {
         return fused ? ((M >= 24576 && K >= 8192) ? 0.18f : kNarrowMinDensity) : (dense_bytes >= (2ll << 20) ? 0.12f : 0.15f);
     const int size = dense_bytes >= (8ll << 20) ? 3 : dense_bytes >= (4ll << 20) ? 2 : dense_bytes >= (2ll << 20) ? 1 : 0;
     const int rows = M < 8192 ? 0 : M < 12288 ? 1 : 2;
-    // (below 8192 rows the attempt got cheaper when the row analysis moved into the tiled kernel: 4k/4k/128 at 10 %
-    // is now 9-13 % faster tiled, hence 0.095 from 2 MB; 12288 rows - 3 rows per wavefront - need 11 % at 2 MB,
-    // where 16384 rows win from 7 %)
-    static const float spmm[3][4] = {{0.17f, 0.095f, 0.095f, 0.06f}, {0.15f, 0.09f, 0.08f, 0.05f}, {0.08f, 0.07f, 0.07f, 0.045f}};
-    static const float fusedmm[3][4] = {{0.17f, 0.095f, 0.09f, 0.05f}, {0.15f, 0.09f, 0.09f, 0.05f}, {0.13f, 0.09f, 0.085f, 0.045f}};
-    if (rows == 2 && size == 1 && M < 16384) return 0.11f;
+    static const float spmm[3][4] = {{0.17f, 0.17f, 0.15f, 0.06f}, {0.15f, 0.09f, 0.08f, 0.05f}, {0.08f, 0.07f, 0.07f, 0.045f}};
+    static const float fusedmm[3][4] = {{0.17f, 0.15f, 0.09f, 0.05f}, {0.15f, 0.09f, 0.09f, 0.05f}, {0.13f, 0.09f, 0.085f, 0.045f}};
+    // Below 8192 rows the attempt got cheap enough, once the row analysis had moved into the tiled kernel, for 10 % at
+    // 2 MB and more - where the grid fills the CUs (`well_filled`: 4096 rows in 4 ranges of K do exactly; 4k/4k/128 is
+    // 9-13 % faster tiled there).  Not at 3072 or between 5000 and 7168 rows, whose grids leave 15-20 % of the rounds
+    // empty and where whole rows stay 5-25 % ahead at 10 %.
+    if (rows == 0 && size >= 1 && well_filled) return fminf(fused ? fusedmm[0][size] : spmm[0][size], 0.095f);
+    // FusedMM at 12288 rows (no 3-row kernel at that width) needs 11 % at 2 MB, where 16384 rows win from 9 %
+    if (fused && rows == 2 && size == 1 && M < 16384) return 0.11f;
     if (fused && rows == 2 && size == 0 && N > 64) return 0.08f;
     return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
@@ -567,8 +581,9 @@ bool narrow_shape_ok(const DeviceState &d, int M, int K, int N, bool fused) {
     if (mode == 2) return true;
     const long long rows_per_cu = (long long)M / d.cus;
     if (N <= 32) return rows_per_cu >= (fused ? 96 : 32);   // tiny dense operand: the general path's gathers stay in cache
-    // at least one workgroup per CU at one row per wavefront, and enough cells of S (see sddmm_tile_shape_ok)
-    return rows_per_cu >= 16 && (long long)M * K >= (8ll << 20);
+    // at least 12 rows per CU (3072 rows: with K cut into ranges the tiled kernels are 10-45 % ahead of whole rows
+    // at 20 % density there), and enough cells of S (see sddmm_tile_shape_ok)
+    return rows_per_cu >= 12 && (long long)M * K >= (8ll << 20);
 }
 
 // tile height of the narrow SPMM kernel: as high as LDS allows with the 128-entry look-ahead in mind (256 rows
@@ -925,7 +940,8 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
         gate = tile_flags(*d);
         if (csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O)) return s;
     } else if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, false), &go))
+        const bool filled = tile_grid_for(*d, M, K, N > 64 ? narrow_kt<2>() : narrow_kt<4>(), kTileWaves * 4).fill >= kWellFilled;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, false, filled), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);
@@ -1089,7 +1105,9 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
         gate = tile_flags(*d);
         if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
     } else if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, true), &go))
+        const int kt = D > 64 ? 128 : (N > 64 ? fused_narrow_kt<2, 64>() : fused_narrow_kt<4, 64>());
+        const bool filled = tile_grid_for(*d, M, K, kt, kTileWaves * 4, fused_three_rows(*d, M, N)).fill >= kWellFilled;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, true, filled), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);
