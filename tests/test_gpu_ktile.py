@@ -312,3 +312,19 @@ def test_released_workspace_is_rebuilt_with_clear_flags(csrk):
         torch.cuda.synchronize()
         csrk.csrk_release_workspace()
         run_spmm(csrk, M, K, N, rp, ci, v, C)
+
+
+@pytest.mark.parametrize("S", [2, 3, 5, 7, 8])
+def test_every_number_of_k_ranges(csrk, monkeypatch, S):
+    # CSRK_KSPLIT_S fixes the number of ranges K is cut into (otherwise chosen from M and the CU count)
+    monkeypatch.setenv("CSRK_KSPLIT_S", str(S))
+    rng = np.random.default_rng(S)
+    M, K, D = 301, 4100, 64
+    rp, ci = inputs.bernoulli_csr(S, M, K, 0.1)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    for N in (512, 128, 64):
+        C = rng.normal(size=(K, N)).astype(np.float32)
+        run_spmm(csrk, M, K, N, rp, ci, v, C)
+        run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
