@@ -436,8 +436,10 @@ float narrow_min_density(int M, int K, int N, bool fused, bool well_filled = fal
 float sddmm_min_density(int M, int K, int D) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const bool big = (long long)K * D * 4 >= (8ll << 20);
-    // rows of B of more than 64 floats in an operand below 4 MB: whole rows keep up to 10 % (12k/4k/128: +37 %)
-    if (M >= 8192 && D > 64 && (long long)K * D * 4 < (4ll << 20)) return 0.12f;
+    // rows of B of more than 64 floats: whole rows keep up to 10 % with an operand below 4 MB (12k/4k/128: +37 %) and,
+    // below 16384 rows, below 8 MB (10000 and 12288 rows by 8192 columns: +25..+37 %; level at 8192 rows; from 24k
+    // rows the tiled kernel is 2-18 % ahead there)
+    if (M >= 8192 && D > 64 && ((long long)K * D * 4 < (4ll << 20) || (!big && M < 16384))) return 0.12f;
     if (M < 8192) return big ? 0.08f : 0.15f;
     if (M < 12288) return big ? 0.05f : (D > 64 ? 0.09f : 0.08f);
     return big ? 0.05f : (D > 64 ? 0.09f : 0.05f);
