@@ -392,19 +392,26 @@ int32_t *other_flags(DeviceState &d) { return d.plan_flags ? nullptr : d.head_ro
 // rows), by the size of the gathered dense operand (columns: 2, 4, 8, 16 MB and more) and by M (rows of the table:
 // below 2048, 4096, 8192 rows, and above); 1 = never.  Read off a grid of 100 (M, K, N, density) points with
 // whole calls timed.
-float wide_min_density(int M, int K, int N, bool fused) {
+float wide_min_density(int M, int K, int N, bool fused, bool well_filled = false) {
     if (env_int("CSRK_KTILE", 1) == 2) return -1.f;
     const long long dense_bytes = (long long)K * N * 4;
     const int size = dense_bytes >= (16ll << 20) ? 3 : dense_bytes >= (8ll << 20) ? 2 : dense_bytes >= (4ll << 20) ? 1 : 0;
     const int rows = M < 2048 ? 0 : M < 4096 ? 1 : M < 8192 ? 2 : 3;
-    static const float spmm[4][4] = {{1.f, 1.f, 0.20f, 0.05f}, {1.f, 0.10f, 0.05f, 0.025f}, {0.10f, 0.08f, 0.06f, kTileMinDensity},
+    static const float spmm[4][4] = {{1.f, 1.f, 0.20f, 0.05f}, {1.f, 0.08f, 0.05f, 0.015f}, {0.10f, 0.08f, 0.06f, kTileMinDensity},
                                      {0.07f, 0.06f, 0.035f, kTileMinDensity}};
     static const float fusedmm[4][4] = {{1.f, 1.f, 0.08f, 0.04f}, {1.f, 0.08f, 0.035f, kTileMinDensity},
-                                        {0.10f, 0.06f, 0.06f, kTileMinDensity}, {0.075f, 0.05f, 0.04f, kTileMinDensity}};
-    // (4096 to 8191 rows, re-measured at 4096 and 6144 rows with the K ranges chosen as they are now: at 8 MB whole rows
-    // keep up to 5 % - level at 4096 rows, 11-20 % ahead at 6144 - and at 16 MB to 2 %; from 32 MB the tiled kernel is
-    // 38 % ahead at 2 %)
-    if (rows == 2 && size == 3 && dense_bytes < (32ll << 20)) return 0.03f;
+                                        {0.10f, 0.06f, 0.06f, kTileMinDensity}, {0.075f, 0.07f, 0.04f, kTileMinDensity}};
+    // (re-measured at 2048 ... 20000 rows with the K ranges chosen as they are now.  From 4096 rows: at 8 MB whole rows
+    // keep up to 5 % - level at 4096 rows, 11-20 % ahead at 6144 - and at 16 MB to 2 %, by 13-34 % from 10000 rows; from
+    // 32 MB the tiled kernel is 6-38 % ahead at 2 %.  2048 to 4095 rows: tiled 16 % ahead at 10 % and 4 MB, 25-36 % at
+    // 2 % and 16 MB and more.  FusedMM from 8192 rows at 4 MB: whole rows 28 % ahead at 5 %.)
+    // 4096 to 8191 rows whose grid fills the CUs (`well_filled`: 4096 rows split into ranges of K do, 6144 rows leave a
+    // quarter of the last round empty): tiled 20-60 % ahead at 5 % and 8 MB and at 2 % from 16 MB, 8 % at 5 % and 4 MB
+    if (rows == 2 && well_filled) {
+        static const float filled[4] = {0.09f, 0.06f, 0.04f, 0.015f};
+        return size == 1 && !fused ? 0.045f : filled[size];      // (FusedMM at 4 MB and 5 %: whole rows 5-7 % ahead)
+    }
+    if (rows >= 2 && size == 3 && dense_bytes < (32ll << 20)) return 0.03f;
     return fused ? fusedmm[rows][size] : spmm[rows][size];
 }
 // Density from which the narrow tiled kernels beat what runs otherwise (whole rows for even matrices, which
@@ -952,7 +959,8 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
     } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
         // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
         // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, false), &go))
+        const bool filled = tile_grid_for(*d, M, K, N <= 256 ? 128 : 64, kTileWaves * 4).fill >= kWellFilled;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, false, filled), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);
@@ -1116,7 +1124,9 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
             if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
         }
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, true), &go))
+        const bool filled =
+            tile_grid_for(*d, M, K, N <= 256 ? 96 : 64, kTileWaves * 4, fused_three_rows(*d, M, N)).fill >= kWellFilled;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, true, filled), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);
