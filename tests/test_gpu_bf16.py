@@ -98,3 +98,11 @@ def test_bf16_nan_in_unreferenced_rows_does_not_leak(csrk):
     B[poisoned] = np.nan
     C[poisoned] = np.inf
     run_all(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
+def test_bf16_at_the_benchmark_size_on_sampled_rows(csrk):
+    # 16384 x 16384 at 20 %, widths 64 / 512 (what `bench.py --bf16` times): every 32nd output row and the ends
+    w = inputs.workload("large16k")
+    rows = np.unique(np.concatenate([np.arange(3, w.M, 32), [0, w.M - 1]])).astype(np.int32)
+    f = w.ops["fusedmm"]
+    run_all(csrk, w.M, w.K, 64, 512, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)

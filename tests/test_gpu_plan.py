@@ -49,6 +49,20 @@ class Planned:
         want, a = oracle.fusedmm(self.M, self.K, D, N, self.rp, self.ci, v, A, B, C)
         check(O.cpu().numpy(), want, a, f"planned fusedmm M={self.M} K={self.K} D={D} N={N}")
 
+    def sampled(self, rows, D, N, v, A, B, C, B_spmm):
+        """All three operations, the oracle on the output rows in `rows` only (rows are independent)."""
+        d_v = dev(v)
+        O = self.csrk.spmm_csr_plan(self.plan, N, d_v, dev(B_spmm))
+        want, a = oracle.spmm(self.M, self.K, N, self.rp, self.ci, v, B_spmm, rows=rows)
+        check(O.cpu().numpy()[rows], want, a, f"planned spmm M={self.M} N={N}, {len(rows)} rows")
+        O = self.csrk.fusedmm_csr_plan(self.plan, D, N, d_v, dev(A), dev(B), dev(C))
+        want, a = oracle.fusedmm(self.M, self.K, D, N, self.rp, self.ci, v, A, B, C, rows=rows)
+        check(O.cpu().numpy()[rows], want, a, f"planned fusedmm M={self.M} D={D} N={N}, {len(rows)} rows")
+        P = self.csrk.sddmm_csr_plan(self.plan, D, d_v, dev(A), dev(B))
+        want, a = oracle.sddmm(self.M, self.K, D, self.rp, self.ci, v, A, B, rows=rows)
+        sel = ~np.isnan(want)
+        check(P.cpu().numpy()[sel], want[sel], a[sel], f"planned sddmm M={self.M} D={D}, {len(rows)} rows")
+
     def all_ops(self, rng, D, N, ones=False):
         nnz = len(self.ci)
         v = None if ones else rng.uniform(-1, 1, nnz).astype(np.float32)
@@ -113,6 +127,17 @@ def test_planned_calls_with_very_many_short_rows(csrk):
     pl = Planned(csrk, M, K, rp, ci)
     pl.all_ops(rng, 16, 32)
     pl.all_ops(rng, 64, 128)
+    pl.close()
+
+
+def test_planned_calls_at_the_benchmark_size_on_sampled_rows(csrk):
+    # the 16384 x 16384 workload the benchmark times, planned: every 16th output row and the first and last rows
+    w = inputs.workload("large16k")
+    rows = np.unique(np.concatenate([np.arange(5, w.M, 16), [0, 1, w.M - 2, w.M - 1]])).astype(np.int32)
+    pl = Planned(csrk, w.M, w.K, w.rowptr, w.colidx)
+    assert csrk.csrk_plan_info(pl.plan) == (len(w.colidx), True, True)
+    f = w.ops["fusedmm"]
+    pl.sampled(rows, 64, 512, w.vals, f["A"], f["B"], f["C"], w.ops["spmm"]["B"])
     pl.close()
 
 
