@@ -452,10 +452,12 @@ float sddmm_min_density(int M, int K, int D) {
     return big ? 0.05f : (D > 64 ? 0.09f : 0.05f);
 }
 
+constexpr int kWideSlab = 512;      // columns one wide tiled kernel holds in registers
+constexpr int kWideMaxN = 2048;     // widest output the wide tiled kernels take, in slabs (wide_slab_width)
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     const int mode = env_int("CSRK_KTILE", 1);       // 1 auto, 2 force where the kernel can run, 3 off
     if (mode == 3) return false;
-    if (N % 4 != 0 || N > 512 || N <= 128) return mode == 2 && N % 4 == 0 && N <= 512;
+    if (N % 4 != 0 || N > kWideMaxN || N <= 128) return mode == 2 && N % 4 == 0 && N <= kWideMaxN;
     if (mode == 2) return true;
     // Measured cross-over with the general path (whose gathers run at L2 speed while the dense operand fits an
     // XCD's L2 and collapse beyond): a dense operand of 8 MB or more with at least 1024 rows, 4 MB with 2048,
@@ -653,7 +655,7 @@ csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int N, c
 }
 
 template <int T, int KT, int ROWS>
-csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
+csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int N, int ld, int col0, const int32_t *rp,
                               const int32_t *ci, const float *v, const float *B, float *O, int ksplit = 1) {
     using L = KTileLds<T, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
@@ -667,28 +669,37 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, B,
-                       O, tile_flags(d), d.head, d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, ld, rp, ci, v,
+                       B + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
+// One launch of the wide SPMM kernel over columns [col0, col0 + N) of operands whose rows are `ld` floats long
+// (ld = N, col0 = 0: the whole operand).  Partial outputs of a K-split launch keep the full row length, so one
+// combine step serves all the slabs of a call.
 template <int T, int KT>
-csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp, const int32_t *ci,
-                         const float *v, const float *B, float *O) {
-    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4);
+csrk_status launch_ktile(DeviceState &d, hipStream_t st, int M, int K, int N, int ld, int col0, const int32_t *rp,
+                         const int32_t *ci, const float *v, const float *B, float *O, int fixed_ksplit = 0) {
+    const int ksplit = fixed_ksplit ? fixed_ksplit : ksplit_for(d, M, K, KT, kTileWaves * 4);
     if (ksplit > 1) {
-        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O, ksplit);
+        if (csrk_status s = ensure_scratch(d, ld, (size_t)ksplit * (size_t)M * (size_t)ld)) return s;
+        return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, ld, col0, rp, ci, v, B, O, ksplit);
     }
     switch (tile_rows_for(d, M, 4, true)) {
-        case 4: return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, rp, ci, v, B, O);
-        case 3: return launch_ktile_rows<T, KT, 3>(d, st, M, K, N, rp, ci, v, B, O);
-        case 2: return launch_ktile_rows<T, KT, 2>(d, st, M, K, N, rp, ci, v, B, O);
-        default: return launch_ktile_rows<T, KT, 1>(d, st, M, K, N, rp, ci, v, B, O);
+        case 4: return launch_ktile_rows<T, KT, 4>(d, st, M, K, N, ld, col0, rp, ci, v, B, O);
+        case 3: return launch_ktile_rows<T, KT, 3>(d, st, M, K, N, ld, col0, rp, ci, v, B, O);
+        case 2: return launch_ktile_rows<T, KT, 2>(d, st, M, K, N, ld, col0, rp, ci, v, B, O);
+        default: return launch_ktile_rows<T, KT, 1>(d, st, M, K, N, ld, col0, rp, ci, v, B, O);
     }
 }
+
+// Outputs wider than the 512 columns one wide tiled kernel holds in registers go in slabs of 512 columns and a
+// remainder, one launch per slab (the 256-wide kernel for a remainder of up to 256 columns).  Every slab walks S
+// again: 8 bytes per entry against 2 KB of dense row per entry and slab.  All slabs of a call are cut into the same
+// number of K ranges - one combine step adds their partial outputs - chosen for the tallest tile among their kernels.
+bool wide_remainder_is_small(int N) { return N % kWideSlab != 0 && N % kWideSlab <= 256; }
 
 // FusedMM's 3-row version carries the score-stage work and registers of four rows, so it pays only where 48-row
 // workgroups save a whole round of the grid against 32-row ones and the accumulate stage is long: measured at
@@ -698,9 +709,9 @@ bool fused_three_rows(const DeviceState &d, int M, int N) {
 }
 
 template <int T, int KT, int ROWS, int SL, int LIVE = ROWS>
-csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                                    const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                                    float *O, int ksplit = 1) {
+csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, int ld, int col0,
+                                    const int32_t *rp, const int32_t *ci, const float *v, const float *A, const float *B,
+                                    const float *C, float *O, int ksplit = 1) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
@@ -717,28 +728,30 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * LIVE;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
-                       A, B, C, O, tile_flags(d), d.head, d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, ld, rp, ci,
+                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
 }
 
 template <int T, int KT, int SL>
-csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
-                               const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                               float *O) {
-    const int ksplit = ksplit_for(d, M, K, KT, kTileWaves * 4, fused_three_rows(d, M, N));
+csrk_status launch_fused_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, int N, int ld, int col0,
+                               const int32_t *rp, const int32_t *ci, const float *v, const float *A, const float *B,
+                               const float *C, float *O, int fixed_ksplit = 0) {
+    // columns [col0, col0 + N) of C and O, whose rows are `ld` floats long (see launch_ktile); every slab of a wider
+    // output computes the scores again, a sixth of its work at 512 columns
+    const int ksplit = fixed_ksplit ? fixed_ksplit : ksplit_for(d, M, K, KT, kTileWaves * 4, fused_three_rows(d, M, N));
     if (ksplit > 1) {
-        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+        if (csrk_status s = ensure_scratch(d, ld, (size_t)ksplit * (size_t)M * (size_t)ld)) return s;
+        return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, ld, col0, rp, ci, v, A, B, C, O, ksplit);
     }
     // 3 rows per wavefront: the kernel laid out for 4, the fourth row of every wavefront empty (see fused_three_rows)
     switch (tile_rows_for(d, M, 4, fused_three_rows(d, M, N))) {
-        case 4: return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 3: return launch_fused_ktile_rows<T, KT, 4, SL, 3>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 2: return launch_fused_ktile_rows<T, KT, 2, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        default: return launch_fused_ktile_rows<T, KT, 1, SL>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 4: return launch_fused_ktile_rows<T, KT, 4, SL>(d, st, M, K, D, N, ld, col0, rp, ci, v, A, B, C, O);
+        case 3: return launch_fused_ktile_rows<T, KT, 4, SL, 3>(d, st, M, K, D, N, ld, col0, rp, ci, v, A, B, C, O);
+        case 2: return launch_fused_ktile_rows<T, KT, 2, SL>(d, st, M, K, D, N, ld, col0, rp, ci, v, A, B, C, O);
+        default: return launch_fused_ktile_rows<T, KT, 1, SL>(d, st, M, K, D, N, ld, col0, rp, ci, v, A, B, C, O);
     }
 }
 
@@ -964,9 +977,19 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
             return s;
         if (go) {
             gate = tile_flags(*d);
-            csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, rowptr, colidx, vals, B, O)
-                                     : launch_ktile<2, 64>(*d, stream, M, K, N, rowptr, colidx, vals, B, O);
-            if (s) return s;
+            if (N <= kWideSlab) {
+                csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, N, 0, rowptr, colidx, vals, B, O)
+                                         : launch_ktile<2, 64>(*d, stream, M, K, N, N, 0, rowptr, colidx, vals, B, O);
+                if (s) return s;
+            } else {
+                const int S = ksplit_for(*d, M, K, wide_remainder_is_small(N) ? 128 : 64, kTileWaves * 4);
+                for (int c0 = 0; c0 < N; c0 += kWideSlab) {
+                    const int w = N - c0 < kWideSlab ? N - c0 : kWideSlab;
+                    csrk_status s = w <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, w, N, c0, rowptr, colidx, vals, B, O, S)
+                                             : launch_ktile<2, 64>(*d, stream, M, K, w, N, c0, rowptr, colidx, vals, B, O, S);
+                    if (s) return s;
+                }
+            }
         }
     }
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole
@@ -1130,10 +1153,22 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
             return s;
         if (go) {
             gate = tile_flags(*d);
-            csrk_status s =
-                N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)
-                         : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O);
-            if (s) return s;
+            if (N <= kWideSlab) {
+                csrk_status s =
+                    N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, N, 0, rowptr, colidx, vals, A, B, C, O)
+                             : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, N, N, 0, rowptr, colidx, vals, A, B, C, O);
+                if (s) return s;
+            } else {
+                const int S = ksplit_for(*d, M, K, wide_remainder_is_small(N) ? 96 : 64, kTileWaves * 4,
+                                         fused_three_rows(*d, M, N));
+                for (int c0 = 0; c0 < N; c0 += kWideSlab) {
+                    const int w = N - c0 < kWideSlab ? N - c0 : kWideSlab;
+                    csrk_status s =
+                        w <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, w, N, c0, rowptr, colidx, vals, A, B, C, O, S)
+                                 : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, w, N, c0, rowptr, colidx, vals, A, B, C, O, S);
+                    if (s) return s;
+                }
+            }
         }
     }
     const int32_t *even = nullptr;          // device flag: rows even enough to be dealt out whole

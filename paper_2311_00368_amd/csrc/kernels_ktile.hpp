@@ -245,7 +245,7 @@ struct KTileLds {
 // SPMM: O[row, :] = sum over the row's entries of value * B[column, :] (Algorithm 2), B called Cmat here.
 template <int T, int KT, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
-    int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int M, int K, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
     float *partial, float inline_density, int32_t *other_flags) {
     using L = KTileLds<T, KT>;
@@ -286,7 +286,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
-    const int n4 = N >> 2;                  // float4s per dense row
+    const int n4 = N >> 2;                  // float4s of a dense row that this launch works on ...
+    const int ld4 = ld >> 2;                // ... out of this many (a launch may take a slab of the columns)
     constexpr int kRow4 = T * 64;
     constexpr int kPer = KT * kRow4 / kTileThreads;
     float4 stage[kPer];
@@ -296,10 +297,10 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
     const bool my_col = my_c4 < n4;
-    const size_t my_off = (size_t)my_kk * n4 + my_c4;
-    const size_t step_off = (size_t)kStep * n4;
+    const size_t my_off = (size_t)my_kk * ld4 + my_c4;
+    const size_t step_off = (size_t)kStep * ld4;
     auto issue = [&](int k0) {
-        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * ld4;   // uniform
         if (k0 + KT <= K) {
 #pragma unroll
             for (int i = 0; i < kPer; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -440,14 +441,14 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         }
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
         if (row < M) {
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * N + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * ld + n + tt * 256, acc[r][tt]);
         }
     }
 }

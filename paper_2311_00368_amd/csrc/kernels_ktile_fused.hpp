@@ -1,5 +1,5 @@
-// LDS-tiled FusedMM for wide outputs (128 < N <= 512, D <= 64): O = (S .* (A B^T)) C with the
-// scores kept on the CU (Algorithm 3's `arow`).
+// LDS-tiled FusedMM for wide outputs (128 < N <= 512 per launch, wider outputs in column slabs;
+// D <= 64): O = (S .* (A B^T)) C with the scores kept on the CU (Algorithm 3's `arow`).
 //
 // The accumulate stage is the SPMM tile kernel's: a workgroup of 16 wavefronts owns 16*ROWS rows
 // of S, sweeps K in tiles of KT columns of C staged in LDS, and every wavefront adds, for each of
@@ -40,7 +40,7 @@ struct FusedTileLds {
 // tile_rows_for on the host): laid out for four rows, the fourth one of every wavefront empty.
 template <int T, int KT, int ROWS, int SL, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
-    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int M, int K, int D, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
     int32_t *other_flags) {
@@ -101,7 +101,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     if (my_r < LIVE && row0 + my_r < M && i16 * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + i16 * 4, a);
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
-    const int n4 = N >> 2;                  // float4s per row of C
+    const int n4 = N >> 2;                  // float4s of a row of C that this launch works on ...
+    const int ld4 = ld >> 2;                // ... out of this many (a launch may take a slab of the columns)
     constexpr int kRow4 = T * 64;
     constexpr int kPer = KT * kRow4 / kTileThreads;
     constexpr int kPerB = (KT * 16 + kTileThreads - 1) / kTileThreads;
@@ -111,11 +112,11 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
     const bool my_col = my_c4 < n4;
-    const size_t my_off = (size_t)my_kk * n4 + my_c4;
-    const size_t step_off = (size_t)kStep * n4;
+    const size_t my_off = (size_t)my_kk * ld4 + my_c4;
+    const size_t step_off = (size_t)kStep * ld4;
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
-        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * ld4;   // uniform
         if (k0 + KT <= K) {
 #pragma unroll
             for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -366,14 +367,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         }
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int row = row0 + r;
         if (r < LIVE && row < M) {
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * N + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * ld + n + tt * 256, acc[r][tt]);
         }
     }
 }

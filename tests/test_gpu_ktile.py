@@ -1,8 +1,8 @@
 """The LDS-tiled SPMM / FusedMM kernels against the CPU oracle.
 
 By default the library picks these kernels only for large shapes; CSRK_KTILE=2 makes it take
-them wherever the kernel can run at all (output width a multiple of 4 up to 512, dot length a
-multiple of 4 up to 64), so small and ragged cases reach them too.  Patterns the kernels cannot
+them wherever the kernel can run at all (output width a multiple of 4 up to 2048 - beyond 512 in
+column slabs, one launch each - dot length a multiple of 4 up to 64), so small and ragged cases reach them too.  Patterns the kernels cannot
 take (columns not ascending, or too sparse) must fall back to the general kernels on the device
 and still give the right answer."""
 import os
@@ -328,3 +328,46 @@ def test_every_number_of_k_ranges(csrk, monkeypatch, S):
         C = rng.normal(size=(K, N)).astype(np.float32)
         run_spmm(csrk, M, K, N, rp, ci, v, C)
         run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+
+
+# outputs wider than one kernel's 512 columns: slabs of 512 columns and a remainder, one launch each (516 -> 512 + 4;
+# 768 -> 512 + 256, the remainder in the 256-wide kernel; 1500 -> 512 + 512 + 476; 2048 -> 4 x 512); M = 130 and 300
+# with long rows take the K-split and its shared combine step
+@pytest.mark.parametrize("M,K,N", [(64, 64, 516), (333, 417, 768), (1000, 129, 1024), (130, 3000, 1500), (2100, 700, 2048),
+                                   (300, 4096, 1024)])
+@pytest.mark.parametrize("p", [0.05, 0.4])
+def test_outputs_wider_than_one_kernel_go_in_column_slabs(csrk, M, K, N, p):
+    rng = np.random.default_rng(M + K + N)
+    rp, ci = inputs.bernoulli_csr(N, M, K, p)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, 64)).astype(np.float32)
+    B = rng.normal(size=(K, 64)).astype(np.float32)
+    C = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C)
+    run_fused(csrk, M, K, 64, N, rp, ci, v, A, B, C)
+    run_fused(csrk, M, K, 40, N, rp, ci, None, A[:, :40].copy(), B[:, :40].copy(), C)
+    # a plan on the same pattern, and the same pattern with one row written backwards (general kernels redo it)
+    plan = csrk.csrk_plan_create(M, K, dev(rp), dev(ci))
+    got = csrk.spmm_csr_plan(plan, N, dev(v), dev(C))
+    assert torch.equal(got, csrk.spmm_csr(M, K, N, dev(rp), dev(ci), dev(v), dev(C)))
+    csrk.csrk_plan_destroy(plan)
+    r = M // 2
+    ci2, v2 = ci.copy(), v.copy()
+    ci2[rp[r]:rp[r + 1]] = ci2[rp[r]:rp[r + 1]][::-1]
+    v2[rp[r]:rp[r + 1]] = v2[rp[r]:rp[r + 1]][::-1]
+    run_spmm(csrk, M, K, N, rp, ci2, v2, C)
+    run_fused(csrk, M, K, 64, N, rp, ci2, v2, A, B, C)
+
+
+def test_wide_outputs_with_automatic_kernel_choice(csrk, monkeypatch):
+    monkeypatch.setenv("CSRK_KTILE", "1")
+    M, K, N = 4096, 4096, 1024
+    rng = np.random.default_rng(8)
+    rp, ci = inputs.bernoulli_csr(3, M, K, 0.1)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, 64)).astype(np.float32)
+    B = rng.normal(size=(K, 64)).astype(np.float32)
+    C = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    rows = np.arange(0, M, 8, dtype=np.int32)
+    run_spmm(csrk, M, K, N, rp, ci, v, C, rows=rows)
+    run_fused(csrk, M, K, 64, N, rp, ci, v, A, B, C, rows=rows)
