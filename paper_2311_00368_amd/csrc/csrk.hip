@@ -769,7 +769,8 @@ constexpr int fused_narrow_kt() {
 template <int G, int ROWS, int DMAX, int LIVE = ROWS>
 csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                      const int32_t *ci, const float *v, const float *A, const float *B,
-                                     const float *C, float *O, int ksplit = 1) {
+                                     const float *C, float *O, int ksplit = 1, int ld = 0, int col0 = 0) {
+    if (ld == 0) ld = N;        // otherwise: columns [col0, col0 + N) of C and O, whose rows are `ld` floats long
     constexpr int KT = fused_narrow_kt<G, DMAX>();
     constexpr int SL = 64;
     using L = FusedNarrowLds<G, KT, ROWS, SL, DMAX>;
@@ -787,8 +788,8 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * LIVE;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, rp, ci, v,
-                       A, B, C, O, tile_flags(d), d.head, d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, ld, rp, ci,
+                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -797,18 +798,21 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
 template <int G, int DMAX>
 csrk_status launch_fused_narrow_g(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                   const int32_t *ci, const float *v, const float *A, const float *B, const float *C,
-                                  float *O) {
+                                  float *O, int ld = 0, int col0 = 0, int fixed_ksplit = 0) {
+    if (ld == 0) ld = N;        // otherwise a slab of a wider output (see launch_ktile), all slabs with one K-split
     // small M: keep 4 rows per wavefront and cut K into ranges (not for outputs of 32 columns or fewer)
-    const int ksplit = G == 8 ? 1 : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4, fused_three_rows(d, M, N));
+    const int ksplit = fixed_ksplit ? fixed_ksplit
+                       : G == 8     ? 1
+                                    : ksplit_for(d, M, K, fused_narrow_kt<G, DMAX>(), kTileWaves * 4, fused_three_rows(d, M, N));
     if (ksplit > 1) {
-        if (csrk_status s = ensure_scratch(d, N, (size_t)ksplit * (size_t)M * (size_t)N)) return s;
-        return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit);
+        if (csrk_status s = ensure_scratch(d, ld, (size_t)ksplit * (size_t)M * (size_t)ld)) return s;
+        return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, ksplit, ld, col0);
     }
     switch (tile_rows_for(d, M, 4, fused_three_rows(d, M, N))) {
-        case 4: return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 3: return launch_fused_narrow_rows<G, 4, DMAX, 3>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        case 2: return launch_fused_narrow_rows<G, 2, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
-        default: return launch_fused_narrow_rows<G, 1, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+        case 4: return launch_fused_narrow_rows<G, 4, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, ld, col0);
+        case 3: return launch_fused_narrow_rows<G, 4, DMAX, 3>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, ld, col0);
+        case 2: return launch_fused_narrow_rows<G, 2, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, ld, col0);
+        default: return launch_fused_narrow_rows<G, 1, DMAX>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, ld, col0);
     }
 }
 
@@ -1168,6 +1172,26 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
                                  : launch_fused_ktile<2, 64, 32>(*d, stream, M, K, D, w, N, c0, rowptr, colidx, vals, A, B, C, O, S);
                     if (s) return s;
                 }
+            }
+        }
+    } else if (nvec4 && dvec4 && D > 64 && D <= 128 && ktile_shape_ok(*d, M, K, N)) {
+        // Dot products of 65 to 128 floats with a wide output: the wide kernel has no room for such rows of B beside
+        // its tile of C, so the narrow kernel takes the output 128 columns at a time, one launch per slab, each
+        // computing the scores again (half of a slab's work).  Measured on 16384^2 / 20 %, D = 128: N = 512
+        // 11.4 -> 4.9 ms, N = 256 5.6 -> 2.5 ms; level with the general kernels at 5 % (8192^2).
+        constexpr int kSlab = 128;
+        const bool three = fused_three_rows(*d, M, kSlab);
+        const float min_density =
+            env_int("CSRK_KTILE", 1) == 2 ? -1.f : ((long long)K * N * 4 >= (16ll << 20) ? 0.06f : 0.10f);
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, min_density, &go)) return s;
+        if (go) {
+            gate = tile_flags(*d);
+            const int S = ksplit_for(*d, M, K, fused_narrow_kt<2, 128>(), kTileWaves * 4, three);
+            for (int c0 = 0; c0 < N; c0 += kSlab) {
+                const int w = N - c0 < kSlab ? N - c0 : kSlab;
+                if (csrk_status s = launch_fused_narrow_g<2, 128>(*d, stream, M, K, D, w, rowptr, colidx, vals, A, B, C, O,
+                                                                  N, c0, S))
+                    return s;
             }
         }
     }

@@ -397,7 +397,7 @@ struct FusedNarrowLds {
 
 template <int G, int KT, int ROWS, int SL, int DMAX, int PF, int LIVE = ROWS>
 __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
-    int M, int K, int D, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int M, int K, int D, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
     int32_t *other_flags) {
@@ -470,7 +470,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
-    const int n4 = N >> 2;                  // float4s per row of C
+    const int n4 = N >> 2;                  // float4s of a row of C that this launch works on ...
+    const int ld4 = ld >> 2;                // ... out of this many (a launch may take a slab of the columns)
     constexpr int kRow4 = 64 / G;
     constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
     constexpr int kPer = KT / kStep;
@@ -482,11 +483,11 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     float4 stageb[kPerB];
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
     const bool my_col = my_c4 < n4;
-    const size_t my_off = (size_t)my_kk * n4 + my_c4;
-    const size_t step_off = (size_t)kStep * n4;
+    const size_t my_off = (size_t)my_kk * ld4 + my_c4;
+    const size_t step_off = (size_t)kStep * ld4;
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
-        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * n4;   // uniform
+        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * ld4;   // uniform
         if (k0 + KT <= K) {
 #pragma unroll
             for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -714,7 +715,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
     // add the G partial rows of every row and store
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
+    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
 #pragma unroll
@@ -722,7 +723,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
         const int row = row0 + r;
-        if (r < LIVE && row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
+        if (r < LIVE && row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * ld + n, acc[r]);
     }
 }
 

@@ -346,6 +346,11 @@ def test_outputs_wider_than_one_kernel_go_in_column_slabs(csrk, M, K, N, p):
     run_spmm(csrk, M, K, N, rp, ci, v, C)
     run_fused(csrk, M, K, 64, N, rp, ci, v, A, B, C)
     run_fused(csrk, M, K, 40, N, rp, ci, None, A[:, :40].copy(), B[:, :40].copy(), C)
+    # dot products of 65 to 128 floats: the narrow kernel, 128 columns of the output per launch
+    A2 = rng.normal(size=(M, 128)).astype(np.float32)
+    B2 = rng.normal(size=(K, 128)).astype(np.float32)
+    run_fused(csrk, M, K, 128, N, rp, ci, v, A2, B2, C)
+    run_fused(csrk, M, K, 100, N, rp, ci, None, A2[:, :100].copy(), B2[:, :100].copy(), C)
     # a plan on the same pattern, and the same pattern with one row written backwards (general kernels redo it)
     plan = csrk.csrk_plan_create(M, K, dev(rp), dev(ci))
     got = csrk.spmm_csr_plan(plan, N, dev(v), dev(C))
@@ -357,6 +362,24 @@ def test_outputs_wider_than_one_kernel_go_in_column_slabs(csrk, M, K, N, p):
     v2[rp[r]:rp[r + 1]] = v2[rp[r]:rp[r + 1]][::-1]
     run_spmm(csrk, M, K, N, rp, ci2, v2, C)
     run_fused(csrk, M, K, 64, N, rp, ci2, v2, A, B, C)
+    run_fused(csrk, M, K, 128, N, rp, ci2, v2, A2, B2, C)
+
+
+@pytest.mark.parametrize("M,K,D,N", [(333, 417, 128, 256), (1000, 700, 72, 512), (130, 3000, 128, 260), (2100, 300, 96, 200)])
+@pytest.mark.parametrize("p", [0.05, 0.3, 1.0])
+def test_fusedmm_long_dot_products_with_wide_outputs(csrk, M, K, D, N, p):
+    rng = np.random.default_rng(M + K + N + D)
+    rp, ci = inputs.bernoulli_csr(N + D, M, K, p)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+    run_fused(csrk, M, K, D, N, rp, ci, None, A, B, C)
+    plan = csrk.csrk_plan_create(M, K, dev(rp), dev(ci))
+    got = csrk.fusedmm_csr_plan(plan, D, N, dev(v), dev(A), dev(B), dev(C))
+    assert torch.equal(got, csrk.fusedmm_csr(M, K, D, N, dev(rp), dev(ci), dev(v), dev(A), dev(B), dev(C)))
+    csrk.csrk_plan_destroy(plan)
 
 
 def test_wide_outputs_with_automatic_kernel_choice(csrk, monkeypatch):
@@ -371,3 +394,6 @@ def test_wide_outputs_with_automatic_kernel_choice(csrk, monkeypatch):
     rows = np.arange(0, M, 8, dtype=np.int32)
     run_spmm(csrk, M, K, N, rp, ci, v, C, rows=rows)
     run_fused(csrk, M, K, 64, N, rp, ci, v, A, B, C, rows=rows)
+    A2 = rng.normal(size=(M, 128)).astype(np.float32)
+    B2 = rng.normal(size=(K, 128)).astype(np.float32)
+    run_fused(csrk, M, K, 128, 512, rp, ci, v, A2, B2, np.ascontiguousarray(C[:, :512]), rows=rows)
