@@ -469,6 +469,7 @@ bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
            (M >= 4096 && dense_bytes >= min_bytes / 2);
 }
 
+constexpr int kSddmmMaxD = 1024;    // longest dot product the tiled SDDMM kernel takes, 128 floats per launch
 bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
     const int mode = env_int("CSRK_KTILE", 1);
     if (mode == 3 || D % 4 != 0 || D > 128 || D < 4) return false;
@@ -480,7 +481,8 @@ bool sddmm_tile_shape_ok(const DeviceState &d, int M, int K, int D) {
 
 template <int DMAX, int ROWS>
 csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
-                               const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
+                               const int32_t *ci, const float *v, const float *A, const float *B, float *P, int ld,
+                               int col0, int accumulate) {
     using L = SddmmTileLds<DMAX, ROWS>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     auto kern = sddmm_ktile_kernel<DMAX, ROWS>;
@@ -492,15 +494,19 @@ csrk_status launch_sddmm_ktile(DeviceState &d, hipStream_t st, int M, int K, int
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, rp, ci, v, A, B, P,
-                       tile_flags(d), d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb), dim3(kTileThreads), L::kBytes, st, M, K, D, ld, accumulate, rp,
+                       ci, v, A + col0, B + col0, P, tile_flags(d), d.inline_density, other_flags(d));
     CSRK_HIP(hipGetLastError());
     return CSRK_OK;
 }
 
 template <int DMAX>
 csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, const int32_t *rp,
-                                    const int32_t *ci, const float *v, const float *A, const float *B, float *P) {
+                                    const int32_t *ci, const float *v, const float *A, const float *B, float *P,
+                                    int ld = 0, int col0 = 0, int accumulate = 0) {
+    // ld != 0: columns [col0, col0 + D) of rows of A and B that are `ld` floats long, one piece of a longer dot
+    // product; accumulate: add this piece to what P holds
+    if (ld == 0) ld = D;
     // (cutting K into ranges for small M, as SPMM and FusedMM do, measured no gain here: the tile is 288-1152
     // rows high, so a K of a few thousand leaves too few tiles per range)
     // rows per wavefront by the same rule as SPMM / FusedMM (the 128-wide kernel takes at most two: its score loop
@@ -508,13 +514,13 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     constexpr int kMaxRows = DMAX <= 64 ? 4 : 2;
     switch (tile_rows_for(d, M, kMaxRows, true)) {
         case 4:
-            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P);
+            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 4>(d, st, M, K, D, rp, ci, v, A, B, P, ld, col0, accumulate);
             [[fallthrough]];
         case 3:
-            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 3>(d, st, M, K, D, rp, ci, v, A, B, P);
+            if constexpr (kMaxRows >= 4) return launch_sddmm_ktile<DMAX, 3>(d, st, M, K, D, rp, ci, v, A, B, P, ld, col0, accumulate);
             [[fallthrough]];
-        case 2: return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P);
-        default: return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P);
+        case 2: return launch_sddmm_ktile<DMAX, 2>(d, st, M, K, D, rp, ci, v, A, B, P, ld, col0, accumulate);
+        default: return launch_sddmm_ktile<DMAX, 1>(d, st, M, K, D, rp, ci, v, A, B, P, ld, col0, accumulate);
     }
 }
 
@@ -1077,6 +1083,20 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const
                             : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                                       : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
             if (s) return s;
+        }
+    } else if (vec4 && D > 128 && D <= kSddmmMaxD && P != vals && sddmm_tile_shape_ok(*d, M, K, 128)) {
+        // Dot products longer than the 128 floats a row of the tile holds: 128 floats at a time, one launch of the
+        // tiled kernel per piece, the second and later pieces adding to P (each reads vals again, so not when P
+        // aliases vals).  16384^2 / 20 %, D = 256: 5.6 ms in the general kernel, whose gathers outgrow L2.
+        if (csrk_status s = ensure_scratch(*d, 1)) return s;
+        bool go = false;
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, sddmm_min_density(M, K, 128), &go)) return s;
+        if (go) {
+            gate = tile_flags(*d);
+            for (int c0 = 0; c0 < D; c0 += 128)
+                if (csrk_status s = launch_sddmm_ktile_rows<128>(*d, stream, M, K, D - c0 < 128 ? D - c0 : 128, rowptr, colidx,
+                                                                 vals, A, B, P, D, c0, c0 > 0))
+                    return s;
         }
     }
     if (plan && gate) {     // the plan vouches for the pattern: the tiled kernel has done the call

@@ -484,9 +484,11 @@ struct SddmmTileLds {
 
 template <int DMAX, int ROWS>
 __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
-    int M, int K, int D, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx, const float *vals,
-    const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags, float inline_density,
-    int32_t *other_flags) {
+    int M, int K, int D, int ld, int accumulate, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const float *vals, const float *__restrict__ A, const float *__restrict__ Bmat, float *P, int32_t *flags,
+    float inline_density, int32_t *other_flags) {
+    // D: the piece of the dot product this launch computes, out of rows of A and B that are `ld` floats long (the
+    // caller offsets A and B to the piece's first column); accumulate != 0: add to what P holds (a later piece)
     using L = SddmmTileLds<DMAX, ROWS>;
     constexpr int KT = L::kKT;
     constexpr int C = L::kPieces;
@@ -501,6 +503,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const int wave = uniform(threadIdx.x >> 6);
     const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
     const int d4n = D >> 2;                 // float4s per row of A / B
+    const int ld4 = ld >> 2;                // float4s from one row of A / B to the next
     float *arows = lds + L::kTileFloats + wave * (ROWS * DMAX);   // this wavefront's rows of A
 
     // which way row_ror turns is measured, not assumed: `turn` is +1 or -1 (mod 16)
@@ -533,7 +536,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
         // the row of A into LDS, zero beyond D (piece `lane` of each row; read back per tile, 16 bytes per lane)
         if (lane < C) {
             float piece[4] = {0.f, 0.f, 0.f, 0.f};
-            if (row < M && lane < d4n) load_vec<4>(A + (size_t)row * D + lane * 4, piece);
+            if (row < M && lane < d4n) load_vec<4>(A + (size_t)row * ld + lane * 4, piece);
             store_vec<4>(arows + r * DMAX + lane * 4, piece);
         }
     }
@@ -549,19 +552,19 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     // the compiler can count outstanding loads exactly and waits for a look-ahead chunk do not also
     // wait for the tile behind it.  Threads of the padding columns (D < DMAX) re-read the row's last
     // piece and write zeros; rows past K in the last tile re-read row K-1 and are never used.
-    const size_t my_off = (size_t)my_kk * d4n + (my_col ? my_c : d4n - 1);
-    const size_t step_off = (size_t)kRound * d4n;
+    const size_t my_off = (size_t)my_kk * ld4 + (my_col ? my_c : d4n - 1);
+    const size_t step_off = (size_t)kRound * ld4;
     auto issue = [&](int k0) {
         const float4 *src = reinterpret_cast<const float4 *>(Bmat);
         if (k0 + KT <= K) {
-            const float4 *tile = src + (size_t)k0 * d4n;   // uniform
+            const float4 *tile = src + (size_t)k0 * ld4;   // uniform
 #pragma unroll
             for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
         } else {                                           // last, partial tile: clamp the row
 #pragma unroll
             for (int i = 0; i < kPer; ++i) {
                 const int k = k0 + i * kRound + my_kk;
-                stage[i] = src[(size_t)(k < K ? k : K - 1) * d4n + (my_col ? my_c : d4n - 1)];
+                stage[i] = src[(size_t)(k < K ? k : K - 1) * ld4 + (my_col ? my_c : d4n - 1)];
             }
         }
     };
@@ -615,7 +618,10 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
                         for (int c = 0; c < 4; ++c) fma_row_rotated<q / H>(dot, a[q % H][c], b[g & 1][u][c]);
                     });
                 });
-                if (in) P[j] = (has_vals ? vcur : 1.f) * dot;
+                if (in) {
+                    const float scaled = (has_vals ? vcur : 1.f) * dot;
+                    P[j] = accumulate ? P[j] + scaled : scaled;
+                }
                 pos[r] += cnt;
             };
             // the look-ahead registers hold what was loaded from clamped positions: mask the lanes past the row's end

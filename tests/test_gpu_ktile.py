@@ -397,3 +397,38 @@ def test_wide_outputs_with_automatic_kernel_choice(csrk, monkeypatch):
     A2 = rng.normal(size=(M, 128)).astype(np.float32)
     B2 = rng.normal(size=(K, 128)).astype(np.float32)
     run_fused(csrk, M, K, 128, 512, rp, ci, v, A2, B2, np.ascontiguousarray(C[:, :512]), rows=rows)
+
+
+# dot products longer than the 128 floats one launch of the tiled SDDMM kernel takes: pieces of 128, the later ones
+# added to P (132 -> 128 + 4; 300 -> 128 + 128 + 44); in place the general kernels run (every piece needs vals)
+@pytest.mark.parametrize("M,K,D", [(64, 64, 132), (333, 417, 256), (1000, 1300, 300), (65, 3000, 512), (2100, 300, 1024)])
+@pytest.mark.parametrize("p", [0.05, 0.4])
+def test_sddmm_long_dot_products_go_in_pieces(csrk, M, K, D, p):
+    rng = np.random.default_rng(M + K + D)
+    rp, ci = inputs.bernoulli_csr(D, M, K, p)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_sddmm(csrk, M, K, D, rp, ci, None, A, B)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
+    plan = csrk.csrk_plan_create(M, K, dev(rp), dev(ci))
+    got = csrk.sddmm_csr_plan(plan, D, dev(v), dev(A), dev(B))
+    assert torch.equal(got, csrk.sddmm_csr(M, K, D, dev(rp), dev(ci), dev(v), dev(A), dev(B)))
+    csrk.csrk_plan_destroy(plan)
+    r = M // 2
+    ci2, v2 = ci.copy(), v.copy()
+    ci2[rp[r]:rp[r + 1]] = ci2[rp[r]:rp[r + 1]][::-1]
+    v2[rp[r]:rp[r + 1]] = v2[rp[r]:rp[r + 1]][::-1]
+    run_sddmm(csrk, M, K, D, rp, ci2, v2, A, B)
+
+
+def test_sddmm_long_dot_products_with_automatic_kernel_choice(csrk, monkeypatch):
+    monkeypatch.setenv("CSRK_KTILE", "1")
+    M, K, D = 8192, 4096, 256
+    rng = np.random.default_rng(9)
+    rp, ci = inputs.bernoulli_csr(4, M, K, 0.2)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, rows=np.arange(0, M, 16, dtype=np.int32))
