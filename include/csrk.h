@@ -76,7 +76,10 @@ csrk_status spmm_csr(int M, int K, int N,
  *   P[j] = vals[j] * <A[i, :], B[colidx[j], :]>   for every stored entry j of row i
  * A is M x D, B is K x D (used as B^T), P has nnz entries in the order of
  * colidx.  vals == NULL means an all-ones pattern, which is the paper's I_A.
- * P may alias vals.
+ * P may alias vals (P == vals: the values are overwritten in place, as in the
+ * paper's Algorithm 1); such a call keeps to the kernels that need no second
+ * pass over vals - the LDS-tiled kernel only through sddmm_csr_plan, whose plan
+ * vouches for the column order.  Partly overlapping P and vals are not allowed.
  */
 csrk_status sddmm_csr(int M, int K, int D,
                       const int32_t *rowptr, const int32_t *colidx, const float *vals,

@@ -1072,7 +1072,10 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const
         CSRK_HIP(hipGetLastError());
         return CSRK_OK;
     }
-    if (small_tiled || (vec4 && sddmm_tile_shape_ok(*d, M, K, D))) {
+    // In place (P aliases vals) a tiled kernel that meets unsorted columns has already overwritten values which the
+    // general kernel would need to redo the call: without a plan to vouch for the order, such calls skip the attempt.
+    const bool may_attempt = plan != nullptr || P != vals;
+    if (small_tiled || (vec4 && may_attempt && sddmm_tile_shape_ok(*d, M, K, D))) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
         bool go = small_tiled;
         if (!go)

@@ -432,3 +432,27 @@ def test_sddmm_long_dot_products_with_automatic_kernel_choice(csrk, monkeypatch)
     A = rng.normal(size=(M, D)).astype(np.float32)
     B = rng.normal(size=(K, D)).astype(np.float32)
     run_sddmm(csrk, M, K, D, rp, ci, v, A, B, rows=np.arange(0, M, 16, dtype=np.int32))
+
+
+def test_sddmm_in_place_on_unsorted_columns_where_the_tiled_kernel_would_be_tried(csrk):
+    # 9 M cells: beyond the whole-row kernels' range, so an attempt with the tiled kernel is in reach.  In place it
+    # would overwrite values that the general kernel needs when the columns turn out unsorted.
+    M, K, D = 3000, 3000, 64
+    rng = np.random.default_rng(1)
+    rp, ci = inputs.bernoulli_csr(3, M, K, 0.3)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    for r in (5, 500, M - 1):
+        ci[rp[r]:rp[r + 1]] = ci[rp[r]:rp[r + 1]][::-1]
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
+    # sorted again: in place through a plan (tiled kernel), and without one (general kernel)
+    rp, ci = inputs.bernoulli_csr(3, M, K, 0.3)
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
+    plan = csrk.csrk_plan_create(M, K, dev(rp), dev(ci))
+    d_v = dev(v)
+    got = csrk.sddmm_csr_plan(plan, D, d_v, dev(A), dev(B), P=d_v)
+    assert got.data_ptr() == d_v.data_ptr()
+    assert torch.equal(got, csrk.sddmm_csr(M, K, D, dev(rp), dev(ci), dev(v), dev(A), dev(B)))
+    csrk.csrk_plan_destroy(plan)
