@@ -65,3 +65,35 @@ def test_random_shapes_all_kernel_families(csrk, monkeypatch, seed):
                 run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
         except AssertionError as e:
             raise AssertionError(f"{what}: {e}") from e
+
+
+@pytest.mark.parametrize("seed", [301, 302])
+def test_random_wide_outputs_and_long_dot_products(csrk, monkeypatch, seed):
+    # widths beyond one launch of the tiled kernels (outputs over 512 columns, dot products over 128 floats and
+    # over 64 with a wide output), every kernel-family setting, SDDMM also in place
+    for c in range(12):
+        rng = np.random.default_rng(seed * 1000 + c)
+        env = {"CSRK_KTILE": ["2", "1", "2", "3"][c % 4], "CSRK_KSPLIT": ["1", "1", "2"][c % 3], "CSRK_ROWS": ["3", "1"][c % 2]}
+        M = int(rng.choice([65, 300, 1024, 2100]))
+        K = int(rng.choice([64, 700, 2048, 4100]))
+        N = int(rng.choice([260, 516, 640, 768, 1024, 1500, 2048]))
+        D = int(rng.choice([64, 72, 100, 128, 132, 256, 300]))
+        p = float(rng.choice([0.02, 0.1, 0.3, 1.0]))
+        if M * K * p > 1e6:
+            p = 1e6 / (M * K)
+        what = f"seed {seed} case {c}: {env} M={M} K={K} N={N} D={D} p={p:.3f}"
+        for name, value in env.items():
+            monkeypatch.setenv(name, value)
+        rp, ci = inputs.bernoulli_csr(c + 11, M, K, p)
+        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+        A = rng.normal(size=(M, D)).astype(np.float32)
+        B = rng.normal(size=(K, D)).astype(np.float32)
+        C = rng.normal(size=(K, N)).astype(np.float32)
+        try:
+            run_spmm(csrk, M, K, N, rp, ci, v, C)
+            run_fused(csrk, M, K, D, N, rp, ci, v, A, B, C)
+            if len(ci):
+                run_sddmm(csrk, M, K, D, rp, ci, v, A, B)
+                run_sddmm(csrk, M, K, D, rp, ci, v, A, B, inplace=True)
+        except AssertionError as e:
+            raise AssertionError(f"{what}: {e}") from e
