@@ -391,7 +391,7 @@ def test_wide_outputs_with_automatic_kernel_choice(csrk, monkeypatch):
     A = rng.normal(size=(M, 64)).astype(np.float32)
     B = rng.normal(size=(K, 64)).astype(np.float32)
     C = rng.uniform(-1, 1, (K, N)).astype(np.float32)
-    rows = np.arange(0, M, 8, dtype=np.int32)
+    rows = np.unique(np.concatenate([np.arange(0, M, 7), [M - 4, M - 3, M - 2, M - 1]])).astype(np.int32)   # a stride coprime to the 64 rows of a workgroup
     run_spmm(csrk, M, K, N, rp, ci, v, C, rows=rows)
     run_fused(csrk, M, K, 64, N, rp, ci, v, A, B, C, rows=rows)
     A2 = rng.normal(size=(M, 128)).astype(np.float32)
@@ -431,7 +431,7 @@ def test_sddmm_long_dot_products_with_automatic_kernel_choice(csrk, monkeypatch)
     v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
     A = rng.normal(size=(M, D)).astype(np.float32)
     B = rng.normal(size=(K, D)).astype(np.float32)
-    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, rows=np.arange(0, M, 16, dtype=np.int32))
+    run_sddmm(csrk, M, K, D, rp, ci, v, A, B, rows=np.unique(np.concatenate([np.arange(0, M, 13), [M - 4, M - 3, M - 2, M - 1]])).astype(np.int32))
 
 
 def test_sddmm_in_place_on_unsorted_columns_where_the_tiled_kernel_would_be_tried(csrk):

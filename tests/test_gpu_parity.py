@@ -254,16 +254,26 @@ def test_workload_fused8k_skew_full(csrk):
     run_fused(csrk, w.M, w.K, 64, 64, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"])
 
 
-def test_workload_large16k_sampled_rows(csrk):
-    # full size, in the launch configuration the benchmark times; the oracle checks every
-    # 16th row plus the first and last rows (each output row is computed independently)
+def test_workload_large16k_every_row(csrk):
+    # full size, in the launch configuration the benchmark times, every output row and every stored entry
+    # against the oracle: this is the only size at which the un-split 4-rows-per-wavefront tiled kernels run,
+    # and every wavefront and row slot of their layout must be looked at
     w = inputs.workload("large16k")
-    rows = np.unique(np.concatenate([np.arange(0, w.M, 16), [1, 2, w.M - 2, w.M - 1]])).astype(np.int32)
-    run_spmm(csrk, w.M, w.K, 512, w.rowptr, w.colidx, w.vals, w.ops["spmm"]["B"], rows=rows)
+    run_spmm(csrk, w.M, w.K, 512, w.rowptr, w.colidx, w.vals, w.ops["spmm"]["B"])
     f = w.ops["fusedmm"]
-    run_fused(csrk, w.M, w.K, 64, 512, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
+    run_fused(csrk, w.M, w.K, 64, 512, w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"])
     s = w.ops["sddmm"]
-    run_sddmm(csrk, w.M, w.K, 64, w.rowptr, w.colidx, w.vals, s["A"], s["B"], rows=rows)
+    run_sddmm(csrk, w.M, w.K, 64, w.rowptr, w.colidx, w.vals, s["A"], s["B"])
+
+
+def test_sddmm_with_128_float_rows_at_the_benchmark_size(csrk):
+    # SDDMM alone at 16384 x 16384 / 20 % with the longer of the two dot lengths of the workloads (D = 128),
+    # every stored entry compared
+    w = inputs.workload("large16k")
+    A = inputs.normal(0, inputs.STREAM_A, (w.M, 128))
+    B = inputs.normal(0, inputs.STREAM_B, (w.K, 128))
+    run_sddmm(csrk, w.M, w.K, 128, w.rowptr, w.colidx, w.vals, A, B)
+    run_sddmm(csrk, w.M, w.K, 128, w.rowptr, w.colidx, None, A, B)
 
 
 # ------------------------------------------------------------------ call-site variations
@@ -351,7 +361,7 @@ def test_automatic_kernel_choice_mid_sizes(csrk, shape):
     # a sample of rows checked (rows are independent)
     M, K, p, N, D = shape
     w = inputs.custom_workload(M, K, p, N, D, seed=3)
-    rows = np.unique(np.concatenate([np.arange(0, M, 37), [0, 1, M - 2, M - 1]])).astype(np.int32)
+    rows = np.unique(np.concatenate([np.arange(0, M, 37), [0, 1, 2, 3, M - 4, M - 3, M - 2, M - 1]])).astype(np.int32)
     f = w.ops["fusedmm"]
     run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
     run_sddmm(csrk, M, K, D, w.rowptr, w.colidx, w.vals, f["A"], f["B"], rows=rows)
@@ -368,7 +378,7 @@ def test_whole_rows_paths_for_even_matrices(csrk, shape):
     arithmetic per row (Algorithms 2 and 3), so the same bar."""
     M, K, p, N, D = shape
     w = inputs.custom_workload(M, K, p, N, D, seed=11)
-    rows = np.unique(np.concatenate([np.arange(0, M, 29), [0, 1, M - 2, M - 1]])).astype(np.int32)
+    rows = np.unique(np.concatenate([np.arange(0, M, 29), [0, 1, 2, 3, M - 4, M - 3, M - 2, M - 1]])).astype(np.int32)
     f = w.ops["fusedmm"]
     run_spmm(csrk, M, K, N, w.rowptr, w.colidx, w.vals, f["C"], rows=rows)
     run_sddmm(csrk, M, K, D, w.rowptr, w.colidx, w.vals, f["A"], f["B"], rows=rows)

@@ -130,14 +130,15 @@ def test_planned_calls_with_very_many_short_rows(csrk):
     pl.close()
 
 
-def test_planned_calls_at_the_benchmark_size_on_sampled_rows(csrk):
-    # the 16384 x 16384 workload the benchmark times, planned: every 16th output row and the first and last rows
+def test_planned_calls_at_the_benchmark_size_every_row(csrk):
+    # the 16384 x 16384 workload the benchmark times, planned: every output row and every stored entry
     w = inputs.workload("large16k")
-    rows = np.unique(np.concatenate([np.arange(5, w.M, 16), [0, 1, w.M - 2, w.M - 1]])).astype(np.int32)
     pl = Planned(csrk, w.M, w.K, w.rowptr, w.colidx)
     assert csrk.csrk_plan_info(pl.plan) == (len(w.colidx), True, True)
     f = w.ops["fusedmm"]
-    pl.sampled(rows, 64, 512, w.vals, f["A"], f["B"], f["C"], w.ops["spmm"]["B"])
+    pl.spmm(512, w.vals, w.ops["spmm"]["B"])
+    pl.fused(64, 512, w.vals, f["A"], f["B"], f["C"])
+    pl.sddmm(64, w.vals, f["A"], f["B"])
     pl.close()
 
 
