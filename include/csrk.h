@@ -30,14 +30,26 @@
  *    D == 0 or nnz == 0 are valid: with D == 0 every dot product is empty (0).
  *  - O must not overlap any input.  P may be the same array as vals (the
  *    paper's SDDMM overwrites the values of the sparse matrix in place).
- *  - SPMM and FusedMM use a per-device scratch area owned by the library for
- *    partial rows (8192 x N floats on an MI355X) or, when M is small and the
- *    reduction dimension is cut into up to 8 ranges, for partial outputs (at most
- *    8 x M x N floats); it is allocated (hipMalloc, which synchronises) the first
- *    time it is needed or has to grow, and kept until csrk_release_workspace or
- *    process exit.  Two calls in flight at once on different streams of one device
- *    would share it and race: serialise such calls on one stream.  Results do not
- *    depend on timing: partial rows and partial outputs are added in a fixed order.
+ *  - Scratch.  SPMM and FusedMM need device memory beyond their operands for partial
+ *    rows (8192 x N floats on an MI355X) or, when M is small and the reduction
+ *    dimension is cut into up to 8 ranges, for partial outputs (at most 8 x M x N
+ *    floats), plus a few flag words; SDDMM needs the flag words only.  Three ways to
+ *    provide it:
+ *      * spmm_csr / sddmm_csr / fusedmm_csr (and their planned and bfloat16 forms) use
+ *        an area the library keeps per device.  It is allocated (hipMalloc, which
+ *        synchronises) the first time it is needed, replaced when it has to grow (after
+ *        a hipDeviceSynchronize), and kept until csrk_release_workspace or process exit.
+ *        These calls take a process-wide lock for their duration and share the area:
+ *        two of them in flight at once on different streams of one device would race
+ *        on it, so serialise them on one stream.  This is the convenience path.
+ *      * *_csr_ws take a workspace from the caller (csrk_workspace_bytes gives the
+ *        size).  They allocate nothing, free nothing, never synchronise, take no lock
+ *        and keep no state between calls: calls on different streams with different
+ *        workspaces are independent, and every call can be captured in a HIP graph.
+ *      * csrk_plan_reserve gives a plan a workspace of its own; planned calls that fit
+ *        into it then behave like the *_csr_ws calls.
+ *    Results do not depend on timing: partial rows and partial outputs are added in a
+ *    fixed order.
  *  - Return value: CSRK_OK or an error code; csrk_last_error() then gives a
  *    message for the calling thread.  On error nothing has been enqueued.
  *  - Any N >= 1 and D >= 1 work.  Widths that are multiples of 4 with 16-byte
@@ -46,6 +58,7 @@
 #ifndef CSRK_H
 #define CSRK_H
 
+#include <stddef.h>
 #include <stdint.h>
 #include <hip/hip_runtime_api.h>
 
@@ -120,6 +133,39 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
                              float *O, hipStream_t stream);
 
 /*
+ * The three operations on a workspace of the caller's (paper section "Overview of the
+ * Algorithms": the same row algorithms; only where the kernels' scratch lives differs).
+ *
+ * csrk_workspace_bytes: host-only; *bytes receives the size that any call of the given
+ * operation (CSRK_OP_*) and shape may need on the current device, whichever kernels it
+ * takes (N is the output width, ignored for SDDMM; D is accepted for symmetry and does
+ * not matter).  `workspace` is a DEVICE pointer to at least that many bytes, aligned to
+ * 256 bytes (what hipMalloc returns), owned by the caller; its contents on entry do not
+ * matter and are unspecified afterwards.  A call whose workspace is too small returns
+ * CSRK_WORKSPACE, and the message names the size it needs; nothing has been enqueued then.
+ * The call neither allocates nor frees nor synchronises, so it may be made while
+ * `stream` is being captured into a HIP graph.  The workspace is in use until `stream`
+ * has passed the enqueued work: two calls in flight at once need two workspaces.
+ * All other arguments and the results are those of spmm_csr / sddmm_csr / fusedmm_csr.
+ */
+#define CSRK_OP_SPMM     1
+#define CSRK_OP_SDDMM    2
+#define CSRK_OP_FUSEDMM  3
+csrk_status csrk_workspace_bytes(int op, int M, int K, int N, int D, size_t *bytes);
+csrk_status spmm_csr_ws(int M, int K, int N,
+                        const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *B, float *O,
+                        void *workspace, size_t workspace_bytes, hipStream_t stream);
+csrk_status sddmm_csr_ws(int M, int K, int D,
+                         const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                         const float *A, const float *B, float *P,
+                         void *workspace, size_t workspace_bytes, hipStream_t stream);
+csrk_status fusedmm_csr_ws(int M, int K, int D, int N,
+                           const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                           const float *A, const float *B, const float *C, float *O,
+                           void *workspace, size_t workspace_bytes, hipStream_t stream);
+
+/*
  * Plans: the sparsity pattern analysed once, for callers that use one pattern many
  * times (training loops; the paper's row analysis - nnzr, NT, nchunks of sections
  * "SDDMM" and "SPMM" - depends on the pattern alone).  The calls above look at the
@@ -137,7 +183,8 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
  * UNCHANGED for as long as the plan is used; a planned call on a pattern changed
  * since has undefined results.  *out (host pointer) receives the plan, owned by the
  * caller until csrk_plan_destroy (NULL is accepted there).  A plan belongs to the
- * device that was current when it was made; it holds 32 bytes of device memory.
+ * device that was current when it was made; it holds 32 bytes of device memory (plus the
+ * workspace that csrk_plan_reserve may add).
  * csrk_plan_info reports what was found (any of the three host pointers may be
  * NULL).  The planned calls take the pattern and M, K from the plan; all other
  * arguments are as in spmm_csr / sddmm_csr / fusedmm_csr.
@@ -145,6 +192,16 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N,
 typedef struct csrk_plan_s csrk_plan;
 csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t *colidx,
                              hipStream_t stream, csrk_plan **out);
+/*
+ * Gives the plan a workspace of its own, large enough for spmm_csr_plan and fusedmm_csr_plan
+ * with outputs of up to max_N columns (and for sddmm_csr_plan): allocates it here
+ * (hipMalloc; if the plan already had a smaller one, the device is synchronised and that one
+ * freed), freed by csrk_plan_destroy.  Planned calls that fit into it use it instead of the
+ * library's per-device area and then allocate nothing, never synchronise, take no lock and
+ * may be captured in a HIP graph; calls that do not fit fall back to the per-device area.
+ * Two calls on the same plan in flight at once on different streams would race on it.
+ */
+csrk_status csrk_plan_reserve(csrk_plan *plan, int max_N);
 csrk_status csrk_plan_destroy(csrk_plan *plan);
 csrk_status csrk_plan_info(const csrk_plan *plan, long long *nnz, int *sorted, int *even);
 csrk_status spmm_csr_plan(const csrk_plan *plan, int N, const float *vals,
@@ -183,7 +240,31 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
 csrk_status csrk_profile_enable(int max_records);
 csrk_status csrk_profile_collect(float *ms, int *kinds, int capacity, int *count);
 
-/* Frees the calling device's scratch area (synchronises the device). */
+/*
+ * Measuring aids (not part of the paper's method; they serve its section "Performance Analysis": where the time of a
+ * kernel goes).
+ *
+ * csrk_tile_phases runs a MEASURING BUILD of the 512-column LDS-tiled SPMM (op = CSRK_OP_SPMM: O = S.C, A and B
+ * ignored) or FusedMM (CSRK_OP_FUSEDMM, D = 64) kernel once - the same code with a cycle counter read at every change
+ * of phase - and returns, in cycles[0..7] (host array of 8 doubles), the mean number of shader-clock cycles a wavefront
+ * spent in each phase over the whole call: [0] waiting at the barrier that ends a tile, [1] copying the next tile from
+ * registers to LDS, [2] waiting at the barrier behind that copy, [3] issuing the loads of a tile, [4] the accumulate
+ * stage (LDS reads and multiply-adds), [5] issuing the loads of the rows' next entries, [6] FusedMM's score stage,
+ * [7] unused; *tiles receives the number of tiles per wavefront.  Needs N = 512, M a multiple of 64, ascending
+ * columns; O is overwritten with the result.  Allocates and frees scratch of its own and SYNCHRONISES `stream`.  The
+ * counter reads perturb what they measure by a few per cent.
+ *
+ * csrk_debug_row_rotation writes, for S = 0 .. 15 and every lane l of one wavefront, into out[S * 64 + l] (device,
+ * 1024 floats) the number of the lane whose operand the row rotation by S of the kernels' rotated multiply-add hands
+ * to lane l: the tiled SDDMM and FusedMM kernels are written for (l & ~15) | ((l - S) & 15).
+ */
+csrk_status csrk_tile_phases(int op, int M, int K, int D, int N,
+                             const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                             const float *A, const float *B, const float *C, float *O,
+                             hipStream_t stream, double *cycles, int *tiles);
+csrk_status csrk_debug_row_rotation(float *out, hipStream_t stream);
+
+/* Frees the current device's scratch area of the plain entry points (synchronises the device). */
 csrk_status csrk_release_workspace(void);
 
 /* Message of the last error on the calling thread ("" if none). Host string owned by the library. */

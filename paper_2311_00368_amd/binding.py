@@ -54,6 +54,15 @@ def load(build_if_missing: bool = True):
     lib.spmm_csr_plan.argtypes = [p, i, p, p, p, p]
     lib.sddmm_csr_plan.argtypes = [p, i, p, p, p, p, p]
     lib.fusedmm_csr_plan.argtypes = [p, i, i, p, p, p, p, p, p]
+    sz = ctypes.c_size_t
+    lib.csrk_workspace_bytes.argtypes = [i, i, i, i, i, ctypes.POINTER(sz)]
+    lib.spmm_csr_ws.argtypes = [i, i, i, p, p, p, p, p, p, sz, p]
+    lib.sddmm_csr_ws.argtypes = [i, i, i, p, p, p, p, p, p, p, sz, p]
+    lib.fusedmm_csr_ws.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p, sz, p]
+    lib.csrk_plan_reserve.argtypes = [p, i]
+    lib.csrk_tile_phases.argtypes = [i, i, i, i, i, p, p, p, p, p, p, p, p, ctypes.POINTER(ctypes.c_double),
+                                     ctypes.POINTER(ctypes.c_int)]
+    lib.csrk_debug_row_rotation.argtypes = [p, p]
     lib.csrk_release_workspace.argtypes = []
     lib.csrk_profile_enable.argtypes = [i]
     lib.csrk_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i,
@@ -61,7 +70,9 @@ def load(build_if_missing: bool = True):
     for f in (lib.spmm_csr, lib.sddmm_csr, lib.fusedmm_csr, lib.spmm_csr_bf16, lib.sddmm_csr_bf16, lib.fusedmm_csr_bf16,
               lib.csrk_validate_csr, lib.csrk_release_workspace, lib.csrk_plan_create, lib.csrk_plan_destroy,
               lib.csrk_plan_info, lib.spmm_csr_plan, lib.sddmm_csr_plan, lib.fusedmm_csr_plan,
-              lib.csrk_profile_enable, lib.csrk_profile_collect):
+              lib.csrk_profile_enable, lib.csrk_profile_collect, lib.csrk_workspace_bytes, lib.spmm_csr_ws,
+              lib.sddmm_csr_ws, lib.fusedmm_csr_ws, lib.csrk_plan_reserve, lib.csrk_tile_phases,
+              lib.csrk_debug_row_rotation):
         f.restype = ctypes.c_int
     lib.csrk_last_error.restype = ctypes.c_char_p
     lib.csrk_version.restype = ctypes.c_char_p
@@ -153,6 +164,66 @@ def fusedmm_csr(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O
     return O
 
 
+CSRK_OP_SPMM, CSRK_OP_SDDMM, CSRK_OP_FUSEDMM = 1, 2, 3
+
+
+def csrk_workspace_bytes(op: int, M: int, K: int, N: int, D: int = 0) -> int:
+    """Bytes of workspace that a *_csr_ws call of this operation (CSRK_OP_*) and shape may need on the current device."""
+    out = ctypes.c_size_t(0)
+    _check(load().csrk_workspace_bytes(op, M, K, N, D, ctypes.byref(out)))
+    return int(out.value)
+
+
+def _ws_ptr(workspace: torch.Tensor, dev):
+    if not isinstance(workspace, torch.Tensor) or not workspace.is_cuda or workspace.device != dev:
+        raise TypeError("workspace must be a CUDA tensor on the operands' device")
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
+    return ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size())
+
+
+def spmm_csr_ws(M: int, K: int, N: int, rowptr, colidx, vals, B, workspace, O=None) -> torch.Tensor:
+    """spmm_csr on the caller's workspace (a CUDA tensor of at least csrk_workspace_bytes(...) bytes)."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws, ws_bytes = _ws_ptr(workspace, dev)
+    with torch.cuda.device(dev):
+        _check(lib.spmm_csr_ws(M, K, N, rp, ci, va, _dev_ptr(B, "B", torch.float32, (K, N), dev),
+                               _dev_ptr(O, "O", torch.float32, (M, N), dev), ws, ws_bytes, _stream(dev)))
+    return O
+
+
+def sddmm_csr_ws(M: int, K: int, D: int, rowptr, colidx, vals, A, B, workspace, P=None) -> torch.Tensor:
+    """sddmm_csr on the caller's workspace."""
+    lib = load()
+    dev, nnz, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if P is None:
+        P = torch.empty((nnz,), dtype=torch.float32, device=dev)
+    ws, ws_bytes = _ws_ptr(workspace, dev)
+    with torch.cuda.device(dev):
+        _check(lib.sddmm_csr_ws(M, K, D, rp, ci, va, _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                                _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                                _dev_ptr(P, "P", torch.float32, (nnz,), dev), ws, ws_bytes, _stream(dev)))
+    return P
+
+
+def fusedmm_csr_ws(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, workspace, O=None) -> torch.Tensor:
+    """fusedmm_csr on the caller's workspace."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    ws, ws_bytes = _ws_ptr(workspace, dev)
+    with torch.cuda.device(dev):
+        _check(lib.fusedmm_csr_ws(M, K, D, N, rp, ci, va, _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                                  _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                                  _dev_ptr(C, "C", torch.float32, (K, N), dev),
+                                  _dev_ptr(O, "O", torch.float32, (M, N), dev), ws, ws_bytes, _stream(dev)))
+    return O
+
+
 def spmm_csr_bf16(M: int, K: int, N: int, rowptr, colidx, vals, B, O=None) -> torch.Tensor:
     """spmm_csr with B stored as bfloat16 (torch.bfloat16, K x N); O and vals are FP32."""
     lib = load()
@@ -229,6 +300,41 @@ def csrk_plan_destroy(plan: Plan) -> None:
         handle, plan.handle = plan.handle, None
         with torch.cuda.device(plan.device):
             _check(load().csrk_plan_destroy(handle))
+
+
+PHASE_NAMES = ("barrier ending a tile", "tile copy to LDS", "barrier behind the copy", "tile loads issued",
+               "accumulate stage", "next entries' loads issued", "score stage", "unused")
+
+
+def csrk_tile_phases(op: int, M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O=None):
+    """Mean cycles per wavefront and phase of the measuring build of the 512-column tiled SPMM / FusedMM kernel
+    (see include/csrk.h).  Returns (cycles: list of 8 floats, tiles per wavefront, O)."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    if O is None:
+        O = torch.empty((M, N), dtype=torch.float32, device=dev)
+    cycles = (ctypes.c_double * 8)()
+    tiles = ctypes.c_int(0)
+    with torch.cuda.device(dev):
+        _check(lib.csrk_tile_phases(op, M, K, D, N, rp, ci, va,
+                                    _dev_ptr(A, "A", torch.float32, (M, D), dev) if A is not None else None,
+                                    _dev_ptr(B, "B", torch.float32, (K, D), dev) if B is not None else None,
+                                    _dev_ptr(C, "C", torch.float32, (K, N), dev),
+                                    _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev), cycles, ctypes.byref(tiles)))
+    return list(cycles), int(tiles.value), O
+
+
+def csrk_debug_row_rotation() -> torch.Tensor:
+    """16 x 64 table: which lane's operand the rotated multiply-add hands to each lane (see include/csrk.h)."""
+    out = torch.empty((16, 64), dtype=torch.float32, device="cuda")
+    _check(load().csrk_debug_row_rotation(ctypes.c_void_p(out.data_ptr()), _stream(out.device)))
+    return out
+
+
+def csrk_plan_reserve(plan: Plan, max_N: int) -> None:
+    """Give the plan a workspace of its own for outputs of up to max_N columns (allocates; see include/csrk.h)."""
+    with torch.cuda.device(plan.device):
+        _check(load().csrk_plan_reserve(plan.handle, max_N))
 
 
 def csrk_plan_info(plan: Plan):

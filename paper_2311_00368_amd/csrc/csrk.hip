@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -26,6 +27,8 @@ struct csrk_plan_s {
     bool sorted;              // columns non-decreasing inside every row
     bool even;                // longest row <= 2 * mean + 64 (what the per-call row analysis asks)
     int32_t *dflags;          // 8 device words laid out like the per-call flags: {0, 1, 0, even, ...}
+    void *ws;                 // scratch owned by the plan (csrk_plan_reserve), or NULL
+    size_t ws_bytes;
 };
 
 namespace {
@@ -52,28 +55,49 @@ csrk_status fail(csrk_status code, const char *fmt, ...) {
 constexpr int kMaxDevices = 64;
 constexpr int kMaxKSplit = 8;
 
-struct DeviceState {
-    bool init = false;
+// What the library knows about a device: filled in once, read-only afterwards.
+struct DeviceInfo {
+    std::atomic<bool> init{false};
     int cus = 0;
     int workers = 0;        // wavefronts the equal-nonzero split is cut into
-    float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way
-    int32_t *head_row = nullptr;  // workers ints (+ a few flag words for csrk_validate_csr)
-    size_t head_floats = 0;
-    int pending_ksplit = 0; // > 1: the tiled kernel of the call in progress left that many partial outputs in `head`
-    int32_t *plan_flags = nullptr;  // flag words of the plan the call in progress runs under (instead of the per-call ones)
-    int flag_set = 0;       // which of the two sets of per-call flag words the next tiled attempt uses (see tile_go)
-    float inline_density = __builtin_nanf("");   // not NaN: the tiled kernel of the call in progress analyses the rows itself
-    bool attempted = false; // the call in progress has made an unplanned tiled attempt (its set of flag words is used up)
 };
 
-DeviceState g_dev[kMaxDevices];
+// The scratch area the library allocates by itself for the plain entry points (one per device, grown on demand,
+// kept until csrk_release_workspace).  Only touched under g_mu.
+struct LazyScratch {
+    float *head = nullptr;
+    int32_t *head_row = nullptr;
+    size_t head_floats = 0;
+    int flag_set = 0;       // which of the two sets of per-call flag words the next tiled attempt uses (see tile_go)
+};
+
+// Everything ONE call works with.  It lives on the calling thread's stack, so calls that bring their own scratch
+// (a caller's workspace, a plan's, the static array) share no state with each other and take no lock.  The plain
+// entry points fill it from the device's LazyScratch under g_mu and write the changes back when they return.
+struct DeviceState {
+    int cus = 0;
+    int workers = 0;
+    float *head = nullptr;  // workers x width floats: partial sums of rows entered mid-way (or partial outputs of a K-split call)
+    int32_t *head_row = nullptr;  // workers ints, 8 spare words, two sets of 8 flag words
+    size_t head_floats = 0;
+    bool fixed = false;     // scratch of a given size that this call may neither grow nor replace
+    LazyScratch *lazy = nullptr;    // where head / head_row / flag_set go back to (plain entry points)
+    int pending_ksplit = 0; // > 1: the tiled kernel of this call left that many partial outputs in `head`
+    int32_t *plan_flags = nullptr;  // flag words of the plan this call runs under (instead of the per-call ones)
+    int flag_set = 0;
+    float inline_density = __builtin_nanf("");   // not NaN: the tiled kernel of this call analyses the rows itself
+    bool attempted = false; // this call has made an unplanned tiled attempt (its set of flag words is used up)
+};
+
+DeviceInfo g_info[kMaxDevices];
+LazyScratch g_lazy[kMaxDevices];
 std::mutex g_mu;
 
 // optional per-call event pairs around the main kernels (csrk_profile_enable)
 struct Recorder {
     std::vector<hipEvent_t> start, stop;
     std::vector<int> kind;
-    int used = 0;
+    std::atomic<int> used{0};   // calls without a lock (own scratch) may record from several threads
 };
 Recorder g_rec;
 
@@ -85,10 +109,15 @@ struct CallRecord {
     hipStream_t st;
     CallRecord(int k, hipStream_t s) : kind(k), st(s) {}
     void begin() {
-        if (slot < 0 && g_rec.used < (int)g_rec.start.size()) {
-            slot = g_rec.used++;
-            g_rec.kind[slot] = kind;
-            (void)hipEventRecord(g_rec.start[slot], st);
+        if (slot < 0 && g_rec.used.load() < (int)g_rec.start.size()) {
+            const int mine = g_rec.used.fetch_add(1);
+            if (mine < (int)g_rec.start.size()) {
+                slot = mine;
+                g_rec.kind[slot] = kind;
+                (void)hipEventRecord(g_rec.start[slot], st);
+            } else {
+                g_rec.used.fetch_sub(1);
+            }
         }
     }
     void end() {
@@ -105,55 +134,124 @@ int env_int(const char *name, int dflt) {
     return v > 0 ? (int)v : dflt;
 }
 
-csrk_status device_state(DeviceState **out) {
+csrk_status device_info(const DeviceInfo **out, int *ordinal = nullptr) {
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return fail(CSRK_UNSUPPORTED, "device ordinal %d not supported", dev);
-    DeviceState &d = g_dev[dev];
-    if (!d.init) {
-        int cus = 0;
-        CSRK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        // 8 wavefronts per SIMD, 4 SIMDs per CU: every CU gets a full complement of shares
-        int workers = env_int("CSRK_WORKERS", cus * 32);
-        workers = (workers + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
-        d.workers = workers;
-        d.cus = cus;
-        d.init = true;
+    DeviceInfo &d = g_info[dev];
+    if (!d.init.load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (!d.init.load(std::memory_order_relaxed)) {
+            int cus = 0;
+            CSRK_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+            // 8 wavefronts per SIMD, 4 SIMDs per CU: every CU gets a full complement of shares
+            int workers = env_int("CSRK_WORKERS", cus * 32);
+            workers = (workers + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
+            d.workers = workers;
+            d.cus = cus;
+            d.init.store(true, std::memory_order_release);
+        }
     }
     *out = &d;
+    if (ordinal) *ordinal = dev;
+    return CSRK_OK;
+}
+
+// ints at the head of a scratch area: worker table, 8 spare words, two sets of 8 flag words; padded to 256 bytes
+size_t scratch_int_bytes(int workers) { return ((sizeof(int32_t) * ((size_t)workers + 8 + 2 * 8)) + 255) / 256 * 256; }
+
+// Where a call's scratch comes from.
+struct ScratchSource {
+    void *mem = nullptr;    // a caller's workspace, a plan's, or the static array; NULL: the device's lazily grown one
+    size_t bytes = 0;
+};
+
+// Holds g_mu for calls on the lazily grown scratch (they share it, and its flag words take turns between calls);
+// calls with scratch of their own take no lock.
+struct CallLock {
+    bool held = false;
+    void take() {
+        g_mu.lock();
+        held = true;
+    }
+    ~CallLock() {
+        if (held) g_mu.unlock();
+    }
+};
+
+// Fills the per-call state.  With a ScratchSource the area is cut into its int part and its float part here and no
+// allocation ever happens; `lock` is taken only for the lazily grown scratch.
+csrk_status begin_call(DeviceState &d, const ScratchSource &src, CallLock &lock) {
+    const DeviceInfo *info = nullptr;
+    int dev = 0;
+    if (csrk_status s = device_info(&info, &dev)) return s;
+    d.cus = info->cus;
+    d.workers = info->workers;
+    if (src.mem) {
+        if (reinterpret_cast<uintptr_t>(src.mem) & 255u)
+            return fail(CSRK_INVALID_ARG, "workspace must be 256-byte aligned");
+        const size_t ints = scratch_int_bytes(d.workers);
+        if (src.bytes < ints + 256)
+            return fail(CSRK_WORKSPACE, "workspace of %zu bytes is too small (at least %zu are needed)", src.bytes, ints + 256);
+        d.head_row = static_cast<int32_t *>(src.mem);
+        d.head = reinterpret_cast<float *>(static_cast<char *>(src.mem) + ints);
+        d.head_floats = (src.bytes - ints) / sizeof(float);
+        d.fixed = true;
+        return CSRK_OK;
+    }
+    lock.take();
+    LazyScratch &g = g_lazy[dev];
+    d.lazy = &g;
+    d.head = g.head;
+    d.head_row = g.head_row;
+    d.head_floats = g.head_floats;
+    d.flag_set = g.flag_set;
     return CSRK_OK;
 }
 
 // scratch for `width` columns of partial rows of the equal-nonzero split, or `min_floats` floats if that is
-// more (partial outputs of a K-split launch); grows, never shrinks
+// more (partial outputs of a K-split launch).  The lazily grown scratch grows (hipMalloc, and a device
+// synchronisation before the old area is freed), never shrinks; scratch that was handed in is only checked.
 csrk_status ensure_scratch(DeviceState &d, int width, size_t min_floats = 0) {
     size_t need = (size_t)d.workers * (size_t)width;
     if (min_floats > need) need = min_floats;
-    if (!d.head_row) {
-        const size_t bytes = sizeof(int32_t) * ((size_t)d.workers + 8 + 2 * 8);   // worker table, spare words, two sets of flags
-        if (hipMalloc((void **)&d.head_row, bytes) != hipSuccess) {
-            d.head_row = nullptr;
+    if (d.fixed) {
+        if (need > d.head_floats)
+            return fail(CSRK_WORKSPACE, "workspace too small: this call needs %zu bytes", scratch_int_bytes(d.workers) + need * sizeof(float));
+        return CSRK_OK;
+    }
+    LazyScratch &g = *d.lazy;
+    if (!g.head_row) {
+        const size_t bytes = scratch_int_bytes(d.workers);
+        if (hipMalloc((void **)&g.head_row, bytes) != hipSuccess) {
+            g.head_row = nullptr;
             return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", bytes);
         }
         // both sets start with a clear ordering flag; from then on each tiled attempt clears the other set's
-        if (hipMemset(d.head_row, 0, bytes) != hipSuccess) {
-            (void)hipFree(d.head_row);
-            d.head_row = nullptr;
+        if (hipMemset(g.head_row, 0, bytes) != hipSuccess) {
+            (void)hipFree(g.head_row);
+            g.head_row = nullptr;
             return fail(CSRK_HIP_ERROR, "cannot clear the flag words of the scratch area");
         }
+        g.flag_set = 0;
         d.flag_set = 0;
+        d.head_row = g.head_row;
     }
-    if (need > d.head_floats) {
-        if (d.head) {
+    if (need > g.head_floats) {
+        if (g.head) {
             CSRK_HIP(hipDeviceSynchronize());
-            CSRK_HIP(hipFree(d.head));
+            CSRK_HIP(hipFree(g.head));
+            g.head = nullptr;
+            g.head_floats = 0;
             d.head = nullptr;
             d.head_floats = 0;
         }
-        if (hipMalloc((void **)&d.head, need * sizeof(float)) != hipSuccess) {
-            d.head = nullptr;
+        if (hipMalloc((void **)&g.head, need * sizeof(float)) != hipSuccess) {
+            g.head = nullptr;
             return fail(CSRK_WORKSPACE, "cannot allocate %zu bytes of scratch", need * sizeof(float));
         }
+        g.head_floats = need;
+        d.head = g.head;
         d.head_floats = need;
     }
     return CSRK_OK;
@@ -383,8 +481,10 @@ constexpr double kWellFilled = 0.87;          // TileGrid::fill from which a gri
 constexpr float kNarrowMinDensity = 0.25f;    // FusedMM with outputs of 32 columns or fewer (measured cross-over with whole rows)
 
 int32_t *tile_flags(DeviceState &d) { return d.plan_flags ? d.plan_flags : d.head_row + d.workers + 8 + 8 * d.flag_set; }
-// the set of flag words the next unplanned tiled attempt will use (nothing to look after under a plan)
-int32_t *other_flags(DeviceState &d) { return d.plan_flags ? nullptr : d.head_row + d.workers + 8 + 8 * (1 - d.flag_set); }
+// the set of flag words the next unplanned tiled attempt will use (nothing to look after under a plan, nor with
+// scratch that was handed in: such calls keep no state from one call to the next and always analyse by a launch
+// of reset_flags_kernel, which clears the ordering flag of the set it fills)
+int32_t *other_flags(DeviceState &d) { return (d.plan_flags || d.fixed) ? nullptr : d.head_row + d.workers + 8 + 8 * (1 - d.flag_set); }
 
 // CSRK_KTILE=2 (tests) takes the tiled kernels wherever they can run, whatever the density and row lengths
 // (a negative threshold tells the analysis kernel so)
@@ -544,7 +644,7 @@ csrk_status tiled_attempt(DeviceState &d, const csrk_plan_s *plan, hipStream_t s
     if (!plan) {
         *go = true;
         d.attempted = true;
-        if (M <= kInlineAnalysisMaxRows) {      // the tiled kernel's workgroups read rowptr themselves (tile_go)
+        if (!d.fixed && M <= kInlineAnalysisMaxRows) {      // the tiled kernel's workgroups read rowptr themselves (tile_go)
             d.inline_density = min_density;
             return CSRK_OK;
         }
@@ -583,10 +683,8 @@ struct PlanScope {
         d.attempted = false;
     }
     ~PlanScope() {
-        d.plan_flags = nullptr;
-        d.inline_density = __builtin_nanf("");
-        if (d.attempted) d.flag_set ^= 1;      // the next attempt takes the set this one has cleared
-        d.attempted = false;
+        // the next attempt on the lazily grown scratch takes the set of flag words this one has cleared
+        if (d.lazy && d.attempted) d.lazy->flag_set = d.flag_set ^ 1;
     }
 };
 
@@ -676,7 +774,8 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
     }
     const int rb = kTileWaves * ROWS;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, ld, rp, ci, v,
-                       B + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
+                       B + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d),
+                       (long long *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -735,7 +834,8 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     }
     const int rb = kTileWaves * LIVE;
     hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, ld, rp, ci,
-                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
+                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d),
+                       (long long *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -930,15 +1030,17 @@ const char *csrk_last_error(void) { return g_err; }
 
 const char *csrk_version(void) { return "csrk 0.1 gfx950"; }
 
-static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const int32_t *rowptr,
-                            const int32_t *colidx, const float *vals, const float *B, float *O, hipStream_t stream) {
+static csrk_status spmm_run(const csrk_plan_s *plan, const ScratchSource &scratch, int M, int K, int N,
+                            const int32_t *rowptr, const int32_t *colidx, const float *vals, const float *B, float *O,
+                            hipStream_t stream) {
     if (csrk_status s = check_dims("spmm_csr", M, K, N, 0)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr: rowptr and O must not be NULL");
     if (K > 0 && !B) return fail(CSRK_INVALID_ARG, "spmm_csr: B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     PlanScope scope(*d, plan);
@@ -1038,16 +1140,17 @@ static csrk_status spmm_run(const csrk_plan_s *plan, int M, int K, int N, const 
     return CSRK_OK;
 }
 
-static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const int32_t *rowptr,
-                             const int32_t *colidx, const float *vals, const float *A, const float *B, float *P,
-                             hipStream_t stream) {
+static csrk_status sddmm_run(const csrk_plan_s *plan, const ScratchSource &scratch, int M, int K, int D,
+                             const int32_t *rowptr, const int32_t *colidx, const float *vals, const float *A,
+                             const float *B, float *P, hipStream_t stream) {
     if (csrk_status s = check_dims("sddmm_csr", M, K, D, 0)) return s;
     if (M == 0 || K == 0) return CSRK_OK;
     if (!rowptr) return fail(CSRK_INVALID_ARG, "sddmm_csr: rowptr must not be NULL");
     if (D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "sddmm_csr: A and B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     PlanScope scope(*d, plan);
     const bool vec4 = (D % 4 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const WidthCfg c = dot_width_cfg(D, vec4);
@@ -1124,17 +1227,18 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, int M, int K, int D, const
     return CSRK_OK;
 }
 
-static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int N, const int32_t *rowptr,
-                               const int32_t *colidx, const float *vals, const float *A, const float *B,
-                               const float *C, float *O, hipStream_t stream) {
+static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scratch, int M, int K, int D, int N,
+                               const int32_t *rowptr, const int32_t *colidx, const float *vals, const float *A,
+                               const float *B, const float *C, float *O, hipStream_t stream) {
     if (csrk_status s = check_dims("fusedmm_csr", M, K, D, N)) return s;
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr: rowptr and O must not be NULL");
     if (K > 0 && !C) return fail(CSRK_INVALID_ARG, "fusedmm_csr: C must not be NULL");
     if (K > 0 && D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "fusedmm_csr: A and B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     PlanScope scope(*d, plan);
@@ -1255,17 +1359,70 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, int M, int K, int D, int
 
 csrk_status spmm_csr(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                      const float *B, float *O, hipStream_t stream) {
-    return spmm_run(nullptr, M, K, N, rowptr, colidx, vals, B, O, stream);
+    return spmm_run(nullptr, ScratchSource{}, M, K, N, rowptr, colidx, vals, B, O, stream);
 }
 
 csrk_status sddmm_csr(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                       const float *A, const float *B, float *P, hipStream_t stream) {
-    return sddmm_run(nullptr, M, K, D, rowptr, colidx, vals, A, B, P, stream);
+    return sddmm_run(nullptr, ScratchSource{}, M, K, D, rowptr, colidx, vals, A, B, P, stream);
 }
 
 csrk_status fusedmm_csr(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                         const float *A, const float *B, const float *C, float *O, hipStream_t stream) {
-    return fusedmm_run(nullptr, M, K, D, N, rowptr, colidx, vals, A, B, C, O, stream);
+    return fusedmm_run(nullptr, ScratchSource{}, M, K, D, N, rowptr, colidx, vals, A, B, C, O, stream);
+}
+
+// --- the same calls on a workspace of the caller's: nothing allocated, nothing shared ------------------------
+
+// floats of scratch behind the int part that a call of this shape can need, whichever kernels it takes: partial
+// rows of the equal-nonzero split (one per worker), or the partial outputs of a K-split launch of a tiled kernel
+static size_t workspace_floats(const DeviceInfo &info, int op, int M, int K, int N) {
+    if (op == CSRK_OP_SDDMM) return (size_t)info.workers;
+    size_t floats = (size_t)info.workers * (size_t)(N > 0 ? N : 1);
+    DeviceState probe;
+    probe.cus = info.cus;
+    probe.workers = info.workers;
+    int smax = 1;
+    for (int kt : {64, 96, 128, 160, 192, 256, 384})      // tile heights of the tiled SPMM / FusedMM kernels
+        for (int three = 0; three < 2; ++three) {
+            const int s = ksplit_for(probe, M, K, kt, kTileWaves * 4, three != 0);
+            smax = s > smax ? s : smax;
+        }
+    if (smax > 1 && (size_t)smax * (size_t)M * (size_t)N > floats) floats = (size_t)smax * (size_t)M * (size_t)N;
+    return floats;
+}
+
+csrk_status csrk_workspace_bytes(int op, int M, int K, int N, int D, size_t *bytes) {
+    (void)D;        // part of the shape for symmetry with the calls; no kernel's scratch depends on it
+    if (!bytes) return fail(CSRK_INVALID_ARG, "csrk_workspace_bytes: bytes must not be NULL");
+    if (op != CSRK_OP_SPMM && op != CSRK_OP_SDDMM && op != CSRK_OP_FUSEDMM)
+        return fail(CSRK_INVALID_ARG, "csrk_workspace_bytes: unknown operation %d", op);
+    if (M < 0 || K < 0 || N < 0) return fail(CSRK_INVALID_ARG, "csrk_workspace_bytes: negative dimension");
+    const DeviceInfo *info = nullptr;
+    if (csrk_status s = device_info(&info)) return s;
+    *bytes = scratch_int_bytes(info->workers) + (workspace_floats(*info, op, M, K, N) * sizeof(float) + 255) / 256 * 256;
+    return CSRK_OK;
+}
+
+csrk_status spmm_csr_ws(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                        const float *B, float *O, void *workspace, size_t workspace_bytes, hipStream_t stream) {
+    if (!workspace) return fail(CSRK_INVALID_ARG, "spmm_csr_ws: workspace must not be NULL");
+    return spmm_run(nullptr, ScratchSource{workspace, workspace_bytes}, M, K, N, rowptr, colidx, vals, B, O, stream);
+}
+
+csrk_status sddmm_csr_ws(int M, int K, int D, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                         const float *A, const float *B, float *P, void *workspace, size_t workspace_bytes,
+                         hipStream_t stream) {
+    if (!workspace) return fail(CSRK_INVALID_ARG, "sddmm_csr_ws: workspace must not be NULL");
+    return sddmm_run(nullptr, ScratchSource{workspace, workspace_bytes}, M, K, D, rowptr, colidx, vals, A, B, P, stream);
+}
+
+csrk_status fusedmm_csr_ws(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                           const float *A, const float *B, const float *C, float *O, void *workspace,
+                           size_t workspace_bytes, hipStream_t stream) {
+    if (!workspace) return fail(CSRK_INVALID_ARG, "fusedmm_csr_ws: workspace must not be NULL");
+    return fusedmm_run(nullptr, ScratchSource{workspace, workspace_bytes}, M, K, D, N, rowptr, colidx, vals, A, B, C, O,
+                       stream);
 }
 
 // --- plans: the pattern analysed once, calls without per-call analysis or stand-by launches ---------------
@@ -1278,15 +1435,47 @@ static csrk_status plan_usable(const char *who, const csrk_plan_s *plan) {
     return CSRK_OK;
 }
 
+// the plan's own scratch if csrk_plan_reserve made it large enough for this call; otherwise the device's lazily
+// grown one (and its lock)
+static ScratchSource plan_scratch(const csrk_plan_s *plan, int op, int N) {
+    if (!plan->ws) return ScratchSource{};
+    const DeviceInfo *info = nullptr;
+    if (device_info(&info) != CSRK_OK) return ScratchSource{};
+    const size_t need = scratch_int_bytes(info->workers) + workspace_floats(*info, op, plan->M, plan->K, N) * sizeof(float);
+    return need <= plan->ws_bytes ? ScratchSource{plan->ws, plan->ws_bytes} : ScratchSource{};
+}
+
+csrk_status csrk_plan_reserve(csrk_plan *plan, int max_N) {
+    if (csrk_status s = plan_usable("csrk_plan_reserve", plan)) return s;
+    if (max_N < 0 || max_N >= (1 << 24)) return fail(CSRK_INVALID_ARG, "csrk_plan_reserve: width out of range");
+    size_t bytes = 0;
+    if (csrk_status s = csrk_workspace_bytes(CSRK_OP_FUSEDMM, plan->M, plan->K, max_N, 0, &bytes)) return s;
+    if (plan->ws && plan->ws_bytes >= bytes) return CSRK_OK;
+    void *mem = nullptr;
+    if (hipMalloc(&mem, bytes) != hipSuccess) return fail(CSRK_WORKSPACE, "csrk_plan_reserve: cannot allocate %zu bytes", bytes);
+    if (plan->ws) {
+        // calls enqueued earlier may still be using the old area
+        if (hipDeviceSynchronize() != hipSuccess || hipFree(plan->ws) != hipSuccess) {
+            (void)hipFree(mem);
+            return fail(CSRK_HIP_ERROR, "csrk_plan_reserve: releasing the previous workspace failed");
+        }
+    }
+    plan->ws = mem;
+    plan->ws_bytes = bytes;
+    return CSRK_OK;
+}
+
 csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t *colidx, hipStream_t stream,
                              csrk_plan **out) {
     if (!out) return fail(CSRK_INVALID_ARG, "csrk_plan_create: out must not be NULL");
     *out = nullptr;
     if (M < 0 || K < 0) return fail(CSRK_INVALID_ARG, "csrk_plan_create: negative dimension");
     if (!rowptr) return fail(CSRK_INVALID_ARG, "csrk_plan_create: rowptr must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    const ScratchSource scratch{};      // the device's lazily grown scratch
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     if (csrk_status s = ensure_scratch(*d, 1)) return s;
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
@@ -1314,7 +1503,7 @@ csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t 
         CSRK_HIP(hipStreamSynchronize(stream));
         if (host[0] != 0) return fail(CSRK_INVALID_ARG, "csrk_plan_create: colidx holds columns outside [0, K)");
     }
-    csrk_plan_s *plan = new csrk_plan_s{dev, M, K, (long long)nnz, rowptr, colidx, host[1] == 0, analysis[3] != 0, nullptr};
+    csrk_plan_s *plan = new csrk_plan_s{dev, M, K, (long long)nnz, rowptr, colidx, host[1] == 0, analysis[3] != 0, nullptr, nullptr, 0};
     if (hipMalloc(&plan->dflags, 8 * sizeof(int32_t)) != hipSuccess) {
         delete plan;
         return fail(CSRK_HIP_ERROR, "csrk_plan_create: hipMalloc of the plan's flag words failed");
@@ -1333,7 +1522,11 @@ csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t 
 csrk_status csrk_plan_destroy(csrk_plan *plan) {
     if (!plan) return CSRK_OK;
     std::lock_guard<std::mutex> lock(g_mu);
-    const hipError_t e = hipFree(plan->dflags);
+    hipError_t e = hipFree(plan->dflags);
+    if (plan->ws) {
+        const hipError_t e2 = hipFree(plan->ws);
+        if (e == hipSuccess) e = e2;
+    }
     delete plan;
     if (e != hipSuccess) return fail(CSRK_HIP_ERROR, "csrk_plan_destroy: hipFree: %s", hipGetErrorString(e));
     return CSRK_OK;
@@ -1350,19 +1543,22 @@ csrk_status csrk_plan_info(const csrk_plan *plan, long long *nnz, int *sorted, i
 csrk_status spmm_csr_plan(const csrk_plan *plan, int N, const float *vals, const float *B, float *O,
                           hipStream_t stream) {
     if (csrk_status s = plan_usable("spmm_csr_plan", plan)) return s;
-    return spmm_run(plan, plan->M, plan->K, N, plan->rowptr, plan->colidx, vals, B, O, stream);
+    return spmm_run(plan, plan_scratch(plan, CSRK_OP_SPMM, N), plan->M, plan->K, N, plan->rowptr, plan->colidx, vals, B, O,
+                    stream);
 }
 
 csrk_status sddmm_csr_plan(const csrk_plan *plan, int D, const float *vals, const float *A, const float *B, float *P,
                            hipStream_t stream) {
     if (csrk_status s = plan_usable("sddmm_csr_plan", plan)) return s;
-    return sddmm_run(plan, plan->M, plan->K, D, plan->rowptr, plan->colidx, vals, A, B, P, stream);
+    return sddmm_run(plan, plan_scratch(plan, CSRK_OP_SDDMM, 0), plan->M, plan->K, D, plan->rowptr, plan->colidx, vals, A,
+                     B, P, stream);
 }
 
 csrk_status fusedmm_csr_plan(const csrk_plan *plan, int D, int N, const float *vals, const float *A, const float *B,
                              const float *C, float *O, hipStream_t stream) {
     if (csrk_status s = plan_usable("fusedmm_csr_plan", plan)) return s;
-    return fusedmm_run(plan, plan->M, plan->K, D, N, plan->rowptr, plan->colidx, vals, A, B, C, O, stream);
+    return fusedmm_run(plan, plan_scratch(plan, CSRK_OP_FUSEDMM, N), plan->M, plan->K, D, N, plan->rowptr, plan->colidx,
+                       vals, A, B, C, O, stream);
 }
 
 csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int32_t *colidx, const float *vals,
@@ -1371,9 +1567,11 @@ csrk_status spmm_csr_bf16(int M, int K, int N, const int32_t *rowptr, const int3
     if (M == 0 || N == 0) return CSRK_OK;
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "spmm_csr_bf16: rowptr and O must not be NULL");
     if (K > 0 && !B) return fail(CSRK_INVALID_ARG, "spmm_csr_bf16: B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    const ScratchSource scratch{};      // the device's lazily grown scratch
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     const bool vec8 = (N % 8 == 0) && aligned16(B) && aligned16(O) && aligned16(d->head);
@@ -1428,9 +1626,11 @@ csrk_status sddmm_csr_bf16(int M, int K, int D, const int32_t *rowptr, const int
     if (M == 0 || K == 0) return CSRK_OK;
     if (!rowptr) return fail(CSRK_INVALID_ARG, "sddmm_csr_bf16: rowptr must not be NULL");
     if (D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "sddmm_csr_bf16: A and B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    const ScratchSource scratch{};      // the device's lazily grown scratch
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     const bool vec8 = (D % 8 == 0) && D > 0 && aligned16(A) && aligned16(B);
     const WidthCfg c = dot_width_cfg_bf16(D, vec8);
     const dim3 grid(d->workers / kWavesPerBlock);
@@ -1471,9 +1671,11 @@ csrk_status fusedmm_csr_bf16(int M, int K, int D, int N, const int32_t *rowptr, 
     if (!rowptr || !O) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: rowptr and O must not be NULL");
     if (K > 0 && !C) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: C must not be NULL");
     if (K > 0 && D > 0 && (!A || !B)) return fail(CSRK_INVALID_ARG, "fusedmm_csr_bf16: A and B must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    const ScratchSource scratch{};      // the device's lazily grown scratch
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     d->pending_ksplit = 0;
     if (csrk_status s = ensure_scratch(*d, N)) return s;
     const bool dvec8 = (D % 8 == 0) && D > 0 && aligned16(A) && aligned16(B);
@@ -1521,9 +1723,11 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
                               int *problems, int *sorted) {
     if (M < 0 || K < 0) return fail(CSRK_INVALID_ARG, "csrk_validate_csr: negative dimension");
     if (!rowptr) return fail(CSRK_INVALID_ARG, "csrk_validate_csr: rowptr must not be NULL");
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState *d = nullptr;
-    if (csrk_status s = device_state(&d)) return s;
+    const ScratchSource scratch{};      // the device's lazily grown scratch
+    CallLock lock;
+    DeviceState state;
+    DeviceState *d = &state;
+    if (csrk_status s = begin_call(state, scratch, lock)) return s;
     if (csrk_status s = ensure_scratch(*d, 1)) return s;
     int32_t *flags = d->head_row + d->workers;    // two spare words behind the worker table
     int32_t host[2] = {0, 0};
@@ -1540,6 +1744,88 @@ csrk_status csrk_validate_csr(int M, int K, const int32_t *rowptr, const int32_t
     }
     if (problems) *problems = host[0];
     if (sorted) *sorted = host[1] == 0;
+    return CSRK_OK;
+}
+
+// --- measuring aids ------------------------------------------------------------------------------------------
+
+__global__ void row_rotation_kernel(float *out) {
+    // lane l puts its own number into `a`; after fma_row_rotated<S>(acc = 0, a, b = 1) acc is the number of the lane
+    // whose `a` the rotation handed over
+    const int lane = threadIdx.x;
+    const float a = (float)lane;
+    static_for<0, 16>([&](auto sc) {
+        constexpr int S = decltype(sc)::value;
+        float acc = 0.f;
+        fma_row_rotated<S>(acc, a, 1.f);
+        out[S * kWave + lane] = acc;
+    });
+}
+
+csrk_status csrk_debug_row_rotation(float *out, hipStream_t stream) {
+    if (!out) return fail(CSRK_INVALID_ARG, "csrk_debug_row_rotation: out must not be NULL");
+    hipLaunchKernelGGL(row_rotation_kernel, dim3(1), dim3(kWave), 0, stream, out);
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status csrk_tile_phases(int op, int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx,
+                             const float *vals, const float *A, const float *B, const float *C, float *O,
+                             hipStream_t stream, double *cycles, int *tiles) {
+    if (op != CSRK_OP_SPMM && op != CSRK_OP_FUSEDMM) return fail(CSRK_INVALID_ARG, "csrk_tile_phases: SPMM or FusedMM");
+    if (!cycles || !tiles || !rowptr || !O || !C) return fail(CSRK_INVALID_ARG, "csrk_tile_phases: NULL argument");
+    if (N != 512 || M <= 0 || M % 64 != 0 || K <= 0 || (op == CSRK_OP_FUSEDMM && (D != 64 || !A || !B)))
+        return fail(CSRK_UNSUPPORTED, "csrk_tile_phases: only the 512-column kernels with 4 rows per wavefront (M a multiple of 64, D = 64)");
+    if (!aligned16(C) || !aligned16(O) || (op == CSRK_OP_FUSEDMM && (!aligned16(A) || !aligned16(B))))
+        return fail(CSRK_INVALID_ARG, "csrk_tile_phases: operands must be 16-byte aligned");
+    const int groups = M / 64;
+    const size_t waves = (size_t)groups * kTileWaves;
+    long long *dtim = nullptr;
+    int32_t *dflags = nullptr;
+    CSRK_HIP(hipMalloc((void **)&dtim, waves * kPhases * sizeof(long long)));
+    if (hipMalloc((void **)&dflags, 8 * sizeof(int32_t)) != hipSuccess) {
+        (void)hipFree(dtim);
+        return fail(CSRK_HIP_ERROR, "csrk_tile_phases: hipMalloc failed");
+    }
+    const int32_t words[8] = {0, 1, 0, 1, 0, 0, 0, 0};      // nothing unsorted seen, tiled kernel allowed, rows even
+    hipError_t e = hipMemcpyAsync(dflags, words, sizeof(words), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipMemsetAsync(dtim, 0, waves * kPhases * sizeof(long long), stream);
+    const float no_inline = __builtin_nanf("");
+    if (e == hipSuccess) {
+        if (op == CSRK_OP_SPMM) {
+            using L = KTileLds<2, 64>;
+            auto kern = ktile_kernel<2, 64, 4, true>;
+            e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, N, N, rowptr, colidx, vals,
+                                   C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim);
+                e = hipGetLastError();
+            }
+        } else {
+            using L = FusedTileLds<2, 64, 4, 32>;
+            auto kern = fused_ktile_kernel<2, 64, 4, 32, 3, 4, true>;
+            e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, D, N, N, rowptr, colidx,
+                                   vals, A, B, C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim);
+                e = hipGetLastError();
+            }
+        }
+    }
+    std::vector<long long> host(waves * kPhases);
+    int32_t seen[8] = {0};
+    if (e == hipSuccess) e = hipMemcpyAsync(host.data(), dtim, host.size() * sizeof(long long), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(seen, dflags, sizeof(seen), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(dtim);
+    (void)hipFree(dflags);
+    if (e != hipSuccess) return fail(CSRK_HIP_ERROR, "csrk_tile_phases: %s", hipGetErrorString(e));
+    if (seen[0] != 0) return fail(CSRK_INVALID_ARG, "csrk_tile_phases: the pattern's columns are not ascending");
+    for (int i = 0; i < kPhases; ++i) cycles[i] = 0.0;
+    for (size_t w = 0; w < waves; ++w)
+        for (int i = 0; i < kPhases; ++i) cycles[i] += (double)host[w * kPhases + i];
+    for (int i = 0; i < kPhases; ++i) cycles[i] /= (double)waves;
+    *tiles = (K + 63) / 64;
     return CSRK_OK;
 }
 
@@ -1584,13 +1870,13 @@ csrk_status csrk_release_workspace(void) {
     int dev = 0;
     CSRK_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return CSRK_OK;
-    DeviceState &d = g_dev[dev];
+    LazyScratch &g = g_lazy[dev];
     CSRK_HIP(hipDeviceSynchronize());
-    if (d.head) CSRK_HIP(hipFree(d.head));
-    if (d.head_row) CSRK_HIP(hipFree(d.head_row));
-    d.head = nullptr;
-    d.head_row = nullptr;
-    d.head_floats = 0;
+    if (g.head) CSRK_HIP(hipFree(g.head));
+    if (g.head_row) CSRK_HIP(hipFree(g.head_row));
+    g.head = nullptr;
+    g.head_row = nullptr;
+    g.head_floats = 0;
     return CSRK_OK;
 }
 

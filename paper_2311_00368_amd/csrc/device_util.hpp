@@ -61,6 +61,10 @@ __device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
     }
 }
 
+// four floats as one 128-bit register value: loads and stores of it are plain moves (an array of HIP's float4
+// structs filled through a casted pointer can end up copied through private memory instead)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 // VEC consecutive floats; VEC a multiple of 4: 128-bit accesses (address must be 16-byte aligned).
 template <int VEC>
 __device__ __forceinline__ void load_vec(const float *p, float (&d)[VEC]) {
@@ -108,6 +112,17 @@ __device__ __forceinline__ void store_vec(float *p, const float (&d)[VEC]) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) p[i] = d[i];
     }
+}
+
+// Element number `lane` behind a wave-uniform pointer, for a lane-wide load of a chunk of colidx or vals: the
+// pointer from scalar registers, the lane's byte offset (unsigned) from one vector register.  The empty asm pins the
+// pointer to scalar registers as it is: otherwise the compiler re-associates base + position + lane into
+// (base + lane) + position and keeps the loop-invariant per-lane 64-bit address in two vector registers per
+// stream, registers the tiled kernels do not have.
+template <typename E>
+__device__ __forceinline__ E lane_elem(const E *uniform_base, unsigned lane_bytes) {
+    asm("" : "+s"(uniform_base));
+    return *reinterpret_cast<const E *>(reinterpret_cast<const char *>(uniform_base) + lane_bytes);
 }
 
 // First r in [0, M) with rowptr[r] >= x, or M if there is none.  All 64 lanes of the

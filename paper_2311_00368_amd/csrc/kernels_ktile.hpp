@@ -232,23 +232,61 @@ __device__ __forceinline__ void ksplit_reduce(size_t count4, int S, const float4
     }
 }
 
-template <int T, int KT>
+// Where a wavefront's cycles go, phase by phase (a measuring build of a kernel; the production instantiations
+// have ON = false and none of this exists in them).  lap(i) adds the cycles since the previous lap to counter i.
+// Reading the clock waits for outstanding LDS / scalar-memory operations of the wavefront, so laps sit only where
+// the kernel drains them anyway (around barriers) or where the perturbation is itself of interest.
+constexpr int kPhases = 8;
+template <bool ON>
+struct PhaseClock {
+    long long last = 0;
+    long long acc[kPhases] = {};
+    __device__ __forceinline__ void start() {
+        if constexpr (ON) last = clock64();
+    }
+    __device__ __forceinline__ void lap(int i) {
+        if constexpr (ON) {
+            const long long now = clock64();
+            acc[i] += now - last;
+            last = now;
+        }
+    }
+    // lane 0 of every wavefront leaves its counters at out[(workgroup * waves + wave) * kPhases ...]
+    __device__ __forceinline__ void store(long long *out, int waves_per_group, int wave, int lane) const {
+        if constexpr (ON) {
+            if (out && lane == 0) {
+                long long *o = out + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * waves_per_group + wave) * kPhases;
+#pragma unroll
+                for (int i = 0; i < kPhases; ++i) o[i] = acc[i];
+            }
+        }
+    }
+};
+// phases of the tiled SPMM / FusedMM kernels
+enum : int { kPhBarrier1 = 0, kPhCommit = 1, kPhBarrier2 = 2, kPhIssue = 3, kPhCompute = 4, kPhReload = 5, kPhScore = 6 };
+
+template <int T, int KT, int WAVES = kTileWaves>
 struct KTileLds {
     static constexpr int kRowFloats = T * 256;
     static constexpr int kCFloats = KT * kRowFloats;
     // (column, value) pairs: two 64-entry slots per wavefront, so that the next row's chunk is
     // written while the current row is consumed
-    static constexpr int kEntFloats = kTileWaves * 2 * kWave * 2;
+    static constexpr int kEntFloats = WAVES * 2 * kWave * 2;
     static constexpr int kBytes = (kCFloats + kEntFloats) * 4;
 };
 
 // SPMM: O[row, :] = sum over the row's entries of value * B[column, :] (Algorithm 2), B called Cmat here.
-template <int T, int KT, int ROWS>
-__global__ __launch_bounds__(kTileThreads) void ktile_kernel(
+// TIMED: the measuring build (see PhaseClock); `tim` receives kPhases counters per wavefront.
+// WAVES: wavefronts per workgroup (16: one workgroup per CU; 8: two, each with a tile half as high, so that one
+// computes while the other sits at a barrier or stages its tile).
+template <int T, int KT, int ROWS, bool TIMED = false, int WAVES = kTileWaves>
+__global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kernel(
     int M, int K, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
-    float *partial, float inline_density, int32_t *other_flags) {
-    using L = KTileLds<T, KT>;
+    float *partial, float inline_density, int32_t *other_flags, long long *tim = nullptr) {
+    using L = KTileLds<T, KT, WAVES>;
+    constexpr int kThreads = WAVES * kWave;
+    PhaseClock<TIMED> clk;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     if (!tile_go(M, K, rowptr, inline_density, flags, other_flags, reinterpret_cast<int *>(lds))) return;
     constexpr int kRowBytes = L::kRowFloats * 4;
@@ -257,11 +295,12 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     float *ct = lds;                        // KT x (T*256) floats
     int2 *ent = reinterpret_cast<int2 *>(lds + L::kCFloats) + wave * (2 * kWave);
 
-    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const int row0 = blockIdx.x * (WAVES * ROWS) + wave * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
+    const unsigned lane_b = (unsigned)lane * 4u;    // ... and its byte offset in a lane-wide load of a chunk
 
     const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+    if (gridDim.y > 1 && ksplit_block_unsorted<WAVES * ROWS>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
     int pos[ROWS], end[ROWS];
@@ -275,10 +314,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
         if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
-        const int j = pos[r] + lane;
-        const bool ok = j < end[r];
-        kc[r] = ok ? colidx[j] : 0x7fffffff;
-        vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+        const bool ok = lane < end[r] - pos[r];
+        kc[r] = ok ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
+        vc[r] = ok ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
 #pragma unroll
         for (int t = 0; t < T; ++t)
 #pragma unroll
@@ -289,60 +327,82 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
     const int n4 = N >> 2;                  // float4s of a dense row that this launch works on ...
     const int ld4 = ld >> 2;                // ... out of this many (a launch may take a slab of the columns)
     constexpr int kRow4 = T * 64;
-    constexpr int kPer = KT * kRow4 / kTileThreads;
-    float4 stage[kPer];
+    constexpr int kPer = KT * kRow4 / kThreads;
+    static_assert((KT * kRow4) % kThreads == 0, "the staging loop copies whole rounds of float4s");
+    f32x4 stage[kPer];
     // Thread t copies float4 number (t % kRow4) of tile rows t / kRow4, + kStep, + 2 kStep, ...: its
     // offset inside a tile never changes, so a tile costs this thread kPer loads off a uniform
-    // base pointer with no address arithmetic in vector registers.
-    constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
+    // base pointer with a 32-bit offset of its own.  Threads past the width of a narrower launch re-read the
+    // row's last float4 (those LDS columns are only ever read by lanes whose accumulators are not stored), rows
+    // past K in the last tile re-read row K-1 (no entry points at them): every thread issues every load, under
+    // no condition.
+    constexpr int kStep = kThreads / kRow4;      // tile rows covered by one round of loads
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
-    const bool my_col = my_c4 < n4;
-    const size_t my_off = (size_t)my_kk * ld4 + my_c4;
-    const size_t step_off = (size_t)kStep * ld4;
-    auto issue = [&](int k0) {
-        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * ld4;   // uniform
+    const int col4 = my_c4 < n4 ? my_c4 : n4 - 1;
+    const unsigned my_off = ((unsigned)my_kk * (unsigned)ld4 + (unsigned)col4) * 16u;
+    const size_t step_bytes = (size_t)kStep * ld4 * 16;
+    // loads number [I0, I1) of this thread for the tile that starts at column k0
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
+        const char *base = reinterpret_cast<const char *>(Cmat);
         if (k0 + KT <= K) {
+            const char *tile = base + (size_t)k0 * ld4 * 16;   // uniform
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (my_col) {
-#pragma unroll
-                for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
-            }
+            for (int i = I0; i < I1; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(tile + i * step_bytes + my_off);
         } else {                                      // last, partial tile
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+            for (int i = I0; i < I1; ++i) {
+                int k = k0 + i * kStep + my_kk;
+                k = k < K ? k : K - 1;
+                stage[i] = *reinterpret_cast<const f32x4 *>(base + ((size_t)k * ld4 + col4) * 16);
             }
         }
     };
     auto commit = [&]() {
-        float4 *dst = reinterpret_cast<float4 *>(ct);
+        f32x4 *dst = reinterpret_cast<f32x4 *>(ct);
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        for (int i = 0; i < kPer; ++i) dst[i * kThreads + threadIdx.x] = stage[i];
     };
 
-    issue(ks.kb);
+    if (ks.kb < ks.ke) issue(ks.kb, std::integral_constant<int, 0>{}, std::integral_constant<int, kPer>{});
+    clk.start();
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
+        clk.lap(kPhBarrier1);
         commit();
+        if constexpr (TIMED) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        clk.lap(kPhCommit);
         __syncthreads();
-        if (k0 + KT < ks.ke) issue(k0 + KT);    // lands while this tile is being worked on
+        clk.lap(kPhBarrier2);
+        // The next tile is requested into registers while this one is worked on - but NOT by all wavefronts at once
+        // here: 16 wavefronts issuing 8 loads of 1 KB each at the same moment fill the vector-memory queue, which
+        // takes them at 64 bytes a clock, and every wavefront then sits in its load instructions for some 3000
+        // cycles before its first multiply-add (measured: a fifth of the kernel's time, and as much again at the
+        // next barrier, where the wavefronts that got through first wait for the last).  A wavefront issues its
+        // loads at the start of one of its rows instead, a different row from wavefront to wavefront, so that at
+        // any moment only a quarter of them are in the queue while the others keep the LDS and the VALUs busy.
+        const bool more = k0 + KT < ks.ke;
+        const int issue_row = wave % ROWS;
         const int kend = k0 + KT;
         // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
         // large column numbers wrap instead of overflowing (the sum below is always a small offset)
         const unsigned lb = (unsigned)(n * 4) - (unsigned)k0 * (unsigned)kRowBytes;
         int cnts[ROWS];
         ent[lane] = make_int2(kc[0], __builtin_bit_cast(int, vc[0]));
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
+        static_for<0, ROWS>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+            if (more && issue_row == r) {
+                clk.lap(kPhCompute);
+                issue(k0 + KT, std::integral_constant<int, 0>{}, std::integral_constant<int, kPer>{});
+                clk.lap(kPhIssue);
+            }
             // entries of this tile = leading lanes of the chunk with column < kend
             const int cnt = __builtin_popcountll(__ballot(kc[r] < kend));
             cnts[r] = cnt;
             // order check on the chunk, here where it is first used (not where it was requested,
             // which would make the request a wait)
             bad |= descending_lanes(kc[r]);
-            if (r + 1 < ROWS)
+            if constexpr (r + 1 < ROWS)
                 ent[((r + 1) & 1) * kWave + lane] = make_int2(kc[r + 1], __builtin_bit_cast(int, vc[r + 1]));
             const int2 *e = ent + (r & 1) * kWave;     // this row's slot
             auto batch = [&](int t, auto count) {
@@ -394,8 +454,8 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                     if (__builtin_expect(c < kWave || pos[r] >= end[r], 1)) break;
                     const int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
                     const bool okn = lane < end[r] - pos[r];
-                    kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
-                    vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                    kc[r] = okn ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
+                    vc[r] = okn ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
                     bad |= descending_lanes(kc[r]);
                     if (__builtin_amdgcn_readlane(kc[r], 0) < lastk) bad |= 1;     // descending across the chunk boundary
                     c = __builtin_popcountll(__ballot(kc[r] < kend));
@@ -428,18 +488,21 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
                     }
                 }
             }
-        }
+        });
+        clk.lap(kPhCompute);
         // look-ahead chunks for the next tile, all requested here, after the arithmetic (requested
         // earlier, inside the row loop, they measure slower)
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (cnts[r] > 0) {
                 const bool okn = lane < end[r] - pos[r];
-                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
-                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                kc[r] = okn ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;          // uniform base + lane
+                vc[r] = okn ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
             }
         }
+        clk.lap(kPhReload);
     }
+    clk.store(tim, WAVES, wave, lane);
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
     float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;
 #pragma unroll
@@ -464,10 +527,10 @@ __global__ __launch_bounds__(kTileThreads) void ktile_kernel(
 // Sixty-four lanes that each read 16 bytes of a different, arbitrary row would collide in the
 // LDS banks (rows start at the same bank), so every lane walks its row in a ROTATED order:
 // at step s lane i (numbered inside its group of 16 lanes) reads the 16-byte piece number
-// (i + s) mod 16 of its row.  The 16 lanes the LDS serves together then touch 16 different
+// (i - s) mod 16 of its row.  The 16 lanes the LDS serves together then touch 16 different
 // pieces, i.e. all banks once, whatever rows they are in; no padding is needed.  The row of
 // A that multiplies these pieces is spread over the same 16 lanes, piece i in lane i, and
-// the rotation `row_ror:s` of the DPP operand of the multiply-add hands lane i piece (i + s)
+// the rotation `row_ror:s` of the DPP operand of the multiply-add hands lane i piece (i - s)
 // at no extra instruction.  Nothing is carried from tile to tile except the per-row cursor
 // and look-ahead chunk, found exactly as in ktile_kernel; the next tile of B is fetched into
 // registers while the current one is worked on.  P may alias vals: each lane reads its value
@@ -506,12 +569,12 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     const int ld4 = ld >> 2;                // float4s from one row of A / B to the next
     float *arows = lds + L::kTileFloats + wave * (ROWS * DMAX);   // this wavefront's rows of A
 
-    // which way row_ror turns is measured, not assumed: `turn` is +1 or -1 (mod 16)
+    // row_ror:s hands lane i the value of lane (i - s) mod 16 (fixed by the instruction set; a GPU test checks
+    // fma_row_rotated against a host loop), so at step s lane i holds piece (i - s) of A and reads that piece of B
     const int i16 = lane & 15;
-    const int turn = (__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15;
     int off[S];                             // byte offset in an LDS row of the piece read at step s
 #pragma unroll
-    for (int s = 0; s < S; ++s) off[s] = ((i16 + turn * s) & (S - 1)) * 16;
+    for (int s = 0; s < S; ++s) off[s] = ((i16 - s) & (S - 1)) * 16;
 
     // vals == NULL means all ones: the value loads then read colidx instead (any readable array of
     // the same length serves) and their results are not used

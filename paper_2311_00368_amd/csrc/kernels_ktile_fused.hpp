@@ -38,13 +38,15 @@ struct FusedTileLds {
 // B tile are loaded at the start of their own tile (all of it ahead, B included, when PF == kPer).
 // LIVE: rows a wavefront really owns.  LIVE = 3 with ROWS = 4 is the 48-rows-per-workgroup version (see
 // tile_rows_for on the host): laid out for four rows, the fourth one of every wavefront empty.
-template <int T, int KT, int ROWS, int SL, int PF, int LIVE = ROWS>
+// TIMED: the measuring build (see PhaseClock in kernels_ktile.hpp); `tim` receives kPhases counters per wavefront.
+template <int T, int KT, int ROWS, int SL, int PF, int LIVE = ROWS, bool TIMED = false>
 __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     int M, int K, int D, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
-    int32_t *other_flags) {
+    int32_t *other_flags, long long *tim = nullptr) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
+    PhaseClock<TIMED> clk;
     static_assert(SL == 32 || SL == 64, "slot sizes");
     static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -58,17 +60,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     float *bt = lds + L::kCFloats;
     int2 *ent = reinterpret_cast<int2 *>(bt + L::kBFloats) + wave * (ROWS * SL);
 
-    // The rotated walk below is written for row_ror:s handing lane i the value of lane i - s.  Measure it;
-    // should it ever turn the other way, stand down and let the general kernel behind this one do the call.
+    // (row_ror:s hands lane i the value of lane (i - s) mod 16 of its row of 16 lanes: fixed by the instruction set;
+    // a GPU test checks fma_row_rotated against a host loop.)
     const int i16 = lane & 15;
-    if (((__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15) != 15) {
-        if (threadIdx.x == 0) flags[0] = 1;
-        return;
-    }
 
     static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
     const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide piece of the output
+    const unsigned lane_b = (unsigned)lane * 4u;    // ... and its byte offset in a lane-wide load of a chunk
     const int my_r = (lane >> 4) / kGroupsPerRow;       // the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
@@ -88,10 +87,9 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         pos[r] = live ? uniform(rowptr[row]) : 0;
         end[r] = live ? uniform(rowptr[row + 1]) : 0;
         if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
-        const int j = pos[r] + lane;
-        const bool ok = j < end[r];
-        kc[r] = ok ? colidx[j] : 0x7fffffff;
-        vc[r] = ok ? (vals ? vals[j] : 1.f) : 0.f;
+        const bool ok = lane < end[r] - pos[r];
+        kc[r] = ok ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
+        vc[r] = ok ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
 #pragma unroll
         for (int t = 0; t < T; ++t)
 #pragma unroll
@@ -107,47 +105,51 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     constexpr int kPer = KT * kRow4 / kTileThreads;
     constexpr int kPerB = (KT * 16 + kTileThreads - 1) / kTileThreads;
     static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
-    float4 stage[kPer];
-    float4 stageb[kPerB];
+    f32x4 stage[kPer];
+    f32x4 stageb[kPerB];
     constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
-    const bool my_col = my_c4 < n4;
-    const size_t my_off = (size_t)my_kk * ld4 + my_c4;
-    const size_t step_off = (size_t)kStep * ld4;
+    // Every thread issues every load, under no condition: threads past the width of a narrower launch re-read the
+    // row's last float4 (LDS columns only read by lanes whose accumulators are not stored), rows past K in the last
+    // tile re-read row K-1 (no entry points at them).
+    const int col4 = my_c4 < n4 ? my_c4 : n4 - 1;
+    const unsigned my_off = ((unsigned)my_kk * (unsigned)ld4 + (unsigned)col4) * 16u;
+    const size_t step_bytes = (size_t)kStep * ld4 * 16;
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
-        const float4 *tile = reinterpret_cast<const float4 *>(Cmat) + (size_t)k0 * ld4;   // uniform
+        const char *base = reinterpret_cast<const char *>(Cmat);
         if (k0 + KT <= K) {
+            const char *tile = base + (size_t)k0 * ld4 * 16;   // uniform
 #pragma unroll
-            for (int i = I0; i < I1; ++i) stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (my_col) {
-#pragma unroll
-                for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
-            }
+            for (int i = I0; i < I1; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(tile + i * step_bytes + my_off);
         } else {                                      // last, partial tile
 #pragma unroll
             for (int i = I0; i < I1; ++i) {
-                stage[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (my_col && k0 + i * kStep + my_kk < K) stage[i] = tile[i * step_off + my_off];
+                int kq = k0 + i * kStep + my_kk;
+                kq = kq < K ? kq : K - 1;
+                stage[i] = *reinterpret_cast<const f32x4 *>(base + ((size_t)kq * ld4 + col4) * 16);
             }
         }
     };
+    // the tile of B: rows of D floats, zero-padded to 64 in LDS (the score stage walks all 16 pieces of a row)
     auto issue_b = [&](int k0) {
-        const float4 *srcb = reinterpret_cast<const float4 *>(Bmat);
         const int d4 = D >> 2;
+        const f32x4 *tileb = reinterpret_cast<const f32x4 *>(Bmat) + (size_t)k0 * d4;     // uniform
 #pragma unroll
         for (int i = 0; i < kPerB; ++i) {
             const int e = i * kTileThreads + threadIdx.x;
-            const int kk = e >> 4, c4 = e & 15;
-            stageb[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (e < KT * 16 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
+            int kk = e >> 4;
+            kk = k0 + kk < K ? kk : K - 1 - k0;
+            const int c4 = e & 15;
+            stageb[i] = lane_elem(tileb, (unsigned)(kk * d4 + (c4 < d4 ? c4 : d4 - 1)) * 16u);
+            if (c4 >= d4) stageb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
     auto commit = [&]() {
-        float4 *dst = reinterpret_cast<float4 *>(ct);
+        f32x4 *dst = reinterpret_cast<f32x4 *>(ct);
 #pragma unroll
         for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
-        float4 *dstb = reinterpret_cast<float4 *>(bt);
+        f32x4 *dstb = reinterpret_cast<f32x4 *>(bt);
 #pragma unroll
         for (int i = 0; i < kPerB; ++i) {
             const int e = i * kTileThreads + threadIdx.x;
@@ -159,21 +161,32 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     using IEND = std::integral_constant<int, kPer>;
     constexpr bool kAllAhead = PF == kPer;
 
-    if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
-    if constexpr (kAllAhead) issue_b(ks.kb);
+    if (ks.kb < ks.ke) {
+        if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
+        if constexpr (kAllAhead) issue_b(ks.kb);
+    }
+    clk.start();
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
-        if constexpr (!kAllAhead) {
+        clk.lap(kPhBarrier1);
+        if constexpr (!kAllAhead) {         // what no register could be spared for during the previous tile's arithmetic
             issue(k0, IPF{}, IEND{});
             issue_b(k0);
+            clk.lap(kPhIssue);
         }
         commit();
+        if constexpr (TIMED) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        clk.lap(kPhCommit);
         __syncthreads();
+        clk.lap(kPhBarrier2);
+        // (Issuing these loads later, from a different row's accumulate stage in each wavefront, as the SPMM kernel
+        // does with its whole tile, measured level here: with 3 of 8 loads ahead the queue is not what is waited for.)
         if constexpr (PF > 0) {
-            if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
+            if (k0 + KT < ks.ke) {          // lands while this tile is being worked on
                 issue(k0 + KT, I0{}, IPF{});
                 if constexpr (kAllAhead) issue_b(k0 + KT);
             }
+            clk.lap(kPhIssue);
         }
         const int kend = k0 + KT;
         // lane's byte offset in a tile row, minus the tile origin; unsigned so that the products with
@@ -219,6 +232,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
 
         for (int base = 0; base < maxcnt; base += kPass) {
             // ---- score stage: this lane's entry of this pass
+            clk.lap(kPhCompute);
             {
                 const int idx = base + my_first;
                 const bool on = idx < my_cnt;
@@ -252,6 +266,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 });
                 if (on) reinterpret_cast<int *>(mine)[1] = __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * dot);
             }
+            if constexpr (TIMED) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            clk.lap(kPhScore);
             // ---- accumulate stage: entries [base, base + kPass) of every row
 #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
@@ -345,8 +361,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 if (full[r] == kWave) {
                     const int lastk = __builtin_amdgcn_readlane(kc[r], kWave - 1);
                     const bool okn = lane < end[r] - pos[r];
-                    kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;
-                    vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                    kc[r] = okn ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
+                    vc[r] = okn ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
                     if (__builtin_amdgcn_readlane(kc[r], 0) < lastk) bad |= 1;   // descending across the chunk boundary
                     fresh[r] = true;
                     moved[r] = false;           // its look-ahead chunk is already the right one
@@ -356,16 +372,19 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             if (__builtin_expect(!again, 1)) break;
         }
         }   // rounds of this tile
+        clk.lap(kPhCompute);
         // look-ahead chunks for the next tile, all requested here, after the arithmetic
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (moved[r]) {
                 const bool okn = lane < end[r] - pos[r];
-                kc[r] = okn ? (colidx + pos[r])[lane] : 0x7fffffff;          // uniform base + lane
-                vc[r] = okn ? (vals ? (vals + pos[r])[lane] : 1.f) : 0.f;
+                kc[r] = okn ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;          // uniform base + lane
+                vc[r] = okn ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
             }
         }
+        clk.lap(kPhReload);
     }
+    clk.store(tim, kTileWaves, wave, lane);
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
     float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
@@ -425,12 +444,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     float *bt = lds + L::kCFloats;
     int2 *ent = reinterpret_cast<int2 *>(bt + L::kBFloats) + wave * (ROWS * SL);
 
-    // see fused_ktile_kernel: the rotated walk assumes row_ror:s hands lane i the value of lane i - s
+    // see fused_ktile_kernel: row_ror:s hands lane i the value of lane (i - s) mod 16
     const int i16 = lane & 15;
-    if (((__builtin_amdgcn_update_dpp(0, lane, 0x121, 0xf, 0xf, false) - lane) & 15) != 15) {
-        if (threadIdx.x == 0) flags[0] = 1;
-        return;
-    }
 
     static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
     const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;

@@ -12,7 +12,8 @@ import pytest
 
 import helpers
 from paper_2311_00368_amd import inputs
-from test_gpu_parity import csrk, dev, run_fused, run_sddmm, run_spmm  # noqa: F401  (csrk is a fixture)
+import oracle
+from test_gpu_parity import check, csrk, dev, run_fused, run_sddmm, run_spmm  # noqa: F401  (csrk is a fixture)
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -456,3 +457,34 @@ def test_sddmm_in_place_on_unsorted_columns_where_the_tiled_kernel_would_be_trie
     assert got.data_ptr() == d_v.data_ptr()
     assert torch.equal(got, csrk.sddmm_csr(M, K, D, dev(rp), dev(ci), dev(v), dev(A), dev(B)))
     csrk.csrk_plan_destroy(plan)
+
+
+def test_row_rotation_of_the_rotated_multiply_add(csrk):
+    # The tiled SDDMM kernel and FusedMM's score stage walk a row of B in rotated order and take the matching piece
+    # of A through the row rotation of the multiply-add's cross-lane operand: rotation by S must hand lane l the
+    # operand of lane (l - S) mod 16 of its row of 16 lanes, for every S the kernels use.
+    got = csrk.csrk_debug_row_rotation().cpu().numpy()
+    lanes = np.arange(64)
+    for S in range(16):
+        want = (lanes & ~15) | ((lanes - S) & 15)
+        np.testing.assert_array_equal(got[S], want.astype(np.float32), err_msg=f"rotation by {S}")
+
+
+def test_phase_clock_build_computes_the_same_results(csrk):
+    # the measuring builds of the 512-column kernels (csrk_tile_phases) are the production code plus cycle counters
+    M, K, N, D = 1024, 2048, 512, 64
+    rng = np.random.default_rng(77)
+    rp, ci = inputs.bernoulli_csr(6, M, K, 0.2)
+    v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
+    cyc, tiles, O = csrk.csrk_tile_phases(csrk.CSRK_OP_SPMM, M, K, D, N, d_rp, d_ci, d_v, None, None, dev(C))
+    assert tiles == K // 64 and cyc[4] > 0 and cyc[6] == 0 and all(c >= 0 for c in cyc)
+    want, a = oracle.spmm(M, K, N, rp, ci, v, C)
+    check(O.cpu().numpy(), want, a, "spmm, measuring build")
+    cyc, tiles, O = csrk.csrk_tile_phases(csrk.CSRK_OP_FUSEDMM, M, K, D, N, d_rp, d_ci, d_v, dev(A), dev(B), dev(C))
+    assert cyc[4] > 0 and cyc[6] > 0
+    want, a = oracle.fusedmm(M, K, D, N, rp, ci, v, A, B, C)
+    check(O.cpu().numpy(), want, a, "fusedmm, measuring build")
