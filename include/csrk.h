@@ -112,6 +112,23 @@ csrk_status fusedmm_csr(int M, int K, int D, int N,
                         float *O, hipStream_t stream);
 
 /*
+ * fusedmm_csr for callers that cannot allocate: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and results as fusedmm_csr; the kernels' scratch is a fixed
+ * area inside the library's device image (16 MB + 64 KB, held by every device the library runs on until the
+ * process ends), so the call allocates and frees nothing, never synchronises and takes no lock beyond the one
+ * that guards looking up the area's address the first time a device is used.  It serves outputs of up to 512
+ * columns (8192 partial rows of N floats), and short matrices whose reduction dimension is cut into ranges only
+ * while their partial outputs fit 16 MB; beyond that it returns CSRK_WORKSPACE with the sizes in the message and
+ * enqueues nothing (fusedmm_csr_ws takes any size).  All calls on one device share the one area, which keeps
+ * whatever the last call left in it (every call initialises what it reads): calls that overlap in time on one
+ * device, on whatever streams, race - serialise them on one stream.
+ */
+csrk_status fusedmm_csr_static(int M, int K, int D, int N,
+                               const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                               const float *A, const float *B, const float *C,
+                               float *O, hipStream_t stream);
+
+/*
  * The same three operations with the DENSE operands stored as bfloat16 (the upper 16
  * bits of an IEEE single, row-major like their FP32 counterparts): the variant the
  * paper names as future work (section "Conclusion").  The stored values of S, all

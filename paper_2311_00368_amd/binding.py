@@ -60,6 +60,7 @@ def load(build_if_missing: bool = True):
     lib.sddmm_csr_ws.argtypes = [i, i, i, p, p, p, p, p, p, p, sz, p]
     lib.fusedmm_csr_ws.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p, sz, p]
     lib.csrk_plan_reserve.argtypes = [p, i]
+    lib.fusedmm_csr_static.argtypes = [i, i, i, i, p, p, p, p, p, p, p, p]
     lib.csrk_tile_phases.argtypes = [i, i, i, i, i, p, p, p, p, p, p, p, p, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_int)]
     lib.csrk_debug_row_rotation.argtypes = [p, p]
@@ -72,7 +73,7 @@ def load(build_if_missing: bool = True):
               lib.csrk_plan_info, lib.spmm_csr_plan, lib.sddmm_csr_plan, lib.fusedmm_csr_plan,
               lib.csrk_profile_enable, lib.csrk_profile_collect, lib.csrk_workspace_bytes, lib.spmm_csr_ws,
               lib.sddmm_csr_ws, lib.fusedmm_csr_ws, lib.csrk_plan_reserve, lib.csrk_tile_phases,
-              lib.csrk_debug_row_rotation):
+              lib.csrk_debug_row_rotation, lib.fusedmm_csr_static):
         f.restype = ctypes.c_int
     lib.csrk_last_error.restype = ctypes.c_char_p
     lib.csrk_version.restype = ctypes.c_char_p
@@ -221,6 +222,18 @@ def fusedmm_csr_ws(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C
                                   _dev_ptr(B, "B", torch.float32, (K, D), dev),
                                   _dev_ptr(C, "C", torch.float32, (K, N), dev),
                                   _dev_ptr(O, "O", torch.float32, (M, N), dev), ws, ws_bytes, _stream(dev)))
+    return O
+
+
+def fusedmm_csr_static(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O) -> torch.Tensor:
+    """fusedmm_csr on the library's static scratch area: allocates nothing (O must be given)."""
+    lib = load()
+    dev, _, rp, ci, va = _csr_ptrs(M, rowptr, colidx, vals, False)
+    with torch.cuda.device(dev):
+        _check(lib.fusedmm_csr_static(M, K, D, N, rp, ci, va, _dev_ptr(A, "A", torch.float32, (M, D), dev),
+                                      _dev_ptr(B, "B", torch.float32, (K, D), dev),
+                                      _dev_ptr(C, "C", torch.float32, (K, N), dev),
+                                      _dev_ptr(O, "O", torch.float32, (M, N), dev), _stream(dev)))
     return O
 
 

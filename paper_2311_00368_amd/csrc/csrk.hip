@@ -1022,6 +1022,33 @@ bool launch_fused_bf16_n(const WidthCfg &nc, dim3 grid, hipStream_t st, int M, i
     return false;
 }
 
+// --- scratch for the entry point that may not allocate --------------------------------------------------------
+// A fixed area in the library's own device image: 64 KB for the worker table and flag words plus 16 MB of partial
+// rows (8192 workers x 512 columns) or partial outputs.  Every device the library runs on holds its own copy, at
+// its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t(16) << 20) + (size_t(64) << 10);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// The array's name is only a host-side stand-in for the symbol: the device address is asked for once per device,
+// with that device current, and host code passes that pointer - never the name - to kernels.
+void *g_static_scratch[kMaxDevices] = {};
+
+csrk_status static_scratch_ptr(void **out) {
+    int dev = 0;
+    CSRK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CSRK_UNSUPPORTED, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_static_scratch[dev]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(CSRK_HIP_ERROR, "hipGetSymbolAddress of the static scratch failed: %s", hipGetErrorString(e));
+        g_static_scratch[dev] = ptr;
+    }
+    *out = g_static_scratch[dev];
+    return CSRK_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1433,6 +1460,25 @@ static csrk_status plan_usable(const char *who, const csrk_plan_s *plan) {
     CSRK_HIP(hipGetDevice(&dev));
     if (dev != plan->dev) return fail(CSRK_INVALID_ARG, "%s: plan was made on device %d, current device is %d", who, plan->dev, dev);
     return CSRK_OK;
+}
+
+csrk_status fusedmm_csr_static(int M, int K, int D, int N, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *A, const float *B, const float *C, float *O,
+                               hipStream_t stream) {
+    if (csrk_status s = check_dims("fusedmm_csr_static", M, K, D, N)) return s;
+    // refuse up front what cannot fit, with the sizes in the message (the call itself would also notice)
+    const DeviceInfo *info = nullptr;
+    if (csrk_status s = device_info(&info)) return s;
+    const size_t need = scratch_int_bytes(info->workers) + workspace_floats(*info, CSRK_OP_FUSEDMM, M, K, N) * sizeof(float);
+    if (need > kStaticScratchBytes)
+        return fail(CSRK_WORKSPACE,
+                    "fusedmm_csr_static: this shape needs %zu bytes of scratch, the static area holds %zu (outputs of up to "
+                    "512 columns; up to 16 MB of partial outputs for short matrices): use fusedmm_csr_ws",
+                    need, kStaticScratchBytes);
+    void *ptr = nullptr;
+    if (csrk_status s = static_scratch_ptr(&ptr)) return s;
+    return fusedmm_run(nullptr, ScratchSource{ptr, kStaticScratchBytes}, M, K, D, N, rowptr, colidx, vals, A, B, C, O,
+                       stream);
 }
 
 // the plan's own scratch if csrk_plan_reserve made it large enough for this call; otherwise the device's lazily
