@@ -34,24 +34,26 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X: 256 CUs x 2.4 GHz x 256 flop/clk/CU (needs packed FP32)
-FP32_FMA_CEILING_TFLOPS = 78.6    # one v_fma_f32 per SIMD per 4 clocks: 128 flop/clk/CU (packed FP32 is switched off)
-HBM_PEAK_GBS = 8000.0
-LDS_READ_MEASURED_TBS = 95.7      # 128-bit LDS reads, 16 wavefronts per CU, micro-benchmarked: 155.7 B/clk/CU
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X, published: 256 CUs x 2.4 GHz x 256 flop/clk/CU
+HBM_PEAK_GBS = 8000.0             # MI355X, published
+# The rates this build's instruction mix can reach (plain v_fma_f32, since packed FP32 is switched off; 128-bit LDS
+# reads with 16 wavefronts per CU; a device copy) are MEASURED in the same run by the library's micro-benchmarks
+# (binding.csrk_microbench) and reported as `measured_peaks`; the frac_*_measured fields divide by them.
 
 KIND = {1: "spmm", 2: "sddmm", 3: "fusedmm"}
 
 
 def hbm_traffic_from_profiles(workload: str, kernel_key: str):
-    """HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc
-    (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel); read from the committed summary
-    profiles/hbm_traffic_<workload>.json if present, else None."""
+    """HBM bytes per launch of the dominant kernel as measured by rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled
+    by a copy kernel) in a RECORDED run: counters cannot be read from inside this process, so the figure comes from
+    the committed summary profiles/hbm_traffic_<workload>.json.  Returns (bytes or None, where it came from)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
     try:
         with open(path) as f:
-            return json.load(f).get(kernel_key)
+            rec = json.load(f)
+        return rec.get(kernel_key), f"recorded rocprofv3 --pmc run, profiles/hbm_traffic_{workload}.json (not measured in this run)"
     except (OSError, ValueError):
-        return None
+        return None, "none recorded for this workload"
 
 
 def main():
@@ -73,6 +75,12 @@ def main():
     ap.add_argument("--bf16", action="store_true",
                     help="also time the bfloat16-operand entry points on the same workload, beside the FP32 general "
                          "path they share their kernels with (adds a `bf16_operands` object to the line)")
+    ap.add_argument("--no-microbench", action="store_true",
+                    help="skip the library's machine-rate micro-benchmarks (`measured_peaks` and the frac_*_measured fields)")
+    ap.add_argument("--no-phases", action="store_true",
+                    help="skip the `phases` object (one run of the measuring builds of the 512-column tiled kernels)")
+    ap.add_argument("--no-sddmm-at-scale", action="store_true",
+                    help="skip the `sddmm_at_scale` object (SDDMM alone on this pattern with D = 64 and D = 128)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB before the timed region: "
                          "the known-size kernel that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -151,6 +159,14 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    peaks = None
+    if not args.no_microbench:
+        peaks = {"hbm_copy_GBps": round(binding.csrk_microbench(binding.CSRK_BENCH_HBM_COPY), 1),
+                 "fma_f32_TFLOPs": round(binding.csrk_microbench(binding.CSRK_BENCH_FMA_F32), 2),
+                 "lds_read_b128_TBps": round(binding.csrk_microbench(binding.CSRK_BENCH_LDS_READ), 2),
+                 "note": "measured in this run by the library's own kernels: 1 GiB device copy (read + written "
+                         "bytes), independent plain v_fma_f32 (packed FP32 is off), conflict-free 128-bit LDS reads "
+                         "with 16 wavefronts per CU"}
     first_call_ms = {}
     for name, fn in ops:                       # very first call of each operation: allocates the workspace
         torch.cuda.synchronize()
@@ -199,21 +215,27 @@ def main():
             "first_call_wall_ms": round(first_call_ms[name], 3),
             "gflops_avg": round(flops[name] / avg / 1e6, 1), "gflops_best": round(flops[name] / mn / 1e6, 1),
             "frac_fp32_peak": round(tf / FP32_VECTOR_PEAK_TFLOPS, 4),
-            "frac_fma_ceiling": round(tf / FP32_FMA_CEILING_TFLOPS, 4),
             "hbm_algorithmic_bytes": int(hbm_bytes[name]),
             "frac_hbm_peak": round(hbm_bytes[name] / avg / 1e6 / HBM_PEAK_GBS, 4),
             "gathered_TBps": round(gather_bytes[name] / avg / 1e9, 2),
-            "frac_lds_read_measured": round(gather_bytes[name] / avg / 1e9 / LDS_READ_MEASURED_TBS, 4),
         }
+        if peaks:
+            op_report[name]["frac_fma_measured"] = round(tf / peaks["fma_f32_TFLOPs"], 4)
+            op_report[name]["frac_hbm_copy_measured"] = round(hbm_bytes[name] / avg / 1e6 / peaks["hbm_copy_GBps"], 4)
+            op_report[name]["frac_lds_read_measured"] = round(gather_bytes[name] / avg / 1e9 / peaks["lds_read_b128_TBps"], 4)
     # dominant kernel = the one the step spends most time in
     dom = max(per_op, key=lambda k: float(np.mean(per_op[k])))
     dom_ms = float(np.mean(per_op[dom]))
     achieved = flops[dom] / dom_ms / 1e9      # TFLOP/s
+    traffic, traffic_source = hbm_traffic_from_profiles(args.workload, dom)
     roofline = {
         "kernel": dom, "bound": "alu", "achieved": round(achieved, 3), "peak": FP32_VECTOR_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4),
-        "traffic": hbm_traffic_from_profiles(args.workload, dom),
+        "traffic": traffic, "traffic_source": traffic_source,
         "flops_per_launch": flops[dom], "avg_launch_ms": round(dom_ms, 4),
+        "ceiling_note": "peak is the published FP32 vector rate; every multiply-add of the method needs its own 4 "
+                        "bytes of a gathered dense row from LDS, so the kernel's own ceiling is the LDS read rate "
+                        "(measured_peaks.lds_read_b128_TBps / 4 bytes x 2 flops), well below the ALU peak",
     }
 
     result = {
@@ -232,6 +254,42 @@ def main():
         "device": torch.cuda.get_device_name(0),
         "input_gen_s": round(t_gen, 2),
     }
+    if peaks:
+        result["measured_peaks"] = peaks
+        result["roofline"]["frac_of_lds_ceiling"] = round(achieved / (peaks["lds_read_b128_TBps"] / 4.0 * 2.0), 4)
+
+    if not args.no_phases and "fusedmm" in w.ops and w.ops["fusedmm"]["N"] == 512 and w.ops["fusedmm"]["D"] == 64 \
+            and w.M % 64 == 0:
+        # where a wavefront's cycles go in the two 512-column tiled kernels (measuring builds, one run each)
+        ph = {}
+        for opname, opcode in (("spmm", binding.CSRK_OP_SPMM), ("fusedmm", binding.CSRK_OP_FUSEDMM)):
+            cyc, tiles, _ = binding.csrk_tile_phases(opcode, w.M, w.K, 64, 512, rp, ci, v, Af, Bf, Cf, Of)
+            total = sum(cyc)
+            ph[opname] = {"tiles_per_wavefront": tiles, "cycles_per_wavefront": round(total),
+                          "share": {n: round(c / total, 4) for n, c in zip(binding.PHASE_NAMES, cyc) if c > 0}}
+        result["phases"] = ph
+
+    if not args.no_sddmm_at_scale:
+        # SDDMM alone at this size with both dot lengths of the workloads (the paper times SDDMM on its own too)
+        sd = {}
+        Psd = torch.empty((nnz,), dtype=torch.float32, device="cuda")
+        for Dsd in (64, 128):
+            Asd = dev(inputs.normal(0, inputs.STREAM_A, (w.M, Dsd)))
+            Bsd = dev(inputs.normal(0, inputs.STREAM_B, (w.K, Dsd)))
+            call = lambda: binding.sddmm_csr(w.M, w.K, Dsd, rp, ci, v, Asd, Bsd, Psd)
+            call()
+            call()
+            torch.cuda.synchronize()
+            binding.csrk_profile_enable(10)
+            for _ in range(10):
+                call()
+            torch.cuda.synchronize()
+            ms = [t for _, t in binding.csrk_profile_collect(16)]
+            binding.csrk_profile_enable(0)
+            sd[f"D{Dsd}"] = {"ms_min": round(min(ms), 4), "ms_avg": round(sum(ms) / len(ms), 4),
+                             "gflops_avg": round(2.0 * nnz * Dsd / (sum(ms) / len(ms)) / 1e6, 1)}
+            del Asd, Bsd
+        result["sddmm_at_scale"] = sd
 
     if "fusedmm" in w.ops and not args.no_fusion_report:
         # the paper's central claim is the gain from fusing: time SDDMM -> SPMM through a materialised

@@ -281,6 +281,22 @@ csrk_status csrk_tile_phases(int op, int M, int K, int D, int N,
                              hipStream_t stream, double *cycles, int *tiles);
 csrk_status csrk_debug_row_rotation(float *out, hipStream_t stream);
 
+/*
+ * The machine rates the kernels are quoted against, measured on the current device by three small kernels of the
+ * library's own (the paper's roofline, section "Performance Analysis", likewise takes its ceilings from what the
+ * profiler measures on the device): *value receives
+ *   CSRK_BENCH_HBM_COPY  GB/s of a 1 GiB device-to-device copy, bytes read plus bytes written;
+ *   CSRK_BENCH_FMA_F32   TFLOP/s of a loop of independent plain FP32 multiply-adds (no packed FP32), 2 flops each;
+ *   CSRK_BENCH_LDS_READ  TB/s of conflict-free 128-bit LDS reads in the tiled kernels' launch shape (one workgroup
+ *                        of 16 wavefronts per CU, 2 KB rows of a 128 KB tile).
+ * Best of five runs each.  Allocates and frees its buffers, synchronises the device, uses the default stream.
+ * Returns a status only (no message is left for csrk_last_error).
+ */
+#define CSRK_BENCH_HBM_COPY  1
+#define CSRK_BENCH_FMA_F32   2
+#define CSRK_BENCH_LDS_READ  3
+csrk_status csrk_microbench(int kind, double *value);
+
 /* Frees the current device's scratch area of the plain entry points (synchronises the device). */
 csrk_status csrk_release_workspace(void);
 

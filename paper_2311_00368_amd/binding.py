@@ -64,6 +64,7 @@ def load(build_if_missing: bool = True):
     lib.csrk_tile_phases.argtypes = [i, i, i, i, i, p, p, p, p, p, p, p, p, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_int)]
     lib.csrk_debug_row_rotation.argtypes = [p, p]
+    lib.csrk_microbench.argtypes = [i, ctypes.POINTER(ctypes.c_double)]
     lib.csrk_release_workspace.argtypes = []
     lib.csrk_profile_enable.argtypes = [i]
     lib.csrk_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int), i,
@@ -73,7 +74,7 @@ def load(build_if_missing: bool = True):
               lib.csrk_plan_info, lib.spmm_csr_plan, lib.sddmm_csr_plan, lib.fusedmm_csr_plan,
               lib.csrk_profile_enable, lib.csrk_profile_collect, lib.csrk_workspace_bytes, lib.spmm_csr_ws,
               lib.sddmm_csr_ws, lib.fusedmm_csr_ws, lib.csrk_plan_reserve, lib.csrk_tile_phases,
-              lib.csrk_debug_row_rotation, lib.fusedmm_csr_static):
+              lib.csrk_debug_row_rotation, lib.fusedmm_csr_static, lib.csrk_microbench):
         f.restype = ctypes.c_int
     lib.csrk_last_error.restype = ctypes.c_char_p
     lib.csrk_version.restype = ctypes.c_char_p
@@ -342,6 +343,19 @@ def csrk_debug_row_rotation() -> torch.Tensor:
     out = torch.empty((16, 64), dtype=torch.float32, device="cuda")
     _check(load().csrk_debug_row_rotation(ctypes.c_void_p(out.data_ptr()), _stream(out.device)))
     return out
+
+
+CSRK_BENCH_HBM_COPY, CSRK_BENCH_FMA_F32, CSRK_BENCH_LDS_READ = 1, 2, 3
+
+
+def csrk_microbench(kind: int) -> float:
+    """One of the library's machine-rate micro-benchmarks on the current device (see include/csrk.h): GB/s of a
+    device copy, TFLOP/s of plain FP32 multiply-adds, or TB/s of 128-bit LDS reads."""
+    out = ctypes.c_double(0.0)
+    code = load().csrk_microbench(kind, ctypes.byref(out))
+    if code != CSRK_OK:
+        raise CsrkError(code, "csrk_microbench failed")
+    return float(out.value)
 
 
 def csrk_plan_reserve(plan: Plan, max_N: int) -> None:

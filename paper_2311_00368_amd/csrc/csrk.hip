@@ -557,6 +557,8 @@ constexpr int kWideMaxN = 2048;     // widest output the wide tiled kernels take
 bool ktile_shape_ok(const DeviceState &d, int M, int K, int N) {
     const int mode = env_int("CSRK_KTILE", 1);       // 1 auto, 2 force where the kernel can run, 3 off
     if (mode == 3) return false;
+    // the wide tiled kernels read the dense operand through a buffer descriptor, whose extent is a 32-bit byte count
+    if ((long long)K * N * 4 >= (1ll << 32)) return false;
     if (N % 4 != 0 || N > kWideMaxN || N <= 128) return mode == 2 && N % 4 == 0 && N <= kWideMaxN;
     if (mode == 2) return true;
     // Measured cross-over with the general path (whose gathers run at L2 speed while the dense operand fits an
@@ -821,9 +823,9 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
     // how much of the next tile is prefetched into registers: as many of a thread's loads as still fit in 128
-    // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 3 of 8 for two)
+    // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 6 of 8 for two)
     constexpr int kPer = KT * T * 64 / kTileThreads;
-    constexpr int kPrefetch = T == 2 ? 3 : kPer - 1;
+    constexpr int kPrefetch = T == 2 ? 6 : kPer - 1;
     auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch, LIVE>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
@@ -1849,7 +1851,7 @@ csrk_status csrk_tile_phases(int op, int M, int K, int D, int N, const int32_t *
             }
         } else {
             using L = FusedTileLds<2, 64, 4, 32>;
-            auto kern = fused_ktile_kernel<2, 64, 4, 32, 3, 4, true>;
+            auto kern = fused_ktile_kernel<2, 64, 4, 32, 6, 4, true>;
             e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
             if (e == hipSuccess) {
                 hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, D, N, N, rowptr, colidx,

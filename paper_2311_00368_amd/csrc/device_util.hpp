@@ -11,6 +11,10 @@ namespace csrk {
 
 constexpr int kWave = 64;
 
+// four floats as one 128-bit register value: loads and stores of it are plain moves (an array of HIP's float4
+// structs filled through a casted pointer can end up copied through private memory instead)
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -61,10 +65,6 @@ __device__ __forceinline__ void fma_row_rotated(float &acc, float a, float b) {
     }
 }
 
-// four floats as one 128-bit register value: loads and stores of it are plain moves (an array of HIP's float4
-// structs filled through a casted pointer can end up copied through private memory instead)
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 // VEC consecutive floats; VEC a multiple of 4: 128-bit accesses (address must be 16-byte aligned).
 template <int VEC>
 __device__ __forceinline__ void load_vec(const float *p, float (&d)[VEC]) {
@@ -112,6 +112,24 @@ __device__ __forceinline__ void store_vec(float *p, const float (&d)[VEC]) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) p[i] = d[i];
     }
+}
+
+// A dense operand seen through a buffer descriptor: loads take the descriptor and a scalar byte offset (the part of
+// the address that is the same for the whole wavefront: tile and load number) from scalar registers and ONE 32-bit
+// vector register with the lane's own byte offset.  Plain global loads need a 64-bit address per lane and load, and
+// since a thread's offsets inside a tile never change the compiler keeps all of them - two vector registers per load
+// of a tile - alive through the whole kernel: 16 registers out of 128 in the 512-column kernels.  Loads past `bytes`
+// return zeros instead of faulting, which is what the rows past K of a last, partial tile should read as.
+// `bytes` must be below 4 GB (the launcher checks).
+struct DenseView {
+    __amdgpu_buffer_rsrc_t rsrc;
+};
+__device__ __forceinline__ DenseView dense_view(const void *base, unsigned bytes) {
+    // word 3: 32-bit data format, no swizzle (the value the gfx9 family's untyped buffer loads expect)
+    return DenseView{__builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000)};
+}
+__device__ __forceinline__ f32x4 load_f32x4(const DenseView &v, unsigned lane_bytes, unsigned uniform_bytes) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(v.rsrc, lane_bytes, uniform_bytes, 0));
 }
 
 // Element number `lane` behind a wave-uniform pointer, for a lane-wide load of a chunk of colidx or vals: the

@@ -332,31 +332,23 @@ __global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kerne
     f32x4 stage[kPer];
     // Thread t copies float4 number (t % kRow4) of tile rows t / kRow4, + kStep, + 2 kStep, ...: its
     // offset inside a tile never changes, so a tile costs this thread kPer loads off a uniform
-    // base pointer with a 32-bit offset of its own.  Threads past the width of a narrower launch re-read the
+    // scalar base with a 32-bit offset of its own.  Threads past the width of a narrower launch re-read the
     // row's last float4 (those LDS columns are only ever read by lanes whose accumulators are not stored), rows
-    // past K in the last tile re-read row K-1 (no entry points at them): every thread issues every load, under
+    // past K in the last tile read as zeros (no entry points at them): every thread issues every load, under
     // no condition.
     constexpr int kStep = kThreads / kRow4;      // tile rows covered by one round of loads
     const int my_kk = threadIdx.x / kRow4, my_c4 = threadIdx.x % kRow4;
     const int col4 = my_c4 < n4 ? my_c4 : n4 - 1;
     const unsigned my_off = ((unsigned)my_kk * (unsigned)ld4 + (unsigned)col4) * 16u;
-    const size_t step_bytes = (size_t)kStep * ld4 * 16;
+    const unsigned step_bytes = (unsigned)kStep * (unsigned)ld4 * 16u;
+    // rows of the operand from this launch's first column on (rows past K read as zeros)
+    const DenseView cview = dense_view(Cmat, (unsigned)(((size_t)K * ld - (ld - N)) * 4));
     // loads number [I0, I1) of this thread for the tile that starts at column k0
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
-        const char *base = reinterpret_cast<const char *>(Cmat);
-        if (k0 + KT <= K) {
-            const char *tile = base + (size_t)k0 * ld4 * 16;   // uniform
+        const unsigned tile = (unsigned)k0 * (unsigned)ld4 * 16u;      // uniform
 #pragma unroll
-            for (int i = I0; i < I1; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(tile + i * step_bytes + my_off);
-        } else {                                      // last, partial tile
-#pragma unroll
-            for (int i = I0; i < I1; ++i) {
-                int k = k0 + i * kStep + my_kk;
-                k = k < K ? k : K - 1;
-                stage[i] = *reinterpret_cast<const f32x4 *>(base + ((size_t)k * ld4 + col4) * 16);
-            }
-        }
+        for (int i = I0; i < I1; ++i) stage[i] = load_f32x4(cview, my_off, tile + i * step_bytes);
     };
     auto commit = [&]() {
         f32x4 *dst = reinterpret_cast<f32x4 *>(ct);

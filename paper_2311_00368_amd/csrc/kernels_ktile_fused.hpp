@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     constexpr int kRow4 = T * 64;
     constexpr int kPer = KT * kRow4 / kTileThreads;
     constexpr int kPerB = (KT * 16 + kTileThreads - 1) / kTileThreads;
-    static_assert(PF >= 0 && PF <= kPer, "prefetch depth beyond the tile");
+    static_assert(PF >= -1 && PF <= kPer, "prefetch depth beyond the tile");
     f32x4 stage[kPer];
     f32x4 stageb[kPerB];
     constexpr int kStep = kTileThreads / kRow4;      // tile rows covered by one round of loads
@@ -114,35 +114,34 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     // tile re-read row K-1 (no entry points at them).
     const int col4 = my_c4 < n4 ? my_c4 : n4 - 1;
     const unsigned my_off = ((unsigned)my_kk * (unsigned)ld4 + (unsigned)col4) * 16u;
-    const size_t step_bytes = (size_t)kStep * ld4 * 16;
+    const unsigned step_bytes = (unsigned)kStep * (unsigned)ld4 * 16u;
+    // the operands through buffer descriptors: scalar tile offset + one 32-bit offset per thread, rows past K read
+    // as zeros (see DenseView)
+    const DenseView cview = dense_view(Cmat, (unsigned)(((size_t)K * ld - (ld - N)) * 4));
+    const DenseView bview = dense_view(Bmat, (unsigned)((size_t)K * D * 4));
     auto issue = [&](int k0, auto i0c, auto i1c) {
         constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
-        const char *base = reinterpret_cast<const char *>(Cmat);
-        if (k0 + KT <= K) {
-            const char *tile = base + (size_t)k0 * ld4 * 16;   // uniform
+        const unsigned tile = (unsigned)k0 * (unsigned)ld4 * 16u;      // uniform
 #pragma unroll
-            for (int i = I0; i < I1; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(tile + i * step_bytes + my_off);
-        } else {                                      // last, partial tile
-#pragma unroll
-            for (int i = I0; i < I1; ++i) {
-                int kq = k0 + i * kStep + my_kk;
-                kq = kq < K ? kq : K - 1;
-                stage[i] = *reinterpret_cast<const f32x4 *>(base + ((size_t)kq * ld4 + col4) * 16);
-            }
-        }
+        for (int i = I0; i < I1; ++i) stage[i] = load_f32x4(cview, my_off, tile + i * step_bytes);
     };
     // the tile of B: rows of D floats, zero-padded to 64 in LDS (the score stage walks all 16 pieces of a row)
+    const int d4 = D >> 2;
+    unsigned my_boff[kPerB];
+    bool my_bpad[kPerB];
+#pragma unroll
+    for (int i = 0; i < kPerB; ++i) {
+        const int e = i * kTileThreads + threadIdx.x;
+        const int c4 = e & 15;
+        my_bpad[i] = c4 >= d4;
+        my_boff[i] = (unsigned)((e >> 4) * d4 + (c4 < d4 ? c4 : d4 - 1)) * 16u;
+    }
     auto issue_b = [&](int k0) {
-        const int d4 = D >> 2;
-        const f32x4 *tileb = reinterpret_cast<const f32x4 *>(Bmat) + (size_t)k0 * d4;     // uniform
+        const unsigned tile = (unsigned)k0 * (unsigned)d4 * 16u;       // uniform
 #pragma unroll
         for (int i = 0; i < kPerB; ++i) {
-            const int e = i * kTileThreads + threadIdx.x;
-            int kk = e >> 4;
-            kk = k0 + kk < K ? kk : K - 1 - k0;
-            const int c4 = e & 15;
-            stageb[i] = lane_elem(tileb, (unsigned)(kk * d4 + (c4 < d4 ? c4 : d4 - 1)) * 16u);
-            if (c4 >= d4) stageb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            stageb[i] = load_f32x4(bview, my_boff[i], tile);
+            if (my_bpad[i]) stageb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
     auto commit = [&]() {
@@ -157,19 +156,27 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
         }
     };
     using I0 = std::integral_constant<int, 0>;
-    using IPF = std::integral_constant<int, PF>;
+    // PF = -1: every load of the next tile goes out at the END of the current one, ahead of the barrier that ends it,
+    // into registers the arithmetic has just let go of
+    constexpr bool kTail = PF < 0;
+    using IPF = std::integral_constant<int, (kTail ? 0 : PF)>;
     using IEND = std::integral_constant<int, kPer>;
     constexpr bool kAllAhead = PF == kPer;
 
     if (ks.kb < ks.ke) {
-        if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
-        if constexpr (kAllAhead) issue_b(ks.kb);
+        if constexpr (kTail) {
+            issue(ks.kb, I0{}, IEND{});
+            issue_b(ks.kb);
+        } else {
+            if constexpr (PF > 0) issue(ks.kb, I0{}, IPF{});
+            if constexpr (kAllAhead) issue_b(ks.kb);
+        }
     }
     clk.start();
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         clk.lap(kPhBarrier1);
-        if constexpr (!kAllAhead) {         // what no register could be spared for during the previous tile's arithmetic
+        if constexpr (!kAllAhead && !kTail) {   // what no register could be spared for during the previous tile's arithmetic
             issue(k0, IPF{}, IEND{});
             issue_b(k0);
             clk.lap(kPhIssue);
@@ -383,6 +390,13 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             }
         }
         clk.lap(kPhReload);
+        if constexpr (kTail) {
+            if (k0 + KT < ks.ke) {
+                issue(k0 + KT, I0{}, IEND{});
+                issue_b(k0 + KT);
+            }
+            clk.lap(kPhIssue);
+        }
     }
     clk.store(tim, kTileWaves, wave, lane);
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
