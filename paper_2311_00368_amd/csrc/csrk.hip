@@ -823,9 +823,9 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
     // how much of the next tile is prefetched into registers: as many of a thread's loads as still fit in 128
-    // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 6 of 8 for two)
+    // registers beside the accumulators (5 of 6 for one 256-wide piece of output, 5 of 8 for two)
     constexpr int kPer = KT * T * 64 / kTileThreads;
-    constexpr int kPrefetch = T == 2 ? 6 : kPer - 1;
+    constexpr int kPrefetch = T == 2 ? 5 : kPer - 1;
     auto kern = fused_ktile_kernel<T, KT, ROWS, SL, kPrefetch, LIVE>;
     static bool attr_set[kMaxDevices] = {};
     int dev = 0;
@@ -1851,7 +1851,7 @@ csrk_status csrk_tile_phases(int op, int M, int K, int D, int N, const int32_t *
             }
         } else {
             using L = FusedTileLds<2, 64, 4, 32>;
-            auto kern = fused_ktile_kernel<2, 64, 4, 32, 6, 4, true>;
+            auto kern = fused_ktile_kernel<2, 64, 4, 32, 5, 4, true>;
             e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
             if (e == hipSuccess) {
                 hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, D, N, N, rowptr, colidx,

@@ -54,6 +54,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     constexpr int kRowBytes = L::kRowFloats * 4;
     constexpr int kGroupsPerRow = 4 / ROWS;
     constexpr int kPass = 16 * kGroupsPerRow;      // entries of a row scored per pass
+    constexpr int kExtra = 8;                      // entries beyond a pass that are scored one by one instead of by another pass
     const int lane = lane_id();
     const int wave = uniform(threadIdx.x >> 6);
     float *ct = lds;
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 ent[r * SL + lane - part] = make_int2(kc[r], __builtin_bit_cast(int, vc[r]));
         }
 
-        for (int base = 0; base < maxcnt; base += kPass) {
+        for (int base = 0; base < maxcnt;) {
             // ---- score stage: this lane's entry of this pass
             clk.lap(kPhCompute);
             {
@@ -273,13 +274,35 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 });
                 if (on) reinterpret_cast<int *>(mine)[1] = __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * dot);
             }
+            // A pass scores kPass entries per row.  The few entries a row has beyond that (a row of a 20 % dense
+            // matrix has 13 +- 3 entries in a 64-column tile, a pass takes 16) are not worth another pass - a chain
+            // of 16 LDS reads and 64 multiply-adds for the whole wavefront, which also makes the wavefronts that need
+            // one arrive late at the tile's barrier: up to kExtra of them per row are scored one at a time instead,
+            // each by the 16 lanes of its row's group (lane i: piece i of the row of B times its piece of A, then a
+            // sum over the group), the groups working side by side.
+            int pass_end = base + kPass;
+            if (maxcnt > pass_end && maxcnt <= pass_end + kExtra) {
+                for (int idx = pass_end; idx < maxcnt; ++idx) {
+                    const bool on = idx < my_cnt;
+                    int2 *mine = ent + my_r * SL + (on ? idx : 0);
+                    const int2 kv = *mine;
+                    float bq[4];
+                    load_vec<4>(bt + (on ? kv.x - k0 : 0) * 64 + i16 * 4, bq);
+                    float part = a[0] * bq[0];
+#pragma unroll
+                    for (int v = 1; v < 4; ++v) part = fmaf(a[v], bq[v], part);
+                    part = group_sum<16>(part);
+                    if (on && my_first == 0) reinterpret_cast<int *>(mine)[1] = __builtin_bit_cast(int, __builtin_bit_cast(float, kv.y) * part);
+                }
+                pass_end = maxcnt;
+            }
             if constexpr (TIMED) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             clk.lap(kPhScore);
-            // ---- accumulate stage: entries [base, base + kPass) of every row
+            // ---- accumulate stage: entries [base, pass_end) of every row
 #pragma unroll
             for (int r = 0; r < ROWS; ++r) {
                 const int2 *e = ent + r * SL;
-                const int lim = cnts[r] < base + kPass ? cnts[r] : base + kPass;
+                const int lim = cnts[r] < pass_end ? cnts[r] : pass_end;
                 auto batch = [&](int t, auto count) {
                     constexpr int CNT = decltype(count)::value;
                     float c[CNT][T][4];
@@ -318,6 +341,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
                 }
                 if (lim - t >= 1) batch(t, std::integral_constant<int, 1>{});
             }
+            base = pass_end;
         }
 
         }   // part
