@@ -11,11 +11,20 @@ workload is the 16384 x 16384, 20 %-dense configuration the benchmark spec's target is
   value        GFLOP/s of the whole step, flops = 2*nnz*N (SPMM) + 2*nnz*D (SDDMM)
                + 2*nnz*(D+N) (FusedMM)
   ops          per operation, from one HIP-event pair around all kernels of a call: GFLOP/s (mean, median, best), the
-               fractions of the FP32 peak, of the plain-FMA ceiling and of HBM bandwidth (algorithmic
-               bytes), the rate at which gathered dense rows reach the ALUs (nnz * width * 4 bytes / time)
-               against the micro-benchmarked LDS read rate, one cold run (caches flushed by writing
-               a 1 GiB buffer) and the wall time of the very first call (workspace allocation included)
-  roofline     the dominant kernel against MI355X's FP32 vector peak (157.3 TFLOP/s)
+               fractions of the published FP32 peak and HBM bandwidth (algorithmic bytes) and of the three machine
+               rates measured in this run (frac_*_measured), the rate at which gathered dense rows reach the ALUs
+               (nnz * width * 4 bytes / time), one cold run (caches flushed by writing a 1 GiB buffer) and the wall
+               time of the very first call (workspace allocation included)
+  measured_peaks  the library's micro-benchmarks (csrk_microbench), run in this process before the timed region:
+               device copy (GB/s), independent FP32 multiply-adds acc += x * y without packed FP32 (TFLOP/s), and
+               conflict-free 128-bit LDS reads with 16 wavefronts per CU (TB/s)
+  roofline     the dominant kernel against MI355X's FP32 vector peak (157.3 TFLOP/s); `traffic` and
+               `traffic_source`: HBM bytes per launch from a recorded rocprofv3 --pmc run (profiles/), since
+               counters cannot be read from inside the process; `frac_of_lds_ceiling`: against the rate the
+               measured LDS read bandwidth allows (one 4-byte LDS operand per multiply-add)
+  phases       where the wavefronts of the dominant kernel spend their cycles (csrk_tile_phases: the measuring
+               build of the same kernel, shares of the summed phase counters)
+  sddmm_at_scale  SDDMM at the benchmark size with D = 64 and D = 128
   cpu_baseline the FP64 CPU oracle timed on a sample of the rows of the same workload
   planned      the same three calls through a plan (pattern analysed once, outside the timing), timed after
                the main region and not part of `value`
@@ -36,7 +45,7 @@ if ROOT not in sys.path:
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X, published: 256 CUs x 2.4 GHz x 256 flop/clk/CU
 HBM_PEAK_GBS = 8000.0             # MI355X, published
-# The rates this build's instruction mix can reach (plain v_fma_f32, since packed FP32 is switched off; 128-bit LDS
+# The rates this build's instruction mix can reach (plain multiply-adds, since packed FP32 is switched off; 128-bit LDS
 # reads with 16 wavefronts per CU; a device copy) are MEASURED in the same run by the library's micro-benchmarks
 # (binding.csrk_microbench) and reported as `measured_peaks`; the frac_*_measured fields divide by them.
 

@@ -1,5 +1,6 @@
 // Micro-benchmarks of the three machine rates the kernels are measured against (csrk_microbench in include/csrk.h):
-// device-to-device copy (HBM), a loop of independent plain FP32 multiply-adds (vector ALU without packed FP32),
+// device-to-device copy (HBM), a loop of independent plain FP32 multiply-adds acc += x * y (vector ALU without packed
+// FP32),
 // and a loop of conflict-free 128-bit LDS reads with 16 wavefronts per CU (the tiled kernels' launch shape).
 // They follow the paper's practice of quoting its kernels against measured device peaks (section "Performance
 // Analysis": the roofline's ceilings are what the profiler measured on the device, not datasheet figures).
@@ -18,15 +19,20 @@ __global__ __launch_bounds__(256) void copy_kernel(const f32x4 *__restrict__ src
         dst[i] = src[i];
 }
 
-// 32 independent accumulators per lane, one v_fma_f32 each per iteration (scale and addend are run-time values, so
-// nothing folds); 2 * 32 * iters flops per lane
+// 32 independent accumulators per lane, each the target of a multiply-add whose two factors are run-time values
+// (acc += x * y, the form the kernels' inner loops have: the accumulator is both addend and result, which the
+// hardware encodes in the short two-operand multiply-add); the factors change from round to round so that nothing
+// folds.  2 * 32 * iters flops per lane.
 __global__ __launch_bounds__(256) void fma_kernel(float *out, int iters, float scale, float addend) {
     float acc[32];
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = (float)(threadIdx.x + i);
+    float x = scale, y = addend;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) acc[i] = fmaf(acc[i], scale, addend);
+        for (int i = 0; i < 32; ++i) acc[i] = fmaf(x, y, acc[i]);
+        x = -x;
+        y += 1e-3f;
     }
     float s = 0.f;
 #pragma unroll
