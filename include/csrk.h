@@ -201,7 +201,17 @@ csrk_status fusedmm_csr_ws(int M, int K, int D, int N,
  * since has undefined results.  *out (host pointer) receives the plan, owned by the
  * caller until csrk_plan_destroy (NULL is accepted there).  A plan belongs to the
  * device that was current when it was made; it holds 32 bytes of device memory (plus the
- * workspace that csrk_plan_reserve may add).
+ * workspace that csrk_plan_reserve may add, and the schedule described next).
+ * Uneven rows (ordered columns, longest row > 2 * mean + 64; at least 256 rows and
+ * K >= 1024): the plan also holds a SCHEDULE for the LDS-tiled kernels - rowptr is
+ * read back to the host, the rows are sorted by length into blocks of 64 and every
+ * block's K is cut into as many ranges as its share of the work asks for (the
+ * paper's NT work-items per row, section "SDDMM", chosen per block of rows); about
+ * 4 * M + 32 * (M / 64 + CUs) bytes of device memory.  Planned SPMM and FusedMM
+ * (D <= 64) calls with outputs of 132 to 512 columns then run the tiled kernels over
+ * that table instead of dealing the stored entries out in equal shares; partial
+ * rows of cut blocks go through the scratch area and are added up in range order
+ * (same bits every run).
  * csrk_plan_info reports what was found (any of the three host pointers may be
  * NULL).  The planned calls take the pattern and M, K from the plan; all other
  * arguments are as in spmm_csr / sddmm_csr / fusedmm_csr.

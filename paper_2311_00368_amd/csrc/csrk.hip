@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -29,6 +30,19 @@ struct csrk_plan_s {
     int32_t *dflags;          // 8 device words laid out like the per-call flags: {0, 1, 0, even, ...}
     void *ws;                 // scratch owned by the plan (csrk_plan_reserve), or NULL
     size_t ws_bytes;
+    // Schedule for uneven rows (patterns that are sorted but not `even`): rows sorted by length and cut into blocks
+    // of 64 (4 per wavefront of a tiled kernel), every block's K cut into as many ranges as its share of the work
+    // asks for.  All arrays live in one device allocation (`sched_mem`).
+    struct Sched {
+        int n_items = 0;          // workgroups: (block, range) pairs, heaviest first
+        int n_comb = 0;           // blocks whose K is cut (their partial rows are added up afterwards)
+        int n_slots = 0;          // partial-row slots (one per item of a cut block), kSchedRows rows each
+        const int32_t *perm = nullptr;    // rows in schedule order, padded with M to whole blocks
+        const int4 *items = nullptr;      // block, range, ranges, first slot of the range
+        const int4 *comb = nullptr;       // block, first slot, ranges
+    } sched;
+    void *sched_mem = nullptr;
+    bool has_sched = false;
 };
 
 namespace {
@@ -703,6 +717,15 @@ bool narrow_shape_ok(const DeviceState &d, int M, int K, int N, bool fused) {
     return rows_per_cu >= 12 && (long long)M * K >= (8ll << 20);
 }
 
+// A plan's schedule as a launch sees it (see csrk_plan_s::Sched): the tiled kernels then take their rows and K
+// ranges from the schedule instead of from the grid.
+struct SchedPart {
+    const int32_t *perm;
+    const int4 *items;
+    int n_items;
+    size_t partial_offset;      // floats into the scratch area where the partial rows start
+};
+
 // tile height of the narrow SPMM kernel: as high as LDS allows with the 128-entry look-ahead in mind (256 rows
 // of 128 columns, 384 of 64 or 32)
 template <int G>
@@ -712,7 +735,8 @@ constexpr int narrow_kt() {
 
 template <int G, int ROWS>
 csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int N, const int32_t *rp,
-                               const int32_t *ci, const float *v, const float *C, float *O, int ksplit = 1) {
+                               const int32_t *ci, const float *v, const float *C, float *O, int ksplit = 1,
+                               const SchedPart *sp = nullptr) {
     constexpr int KT = narrow_kt<G>();
     using L = NarrowLds<G, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
@@ -727,8 +751,9 @@ csrk_status launch_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, rp, ci, v, C,
-                       O, tile_flags(d), d.head, d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, sp ? dim3(sp->n_items) : dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st,
+                       M, K, N, rp, ci, v, C, O, tile_flags(d), d.head + (sp ? sp->partial_offset : 0), d.inline_density,
+                       other_flags(d), sp ? sp->perm : (const int32_t *)nullptr, sp ? sp->items : (const int4 *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -762,7 +787,8 @@ csrk_status launch_narrow(DeviceState &d, hipStream_t st, int M, int K, int N, c
 
 template <int T, int KT, int ROWS>
 csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int N, int ld, int col0, const int32_t *rp,
-                              const int32_t *ci, const float *v, const float *B, float *O, int ksplit = 1) {
+                              const int32_t *ci, const float *v, const float *B, float *O, int ksplit = 1,
+                              const SchedPart *sp = nullptr) {
     using L = KTileLds<T, KT>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
@@ -775,9 +801,10 @@ csrk_status launch_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int 
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * ROWS;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, N, ld, rp, ci, v,
-                       B + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d),
-                       (long long *)nullptr);
+    hipLaunchKernelGGL(kern, sp ? dim3(sp->n_items) : dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st,
+                       M, K, N, ld, rp, ci, v, B + col0, O + col0, tile_flags(d),
+                       d.head + col0 + (sp ? sp->partial_offset : 0), d.inline_density, other_flags(d), (long long *)nullptr,
+                       sp ? sp->perm : (const int32_t *)nullptr, sp ? sp->items : (const int4 *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -818,7 +845,7 @@ bool fused_three_rows(const DeviceState &d, int M, int N) {
 template <int T, int KT, int ROWS, int SL, int LIVE = ROWS>
 csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, int ld, int col0,
                                     const int32_t *rp, const int32_t *ci, const float *v, const float *A, const float *B,
-                                    const float *C, float *O, int ksplit = 1) {
+                                    const float *C, float *O, int ksplit = 1, const SchedPart *sp = nullptr) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     static_assert(L::kBytes <= 160 * 1024, "tile does not fit the 160 KB of LDS of a gfx950 CU");
     static_assert((KT * T * 64) % kTileThreads == 0, "the staging loop copies whole rounds of 1024 float4");
@@ -835,9 +862,10 @@ csrk_status launch_fused_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * LIVE;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, ld, rp, ci,
-                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d),
-                       (long long *)nullptr);
+    hipLaunchKernelGGL(kern, sp ? dim3(sp->n_items) : dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st,
+                       M, K, D, N, ld, rp, ci, v, A, B, C + col0, O + col0, tile_flags(d),
+                       d.head + col0 + (sp ? sp->partial_offset : 0), d.inline_density, other_flags(d), (long long *)nullptr,
+                       sp ? sp->perm : (const int32_t *)nullptr, sp ? sp->items : (const int4 *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -877,7 +905,8 @@ constexpr int fused_narrow_kt() {
 template <int G, int ROWS, int DMAX, int LIVE = ROWS>
 csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int K, int D, int N, const int32_t *rp,
                                      const int32_t *ci, const float *v, const float *A, const float *B,
-                                     const float *C, float *O, int ksplit = 1, int ld = 0, int col0 = 0) {
+                                     const float *C, float *O, int ksplit = 1, int ld = 0, int col0 = 0,
+                                     const SchedPart *sp = nullptr) {
     if (ld == 0) ld = N;        // otherwise: columns [col0, col0 + N) of C and O, whose rows are `ld` floats long
     constexpr int KT = fused_narrow_kt<G, DMAX>();
     constexpr int SL = 64;
@@ -896,8 +925,10 @@ csrk_status launch_fused_narrow_rows(DeviceState &d, hipStream_t st, int M, int 
         attr_set[dev] = true;
     }
     const int rb = kTileWaves * LIVE;
-    hipLaunchKernelGGL(kern, dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st, M, K, D, N, ld, rp, ci,
-                       v, A, B, C + col0, O + col0, tile_flags(d), d.head + col0, d.inline_density, other_flags(d));
+    hipLaunchKernelGGL(kern, sp ? dim3(sp->n_items) : dim3((M + rb - 1) / rb, ksplit), dim3(kTileThreads), L::kBytes, st,
+                       M, K, D, N, ld, rp, ci, v, A, B, C + col0, O + col0, tile_flags(d),
+                       d.head + col0 + (sp ? sp->partial_offset : 0), d.inline_density, other_flags(d),
+                       sp ? sp->perm : (const int32_t *)nullptr, sp ? sp->items : (const int4 *)nullptr);
     CSRK_HIP(hipGetLastError());
     if (ksplit > 1) d.pending_ksplit = ksplit;     // the call's last kernel adds the partial outputs (launch_combine)
     return CSRK_OK;
@@ -938,6 +969,156 @@ csrk_status launch_fused_narrow(DeviceState &d, hipStream_t st, int M, int K, in
                                 float *O) {
     if (D > 64) return launch_fused_narrow_d<128>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
     return launch_fused_narrow_d<64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O);
+}
+
+// --- planned calls on uneven rows: the schedule made by csrk_plan_create (csrk_plan_s::Sched) --------------------
+// Cost of a workgroup in units of one stored entry's work: it stages every dense row of its K range whatever the
+// rows of S hold, which costs about as much as kSchedRowCost entries per dense row, plus its entries.  The aim is
+// kSchedPerCu workgroups per CU, the heaviest first, none cut finer than kSchedMinSegment columns of K.
+// Measured on 8192 x 8192, log-normal row lengths (mean 10 % of K, sigma 1), FusedMM D = 64 N = 512 / SPMM N = 512,
+// in us: row cost 16 with 2 per CU 536 / 428; 8 with 3: 576 / 492; 16 with 3: 590 / 467; 8 with 2: 637 / 502;
+// 32 with 3: 616 / 505; 4 with 3: 610 / 495; ranges down to 256 columns: 609-775 / 488-673.  A second class of
+// blocks of 16 rows (one per wavefront) for the longest rows, so that they could be cut finer, only cost time
+// (677 / 550 with 8 and 3): the one-row kernels pay the per-tile barriers for a quarter of the work.
+constexpr int kSchedRows = 64;
+constexpr double kSchedRowCost = 16.0;
+constexpr int kSchedMinSegment = 512;
+constexpr int kSchedPerCu = 2;
+
+struct SchedHost {
+    std::vector<int32_t> perm;
+    std::vector<int4> items, comb;
+    int n_slots = 0;
+};
+
+// rows (by length, longest first) -> blocks of kSchedRows -> (block, range) items
+void build_schedule(int M, int K, const std::vector<int32_t> &rp, int cus, SchedHost &out) {
+    std::vector<int32_t> order(M);
+    for (int i = 0; i < M; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return rp[a + 1] - rp[a] > rp[b + 1] - rp[b]; });
+    const int blocks = (M + kSchedRows - 1) / kSchedRows;
+    const int max_seg = K / kSchedMinSegment > 1 ? K / kSchedMinSegment : 1;
+    const double total = (double)rp[M] + kSchedRowCost * (double)K * (double)blocks;
+    const double target = total / ((double)cus * kSchedPerCu);
+    struct Item {
+        int4 it;
+        double cost;
+    };
+    std::vector<Item> items;
+    out.perm.assign((size_t)blocks * kSchedRows, M);
+    for (int i = 0; i < M; ++i) out.perm[i] = order[i];
+    for (int b = 0; b < blocks; ++b) {
+        double work = 0;
+        for (int i = 0; i < kSchedRows; ++i) {
+            const int32_t row = out.perm[(size_t)b * kSchedRows + i];
+            if (row < M) work += (double)(rp[row + 1] - rp[row]);
+        }
+        const double cost = kSchedRowCost * (double)K + work;
+        int nseg = (int)(cost / target + 0.5);
+        nseg = nseg < 1 ? 1 : (nseg > max_seg ? max_seg : nseg);
+        int slot0 = 0;
+        if (nseg > 1) {
+            slot0 = out.n_slots;
+            out.n_slots += nseg;
+            out.comb.push_back(make_int4(b, slot0, nseg, 0));
+        }
+        for (int sgm = 0; sgm < nseg; ++sgm) items.push_back(Item{make_int4(b, sgm, nseg, slot0 + sgm), cost / nseg});
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Item &x, const Item &y) { return x.cost > y.cost; });
+    for (const Item &i : items) out.items.push_back(i.it);
+}
+
+// the plan's device copy of the schedule: one allocation, the int4 tables first
+csrk_status upload_schedule(csrk_plan_s *plan, const SchedHost &h, hipStream_t stream) {
+    const size_t off_comb = h.items.size() * sizeof(int4);
+    const size_t off_perm = off_comb + h.comb.size() * sizeof(int4);
+    const size_t bytes = off_perm + h.perm.size() * sizeof(int32_t);
+    std::vector<char> image(bytes, 0);
+    memcpy(image.data(), h.items.data(), h.items.size() * sizeof(int4));
+    if (!h.comb.empty()) memcpy(image.data() + off_comb, h.comb.data(), h.comb.size() * sizeof(int4));
+    memcpy(image.data() + off_perm, h.perm.data(), h.perm.size() * sizeof(int32_t));
+    void *mem = nullptr;
+    if (hipMalloc(&mem, bytes) != hipSuccess) return fail(CSRK_WORKSPACE, "csrk_plan_create: cannot allocate %zu bytes for the schedule", bytes);
+    if (hipMemcpyAsync(mem, image.data(), bytes, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
+        (void)hipFree(mem);
+        return fail(CSRK_HIP_ERROR, "csrk_plan_create: copying the schedule failed");
+    }
+    plan->sched_mem = mem;
+    char *base = static_cast<char *>(mem);
+    plan->sched.n_items = (int)h.items.size();
+    plan->sched.n_comb = (int)h.comb.size();
+    plan->sched.n_slots = h.n_slots;
+    plan->sched.items = reinterpret_cast<const int4 *>(base);
+    plan->sched.comb = reinterpret_cast<const int4 *>(base + off_comb);
+    plan->sched.perm = reinterpret_cast<const int32_t *>(base + off_perm);
+    plan->has_sched = true;
+    return CSRK_OK;
+}
+
+// floats of scratch the partial rows of a scheduled call take, for rows of `ld` floats
+size_t sched_partial_floats(const csrk_plan_s *plan, int ld) {
+    return (size_t)plan->sched.n_slots * (size_t)kSchedRows * (size_t)ld;
+}
+
+// A planned call takes the schedule if the plan has one, the shape is one the tiled kernels serve in one launch,
+// the pattern is dense enough for them, and the scratch at hand holds the partial rows.
+// Measured on the pattern above, planned FusedMM D = 64 / SPMM, schedule against equal shares of the stored
+// entries: N = 512 536 / 428 us against 1601 / 1370, N = 256 347 / 256 against 703 / 492; N = 128 311 / 218 against
+// 312 / 171, N = 64 237 / 147 against 168 / 91: with 128 columns or fewer the staging of whole tiles for rows that
+// hold few entries costs more than the gathers it replaces, so such outputs take the schedule only where the tiled
+// kernels are forced (CSRK_KTILE=2, tests).
+bool sched_usable(const DeviceState &d, const csrk_plan_s *plan, int K, int N, int D, bool fused) {
+    const int mode = env_int("CSRK_KTILE", 1);
+    if (!plan || !plan->has_sched || env_int("CSRK_SCHED", 1) != 1 || mode == 3) return false;
+    if (N % 4 != 0 || N < 4 || N > kWideSlab || D % 4 != 0 || D > 64) return false;
+    if (N <= 128 && mode != 2) return false;
+    if (N > 128 && (long long)K * N * 4 >= (1ll << 32)) return false;
+    const double density = (double)plan->nnz / ((double)plan->M * (double)plan->K);
+    if (density < (double)wide_min_density(plan->M, K, N, fused, true)) return false;
+    if (d.fixed && sched_partial_floats(plan, N) > d.head_floats) return false;
+    return true;
+}
+
+csrk_status launch_sched_combine(DeviceState &d, const csrk_plan_s *plan, hipStream_t st, int N, float *O) {
+    const csrk_plan_s::Sched &k = plan->sched;
+    if (k.n_comb > 0)
+        hipLaunchKernelGGL(sched_combine_kernel, dim3(k.n_comb), dim3(256), 0, st, plan->M, N, N, kSchedRows, k.perm, k.comb,
+                           (const float *)d.head, O);
+    CSRK_HIP(hipGetLastError());
+    return CSRK_OK;
+}
+
+csrk_status sched_spmm(DeviceState &d, const csrk_plan_s *plan, hipStream_t st, int N, const float *v, const float *B,
+                       float *O) {
+    if (csrk_status s = ensure_scratch(d, N, sched_partial_floats(plan, N))) return s;
+    const int M = plan->M, K = plan->K;
+    const int32_t *rp = plan->rowptr, *ci = plan->colidx;
+    const SchedPart sp{plan->sched.perm, plan->sched.items, plan->sched.n_items, 0};
+    csrk_status s = N <= 32    ? launch_narrow_rows<8, 4>(d, st, M, K, N, rp, ci, v, B, O, 1, &sp)
+                    : N <= 64  ? launch_narrow_rows<4, 4>(d, st, M, K, N, rp, ci, v, B, O, 1, &sp)
+                    : N <= 128 ? launch_narrow_rows<2, 4>(d, st, M, K, N, rp, ci, v, B, O, 1, &sp)
+                    : N <= 256 ? launch_ktile_rows<1, 128, 4>(d, st, M, K, N, N, 0, rp, ci, v, B, O, 1, &sp)
+                               : launch_ktile_rows<2, 64, 4>(d, st, M, K, N, N, 0, rp, ci, v, B, O, 1, &sp);
+    if (s) return s;
+    return launch_sched_combine(d, plan, st, N, O);
+}
+
+csrk_status sched_fused(DeviceState &d, const csrk_plan_s *plan, hipStream_t st, int D, int N, const float *v,
+                        const float *A, const float *B, const float *C, float *O) {
+    if (csrk_status s = ensure_scratch(d, N, sched_partial_floats(plan, N))) return s;
+    const int M = plan->M, K = plan->K;
+    const int32_t *rp = plan->rowptr, *ci = plan->colidx;
+    const SchedPart sp{plan->sched.perm, plan->sched.items, plan->sched.n_items, 0};
+    csrk_status s =
+        N <= 32    ? launch_fused_narrow_rows<8, 4, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, 0, 0, &sp)
+        : N <= 64  ? launch_fused_narrow_rows<4, 4, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, 0, 0, &sp)
+        : N <= 128 ? launch_fused_narrow_rows<2, 4, 64>(d, st, M, K, D, N, rp, ci, v, A, B, C, O, 1, 0, 0, &sp)
+        : N <= 256 ? launch_fused_ktile_rows<1, 96, 4, 64>(d, st, M, K, D, N, N, 0, rp, ci, v, A, B, C, O, 1, &sp)
+                   : launch_fused_ktile_rows<2, 64, 4, 32>(d, st, M, K, D, N, N, 0, rp, ci, v, A, B, C, O, 1, &sp);
+    if (s) return s;
+    return launch_sched_combine(d, plan, st, N, O);
 }
 
 // --- validation kernels -------------------------------------------------------------
@@ -1080,6 +1261,11 @@ static csrk_status spmm_run(const csrk_plan_s *plan, const ScratchSource &scratc
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     rec.begin();
+    if (vec4 && sched_usable(*d, plan, K, N, 0, false)) {      // uneven rows, planned: the plan's schedule for the tiled kernels
+        const csrk_status s = sched_spmm(*d, plan, stream, N, vals, B, O);
+        rec.end();
+        return s;
+    }
     const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, N, 0);
     if (!small_tiled && vec4 && rows_mode_ok(M, K, N)) {
         const int wpr = rows_wpr(M, N);
@@ -1281,6 +1467,11 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scr
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     rec.begin();
+    if (nvec4 && dvec4 && D >= 4 && sched_usable(*d, plan, K, N, D, true)) {      // uneven rows, planned: the plan's schedule
+        const csrk_status s = sched_fused(*d, plan, stream, D, N, vals, A, B, C, O);
+        rec.end();
+        return s;
+    }
     const bool small_tiled = nvec4 && dvec4 && D <= 128 && plan_small_tiled(*d, plan, M, K, N, 2);
     if (!small_tiled && nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N)) {
         bool launched = false;
@@ -1489,7 +1680,9 @@ static ScratchSource plan_scratch(const csrk_plan_s *plan, int op, int N) {
     if (!plan->ws) return ScratchSource{};
     const DeviceInfo *info = nullptr;
     if (device_info(&info) != CSRK_OK) return ScratchSource{};
-    const size_t need = scratch_int_bytes(info->workers) + workspace_floats(*info, op, plan->M, plan->K, N) * sizeof(float);
+    size_t floats = workspace_floats(*info, op, plan->M, plan->K, N);
+    if (plan->has_sched && op != CSRK_OP_SDDMM && sched_partial_floats(plan, N) > floats) floats = sched_partial_floats(plan, N);
+    const size_t need = scratch_int_bytes(info->workers) + floats * sizeof(float);
     return need <= plan->ws_bytes ? ScratchSource{plan->ws, plan->ws_bytes} : ScratchSource{};
 }
 
@@ -1498,6 +1691,12 @@ csrk_status csrk_plan_reserve(csrk_plan *plan, int max_N) {
     if (max_N < 0 || max_N >= (1 << 24)) return fail(CSRK_INVALID_ARG, "csrk_plan_reserve: width out of range");
     size_t bytes = 0;
     if (csrk_status s = csrk_workspace_bytes(CSRK_OP_FUSEDMM, plan->M, plan->K, max_N, 0, &bytes)) return s;
+    if (plan->has_sched) {      // the partial rows of the plan's schedule for uneven rows
+        const DeviceInfo *info = nullptr;
+        if (csrk_status s = device_info(&info)) return s;
+        const size_t with_sched = scratch_int_bytes(info->workers) + sched_partial_floats(plan, max_N) * sizeof(float);
+        bytes = with_sched > bytes ? with_sched : bytes;
+    }
     if (plan->ws && plan->ws_bytes >= bytes) return CSRK_OK;
     void *mem = nullptr;
     if (hipMalloc(&mem, bytes) != hipSuccess) return fail(CSRK_WORKSPACE, "csrk_plan_reserve: cannot allocate %zu bytes", bytes);
@@ -1510,6 +1709,19 @@ csrk_status csrk_plan_reserve(csrk_plan *plan, int max_N) {
     }
     plan->ws = mem;
     plan->ws_bytes = bytes;
+    return CSRK_OK;
+}
+
+// frees what a plan owns (the caller holds g_mu, or the plan has not been handed out yet)
+static csrk_status csrk_plan_destroy_unlocked(csrk_plan_s *plan) {
+    hipError_t e = hipFree(plan->dflags);
+    for (void *mem : {plan->ws, plan->sched_mem})
+        if (mem) {
+            const hipError_t e2 = hipFree(mem);
+            if (e == hipSuccess) e = e2;
+        }
+    delete plan;
+    if (e != hipSuccess) return fail(CSRK_HIP_ERROR, "csrk_plan_destroy: hipFree: %s", hipGetErrorString(e));
     return CSRK_OK;
 }
 
@@ -1563,6 +1775,21 @@ csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t 
         delete plan;
         return fail(CSRK_HIP_ERROR, "csrk_plan_create: copying the plan's flag words failed");
     }
+    // uneven rows with ordered columns: a schedule for the tiled kernels (see csrk_plan_s::Sched)
+    if (plan->sorted && !plan->even && M >= 256 && K >= 2 * kSchedMinSegment && nnz > 0 && env_int("CSRK_SCHED", 1) == 1) {
+        std::vector<int32_t> rp((size_t)M + 1);
+        SchedHost host_sched;
+        if (hipMemcpyAsync(rp.data(), rowptr, rp.size() * sizeof(int32_t), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+            hipStreamSynchronize(stream) != hipSuccess) {
+            (void)csrk_plan_destroy_unlocked(plan);
+            return fail(CSRK_HIP_ERROR, "csrk_plan_create: reading rowptr back failed");
+        }
+        build_schedule(M, K, rp, d->cus, host_sched);
+        if (csrk_status s = upload_schedule(plan, host_sched, stream)) {
+            (void)csrk_plan_destroy_unlocked(plan);
+            return s;
+        }
+    }
     *out = plan;
     return CSRK_OK;
 }
@@ -1570,14 +1797,7 @@ csrk_status csrk_plan_create(int M, int K, const int32_t *rowptr, const int32_t 
 csrk_status csrk_plan_destroy(csrk_plan *plan) {
     if (!plan) return CSRK_OK;
     std::lock_guard<std::mutex> lock(g_mu);
-    hipError_t e = hipFree(plan->dflags);
-    if (plan->ws) {
-        const hipError_t e2 = hipFree(plan->ws);
-        if (e == hipSuccess) e = e2;
-    }
-    delete plan;
-    if (e != hipSuccess) return fail(CSRK_HIP_ERROR, "csrk_plan_destroy: hipFree: %s", hipGetErrorString(e));
-    return CSRK_OK;
+    return csrk_plan_destroy_unlocked(plan);
 }
 
 csrk_status csrk_plan_info(const csrk_plan *plan, long long *nnz, int *sorted, int *even) {
@@ -1846,7 +2066,8 @@ csrk_status csrk_tile_phases(int op, int M, int K, int D, int N, const int32_t *
             e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
             if (e == hipSuccess) {
                 hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, N, N, rowptr, colidx, vals,
-                                   C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim);
+                                   C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim,
+                                   (const int32_t *)nullptr, (const int4 *)nullptr);
                 e = hipGetLastError();
             }
         } else {
@@ -1855,7 +2076,8 @@ csrk_status csrk_tile_phases(int op, int M, int K, int D, int N, const int32_t *
             e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, L::kBytes);
             if (e == hipSuccess) {
                 hipLaunchKernelGGL(kern, dim3(groups), dim3(kTileThreads), L::kBytes, stream, M, K, D, N, N, rowptr, colidx,
-                                   vals, A, B, C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim);
+                                   vals, A, B, C, O, dflags, (float *)nullptr, no_inline, (int32_t *)nullptr, dtim,
+                                   (const int32_t *)nullptr, (const int4 *)nullptr);
                 e = hipGetLastError();
             }
         }

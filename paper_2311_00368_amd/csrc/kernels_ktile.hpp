@@ -195,16 +195,71 @@ __device__ __forceinline__ bool ksplit_block_unsorted(int M, const int32_t *__re
 struct KSplit {
     int kb, ke;
 };
+// One workgroup's job: a block of RB rows and a range of K.  A regular launch reads it off the grid (row block
+// blockIdx.x, range blockIdx.y of gridDim.y).  A launch over a plan's SCHEDULE for uneven rows (rows sorted by length
+// when the plan was made, so that the rows of a block are about equally long, and every block's K cut into as many
+// ranges as its share of the work asks for - the paper's NT work-items per row, section "SDDMM", with NT chosen per
+// block of rows) reads entry blockIdx.x of the schedule: x = block, y = range, z = ranges of that block, w = where
+// the block's partial rows of this range go in the scratch area (blocks whose K is cut).  The rows of block b are
+// perm[b * RB ...]; padding entries of perm hold M ("no row").
+struct TileJob {
+    int block, seg, nseg, slot;
+    bool sched;
+};
+__device__ __forceinline__ TileJob tile_job(const int4 *items) {
+    TileJob j;
+    j.sched = items != nullptr;
+    if (j.sched) {
+        const int4 it = items[blockIdx.x];
+        j.block = uniform(it.x);
+        j.seg = uniform(it.y);
+        j.nseg = uniform(it.z);
+        j.slot = uniform(it.w);
+    } else {
+        j.block = blockIdx.x;
+        j.seg = blockIdx.y;
+        j.nseg = gridDim.y;
+        j.slot = 0;
+    }
+    return j;
+}
 template <int KT>
-__device__ __forceinline__ KSplit ksplit_range(int K) {
+__device__ __forceinline__ KSplit job_range(const TileJob &j, int K) {
     const int tiles = (K + KT - 1) / KT;
-    const int per = (tiles + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int per = (tiles + j.nseg - 1) / j.nseg;
     KSplit r;
-    r.kb = (int)blockIdx.y * per * KT;
+    r.kb = j.seg * per * KT;
     r.ke = r.kb + per * KT;
     r.ke = r.ke < K ? r.ke : K;
     r.kb = r.kb < K ? r.kb : K;
     return r;
+}
+// the row of S at position idx of the job's block (M or more: no row)
+__device__ __forceinline__ int job_row(const TileJob &j, const int32_t *perm, int RB, int idx) {
+    return j.sched ? uniform(perm[j.block * RB + idx]) : j.block * RB + idx;
+}
+// where that row's result goes: its row of O, or - if the block's K is cut - a partial row in the scratch area
+__device__ __forceinline__ float *job_out(const TileJob &j, float *O, float *partial, int M, int ld, int RB, int idx,
+                                          int row) {
+    if (j.nseg <= 1) return O + (size_t)row * ld;
+    return partial + (j.sched ? (size_t)j.slot * RB + idx : (size_t)j.seg * M + row) * ld;
+}
+
+// Adds up the partial rows of the blocks of a schedule whose K was cut: one workgroup per such block (table entry:
+// x = block, y = first slot, z = ranges), in the order of the ranges - no float atomics, same bits every run.
+__global__ __launch_bounds__(256) void sched_combine_kernel(int M, int N, int ld, int RB, const int32_t *__restrict__ perm,
+                                                           const int4 *__restrict__ table, const float *__restrict__ partial,
+                                                           float *__restrict__ O) {
+    const int4 t = table[blockIdx.x];
+    const int n4 = N >> 2, ld4 = ld >> 2;
+    for (int e = threadIdx.x; e < RB * n4; e += blockDim.x) {
+        const int idx = e / n4, c4 = e % n4;
+        const int row = perm[t.x * RB + idx];
+        if (row >= M) continue;
+        f32x4 sum = reinterpret_cast<const f32x4 *>(partial)[((size_t)t.y * RB + idx) * ld4 + c4];
+        for (int s = 1; s < t.z; ++s) sum += reinterpret_cast<const f32x4 *>(partial)[((size_t)(t.y + s) * RB + idx) * ld4 + c4];
+        reinterpret_cast<f32x4 *>(O)[(size_t)row * ld4 + c4] = sum;
+    }
 }
 
 // position of the first entry of [p0, p1) whose column is >= kb (columns ascending)
@@ -283,7 +338,8 @@ template <int T, int KT, int ROWS, bool TIMED = false, int WAVES = kTileWaves>
 __global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kernel(
     int M, int K, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
-    float *partial, float inline_density, int32_t *other_flags, long long *tim = nullptr) {
+    float *partial, float inline_density, int32_t *other_flags, long long *tim = nullptr,
+    const int32_t *__restrict__ perm = nullptr, const int4 *__restrict__ items = nullptr) {
     using L = KTileLds<T, KT, WAVES>;
     constexpr int kThreads = WAVES * kWave;
     PhaseClock<TIMED> clk;
@@ -295,14 +351,16 @@ __global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kerne
     float *ct = lds;                        // KT x (T*256) floats
     int2 *ent = reinterpret_cast<int2 *>(lds + L::kCFloats) + wave * (2 * kWave);
 
-    const int row0 = blockIdx.x * (WAVES * ROWS) + wave * ROWS;
+    const TileJob job = tile_job(items);
+    constexpr int RB = WAVES * ROWS;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide tile
     const unsigned lane_b = (unsigned)lane * 4u;    // ... and its byte offset in a lane-wide load of a chunk
 
-    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split
-    if (gridDim.y > 1 && ksplit_block_unsorted<WAVES * ROWS>(M, rowptr, colidx)) {
+    const KSplit ks = job_range<KT>(job, K);    // the whole of K unless the job is one range of several
+    if (!job.sched && job.nseg > 1 && ksplit_block_unsorted<RB>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
+    int rows[ROWS];
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -310,10 +368,11 @@ __global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kerne
     unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
+        const int row = job_row(job, perm, RB, wave * ROWS + r);
+        rows[r] = row;
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
-        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
+        if (job.nseg > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const bool ok = lane < end[r] - pos[r];
         kc[r] = ok ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
         vc[r] = ok ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
@@ -496,14 +555,14 @@ __global__ __launch_bounds__(WAVES *kWave, WAVES == 16 ? 4 : 2) void ktile_kerne
     }
     clk.store(tim, WAVES, wave, lane);
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
+        const int row = rows[r];
         if (row < M) {
+            float *out = job_out(job, O, partial, M, ld, RB, wave * ROWS + r, row);
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * ld + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + n + tt * 256, acc[r][tt]);
         }
     }
 }

@@ -44,7 +44,8 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     int M, int K, int D, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
-    int32_t *other_flags, long long *tim = nullptr) {
+    int32_t *other_flags, long long *tim = nullptr, const int32_t *__restrict__ perm = nullptr,
+    const int4 *__restrict__ items = nullptr) {
     using L = FusedTileLds<T, KT, ROWS, SL>;
     PhaseClock<TIMED> clk;
     static_assert(SL == 32 || SL == 64, "slot sizes");
@@ -66,16 +67,18 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     const int i16 = lane & 15;
 
     static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
-    const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;
+    const TileJob job = tile_job(items);
+    constexpr int RB = kTileWaves * LIVE;
     const int n = lane * 4;                 // this lane's first column inside each 256-wide piece of the output
     const unsigned lane_b = (unsigned)lane * 4u;    // ... and its byte offset in a lane-wide load of a chunk
     const int my_r = (lane >> 4) / kGroupsPerRow;       // the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
-    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * LIVE>(M, rowptr, colidx)) {
+    const KSplit ks = job_range<KT>(job, K);    // the whole of K unless the job is one range of several
+    if (!job.sched && job.nseg > 1 && ksplit_block_unsorted<RB>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
+    int rows[ROWS];
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -83,11 +86,12 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
-        const bool live = r < LIVE && row < M;
+        const int row = r < LIVE ? job_row(job, perm, RB, wave * LIVE + r) : M;
+        rows[r] = row;
+        const bool live = row < M;
         pos[r] = live ? uniform(rowptr[row]) : 0;
         end[r] = live ? uniform(rowptr[row + 1]) : 0;
-        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
+        if (job.nseg > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const bool ok = lane < end[r] - pos[r];
         kc[r] = ok ? lane_elem(colidx + pos[r], lane_b) : 0x7fffffff;
         vc[r] = ok ? (vals ? lane_elem(vals + pos[r], lane_b) : 1.f) : 0.f;
@@ -97,7 +101,12 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             for (int v = 0; v < 4; ++v) acc[r][t][v] = 0.f;
     }
     float a[4] = {0.f, 0.f, 0.f, 0.f};      // piece i16 of this group's row of A, zero beyond D
-    if (my_r < LIVE && row0 + my_r < M && i16 * 4 < D) load_vec<4>(A + (size_t)(row0 + my_r) * D + i16 * 4, a);
+    {
+        int my_row = M;                     // the row of S this lane's group scores entries of
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) my_row = my_r == r ? rows[r] : my_row;
+        if (my_row < M && i16 * 4 < D) load_vec<4>(A + (size_t)my_row * D + i16 * 4, a);
+    }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
     const int n4 = N >> 2;                  // float4s of a row of C that this launch works on ...
@@ -424,14 +433,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     }
     clk.store(tim, kTileWaves, wave, lane);
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
-        if (r < LIVE && row < M) {
+        const int row = rows[r];
+        if (row < M) {
+            float *out = job_out(job, O, partial, M, ld, RB, wave * LIVE + r, row);   // K cut: a partial row, added up later
 #pragma unroll
             for (int tt = 0; tt < T; ++tt)
-                if (n + tt * 256 < N) store_vec<4>(out + (size_t)row * ld + n + tt * 256, acc[r][tt]);
+                if (n + tt * 256 < N) store_vec<4>(out + n + tt * 256, acc[r][tt]);
         }
     }
 }
@@ -457,7 +466,7 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     int M, int K, int D, int N, int ld, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ A, const float *__restrict__ Bmat,
     const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags, float *partial, float inline_density,
-    int32_t *other_flags) {
+    int32_t *other_flags, const int32_t *__restrict__ perm = nullptr, const int4 *__restrict__ items = nullptr) {
     using L = FusedNarrowLds<G, KT, ROWS, SL, DMAX>;
     static_assert(SL == 32 || SL == 64, "slot sizes");
     static_assert(ROWS == 1 || ROWS == 2 || ROWS == 4, "a row owns 4 / ROWS groups of 16 lanes");
@@ -486,16 +495,18 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     const int i16 = lane & 15;
 
     static_assert(LIVE >= 1 && LIVE <= ROWS, "rows owned within rows laid out");
-    const int row0 = blockIdx.x * (kTileWaves * LIVE) + wave * LIVE;
+    const TileJob job = tile_job(items);
+    constexpr int RB = kTileWaves * LIVE;
     const int g = lane / LN;                // accumulate stage: which of the G side-by-side entries
     const int n = (lane % LN) * 4;          // accumulate stage: this lane's first column
     const int my_r = (lane >> 4) / kGroupsPerRow;       // score stage: the row this lane's group scores entries of
     const int my_first = ((lane >> 4) % kGroupsPerRow) * 16 + i16;   // ... and which entry of a pass
 
-    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * LIVE>(M, rowptr, colidx)) {
+    const KSplit ks = job_range<KT>(job, K);    // the whole of K unless the job is one range of several
+    if (!job.sched && job.nseg > 1 && ksplit_block_unsorted<RB>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
+    int rows[ROWS];
     int pos[ROWS], end[ROWS];
     int kc[ROWS];
     float vc[ROWS];
@@ -503,11 +514,12 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     unsigned long long bad = 0;             // lanes that ever saw a descending pair of columns
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
-        const bool live = r < LIVE && row < M;
+        const int row = r < LIVE ? job_row(job, perm, RB, wave * LIVE + r) : M;
+        rows[r] = row;
+        const bool live = row < M;
         pos[r] = live ? uniform(rowptr[row]) : 0;
         end[r] = live ? uniform(rowptr[row + 1]) : 0;
-        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
+        if (job.nseg > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
@@ -515,11 +527,13 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
         acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0.f;
     }
     float a[H][4];                          // pieces i16 (and 16 + i16) of this group's row of A, zero beyond D
+    int my_row = M;                         // the row of S this lane's group scores entries of
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) my_row = my_r == r ? rows[r] : my_row;
 #pragma unroll
     for (int h = 0; h < H; ++h) {
         a[h][0] = a[h][1] = a[h][2] = a[h][3] = 0.f;
-        if (my_r < LIVE && row0 + my_r < M && (h * 16 + i16) * 4 < D)
-            load_vec<4>(A + (size_t)(row0 + my_r) * D + (h * 16 + i16) * 4, a[h]);
+        if (my_row < M && (h * 16 + i16) * 4 < D) load_vec<4>(A + (size_t)my_row * D + (h * 16 + i16) * 4, a[h]);
     }
 
     // ---- staging of the dense tiles: global -> registers (`issue`), registers -> LDS (`commit`)
@@ -768,15 +782,15 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernels behind this one redo the call
     // add the G partial rows of every row and store
-    float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * ld : O;   // K-split: ksplit_reduce adds them
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
 #pragma unroll
         for (int off = LN; off < kWave; off <<= 1)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
-        const int row = row0 + r;
-        if (r < LIVE && row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * ld + n, acc[r]);
+        const int row = rows[r];
+        if (row < M && g == 0 && n < N)         // K cut: a partial row, added up later
+            store_vec<4>(job_out(job, O, partial, M, ld, RB, wave * LIVE + r, row) + n, acc[r]);
     }
 }
 

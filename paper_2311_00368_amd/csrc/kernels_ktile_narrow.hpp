@@ -35,7 +35,8 @@ template <int G, int KT, int ROWS, int PF>
 __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     int M, int K, int N, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ vals, const float *__restrict__ Cmat, float *__restrict__ O, int32_t *flags,
-    float *partial, float inline_density, int32_t *other_flags) {
+    float *partial, float inline_density, int32_t *other_flags, const int32_t *__restrict__ perm = nullptr,
+    const int4 *__restrict__ items = nullptr) {
     using L = NarrowLds<G, KT>;
     constexpr int LN = kWave / G;           // lanes per entry
     constexpr int kRowBytes = L::kRowFloats * 4;
@@ -46,14 +47,16 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     float *ct = lds;
     int2 *ent = reinterpret_cast<int2 *>(lds + L::kCFloats) + wave * (2 * kWave);
 
-    const int row0 = blockIdx.x * (kTileWaves * ROWS) + wave * ROWS;
+    const TileJob job = tile_job(items);
+    constexpr int RB = kTileWaves * ROWS;
     const int g = lane / LN;                // which of the G side-by-side entries
     const int n = (lane % LN) * 4;          // this lane's first column
 
-    const KSplit ks = ksplit_range<KT>(K);  // the whole of K unless the launch is K-split (gridDim.y > 1)
-    if (gridDim.y > 1 && ksplit_block_unsorted<kTileWaves * ROWS>(M, rowptr, colidx)) {
+    const KSplit ks = job_range<KT>(job, K);    // the whole of K unless the job is one range of several
+    if (!job.sched && job.nseg > 1 && ksplit_block_unsorted<RB>(M, rowptr, colidx)) {
         if (lane == 0) flags[0] = 1;        // the reduction stands down, the general kernels redo the call
     }
+    int rows[ROWS];
     int pos[ROWS], end[ROWS];
     int kc[ROWS], kc2[ROWS];                // look-ahead: columns of the next 64 entries and of the 64 after them
     float vc[ROWS], vc2[ROWS];              // ... and their values
@@ -61,10 +64,11 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
     unsigned long long bad = 0;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int row = row0 + r;
+        const int row = job_row(job, perm, RB, wave * ROWS + r);
+        rows[r] = row;
         pos[r] = row < M ? uniform(rowptr[row]) : 0;
         end[r] = row < M ? uniform(rowptr[row + 1]) : 0;
-        if (gridDim.y > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
+        if (job.nseg > 1) pos[r] = first_entry_at_or_after(colidx, pos[r], end[r], ks.kb);
         const int j = pos[r] + lane;
         const bool ok = j < end[r];
         kc[r] = ok ? colidx[j] : 0x7fffffff;
@@ -239,9 +243,9 @@ __global__ __launch_bounds__(kTileThreads) void ktile_narrow_kernel(
         for (int off = LN; off < kWave; off <<= 1)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[r][v] += __shfl_xor(acc[r][v], off);
-        const int row = row0 + r;
-        float *out = gridDim.y > 1 ? partial + (size_t)blockIdx.y * M * N : O;   // K-split: ksplit_reduce adds them
-        if (row < M && g == 0 && n < N) store_vec<4>(out + (size_t)row * N + n, acc[r]);
+        const int row = rows[r];
+        if (row < M && g == 0 && n < N)         // K cut: a partial row, added up later
+            store_vec<4>(job_out(job, O, partial, M, N, RB, wave * ROWS + r, row) + n, acc[r]);
     }
     if (bad != 0 && lane == 0) flags[0] = 1;
 }
