@@ -640,6 +640,10 @@ csrk_status launch_sddmm_ktile_rows(DeviceState &d, hipStream_t st, int M, int K
     }
 }
 
+// a density threshold of the wide tiled kernels (outputs of more than 128 columns), marked for the row analysis as
+// one that goes with moderately uneven rows (row_analysis); "never" (1) and "always" (negative) stay what they are
+float uneven_ok(float min_density) { return min_density >= 0.f && min_density < 1.f ? min_density + kUnevenOk : min_density; }
+
 csrk_status launch_analysis(DeviceState &d, hipStream_t st, int M, int K, const int32_t *rp, float min_density) {
     int32_t *flags = tile_flags(d);
     // column order is verified inside the tiled kernels themselves
@@ -666,7 +670,9 @@ csrk_status tiled_attempt(DeviceState &d, const csrk_plan_s *plan, hipStream_t s
         }
         return launch_analysis(d, st, M, K, rp, min_density);
     }
-    const bool dense = (double)plan->nnz >= (double)min_density * (double)M * (double)K;
+    // (a plan knows `even` only; uneven patterns have their schedule, see sched_usable)
+    const float threshold = min_density >= kUnevenOk ? min_density - kUnevenOk : min_density;
+    const bool dense = (double)plan->nnz >= (double)threshold * (double)M * (double)K;
     *go = plan->sorted && (min_density < 0.f || (dense && plan->even));
     return CSRK_OK;
 }
@@ -1300,7 +1306,7 @@ static csrk_status spmm_run(const csrk_plan_s *plan, const ScratchSource &scratc
         // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
         // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
         const bool filled = tile_grid_for(*d, M, K, N <= 256 ? 128 : 64, kTileWaves * 4).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, false, filled), &go))
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, uneven_ok(wide_min_density(M, K, N, false, filled)), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);
@@ -1500,7 +1506,7 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scr
     } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
         const bool filled =
             tile_grid_for(*d, M, K, N <= 256 ? 96 : 64, kTileWaves * 4, fused_three_rows(*d, M, N)).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, wide_min_density(M, K, N, true, filled), &go))
+        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, uneven_ok(wide_min_density(M, K, N, true, filled)), &go))
             return s;
         if (go) {
             gate = tile_flags(*d);

@@ -54,6 +54,9 @@ namespace csrk {
 constexpr int kTileThreads = 1024;
 constexpr int kTileWaves = kTileThreads / kWave;
 
+// added to a density threshold handed to the row analysis: moderately uneven rows are acceptable (see row_analysis)
+constexpr float kUnevenOk = 4.f;
+
 // flags[0] != 0: some row has descending columns.  flags[1] != 0: dense enough.
 __device__ __forceinline__ bool ktile_ok(const int32_t *flags) { return flags[0] == 0 && flags[1] != 0; }
 
@@ -61,7 +64,12 @@ __device__ __forceinline__ bool ktile_ok(const int32_t *flags) { return flags[0]
 // nnz = rowptr[M] must reach `min_density` of M*K, and no row may be much longer than the mean row (the tiled
 // kernels give every wavefront a fixed set of rows and synchronise per tile, so skewed row lengths are left to
 // the equal-nonzero split of the general kernels).  A negative `min_density` switches both criteria off (used
-// by tests to reach the tiled kernels with any pattern).
+// by tests to reach the tiled kernels with any pattern).  kUnevenOk + threshold: the caller's kernel is one of the
+// wide ones (more than 128 output columns), for which moderately uneven rows - longest up to 16 mean rows - still
+// beat the general kernels' gathers of long dense rows (8192^2, log-normal row lengths with mean 10 % of K and
+// sigma 1, longest = 10 means, unplanned FusedMM D = 64 / SPMM: N = 512 680 / 452 us against 1570 / 1362, N = 256
+// 545 / 332 against 703 / 496; N = 128 and 64 the other way round, 394 / 206 against 313 / 171 and 327 / 145
+// against 182 / 101).
 //
 // Run by a whole workgroup of up to 1024 threads; `red` is room for 16 ints in LDS.  Returns, in every thread,
 // bit 0: the tiled kernel may run, bit 1: rows even (for the general kernels: rows can be dealt out whole).
@@ -92,10 +100,13 @@ __device__ __forceinline__ int row_analysis(int M, int K, const int32_t *__restr
     for (int w = 0; w < (int)(blockDim.x >> 6); ++w) longest = red[w] > longest ? red[w] : longest;
     const double nnz = (double)rowptr[M];
     const double mean = M > 0 ? nnz / (double)M : 0.0;
-    const bool dense = nnz >= (double)min_density * (double)M * (double)K;
+    const bool wide = min_density >= kUnevenOk;
+    const double threshold = wide ? (double)(min_density - kUnevenOk) : (double)min_density;
+    const bool dense = nnz >= threshold * (double)M * (double)K;
     const bool even = (double)longest <= 2.0 * mean + 64.0;
+    const bool suits = even || (wide && (double)longest <= 16.0 * mean + 64.0);
     __syncthreads();                         // `red` may be reused by the caller
-    return (((dense && even) || min_density < 0.f) ? 1 : 0) | (even ? 2 : 0);
+    return (((dense && suits) || min_density < 0.f) ? 1 : 0) | (even ? 2 : 0);
 }
 
 // The analysis as a launch of its own (one workgroup), ahead of tiled kernels on matrices with so many rows that

@@ -109,3 +109,28 @@ def test_skewed_8192_square_with_512_columns_planned(csrk):
     want, a = oracle.fusedmm(w.M, w.K, f["D"], f["N"], w.rowptr, w.colidx, w.vals, f["A"], f["B"], f["C"], rows=rows)
     check(O.cpu().numpy()[rows], want, a, "skewed 8192^2, N = 512, planned, every 7th row")
     p.close()
+
+
+@pytest.mark.parametrize("N", [256, 512])
+def test_unplanned_calls_on_uneven_rows_with_wide_outputs(csrk, N):
+    # Without a plan, outputs of more than 128 columns take the tiled kernels on moderately uneven rows as well
+    # (longest row up to 16 mean rows); beyond that the equal-share kernels.  Both against the oracle, every row.
+    M, K, D = 4096 + 11, 4096, 64
+    rng = np.random.default_rng(N)
+    A = rng.normal(size=(M, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    for name, (rp, ci) in {
+        "longest row about 10 mean rows": inputs.lognormal_csr(21, M, K, 0.1 * K, 1.0),
+        "a few full rows among short ones": skewed_pattern(22, M, K, 0.03 * K, sigma=0.5, full_rows=12, empty_rows=5),
+    }.items():
+        lens = np.diff(rp)
+        assert lens.max() > 2 * lens.mean() + 64
+        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+        d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
+        O = csrk.spmm_csr(M, K, N, d_rp, d_ci, d_v, dev(C))
+        want, a = oracle.spmm(M, K, N, rp, ci, v, C)
+        check(O.cpu().numpy(), want, a, f"unplanned spmm N={N}, {name}")
+        O = csrk.fusedmm_csr(M, K, D, N, d_rp, d_ci, d_v, dev(A), dev(B), dev(C))
+        want, a = oracle.fusedmm(M, K, D, N, rp, ci, v, A, B, C)
+        check(O.cpu().numpy(), want, a, f"unplanned fusedmm N={N}, {name}")
