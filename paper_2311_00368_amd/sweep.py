@@ -1,6 +1,7 @@
 """The paper's 72-shape benchmark grid as synthetic inputs, on one MI355X.
 
     python -m paper_2311_00368_amd.sweep [--out sweep72.md] [--iters 10] [--bf16 | --plan]
+    python -m paper_2311_00368_amd.sweep --skew [--out skew.md] [--iters 10]
 
 The grid is the one on the x axes of the paper's benchmark figures: 12 (M, K) pairs x sparsity
 70 / 80 / 90 % x N in {32, 128}, with D = N as in the paper.  The paper's own matrices (the
@@ -12,6 +13,11 @@ library records around each call's kernels.  Gflop/s use 2*nnz*N, 2*nnz*D and 2*
 
 The output is a markdown table; the bars of the paper's figures (Intel Data Center GPU Max 1550,
 one stack; other hardware, context only; `paper_grid_bars.txt`) are put next to the measured numbers.
+
+--skew: uneven rows instead of the grid.  The pattern of the `fused8k_skew` workload (8192 x 8192, row lengths
+log-normal with mean 10 % of K and sigma 1) with D = 64 and N in {64, 128, 256, 512}; SPMM and FusedMM, unplanned
+and planned, microseconds per call (minimum), and the same calls with the LDS-tiled kernels switched off
+(CSRK_KTILE=3: the equal-share kernels only) for comparison.
 """
 from __future__ import annotations
 
@@ -37,6 +43,56 @@ def paper_bars():
     return out
 
 
+def skew_table(args, torch, binding, inputs):
+    """Uneven rows: see the module text."""
+    import numpy as np
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    w = inputs.workload("fused8k_skew")
+    f = w.ops["fusedmm"]
+    M, K, D = w.M, w.K, f["D"]
+    rp, ci, v = dev(w.rowptr), dev(w.colidx), dev(w.vals)
+    A, B = dev(f["A"]), dev(f["B"])
+    lens = np.diff(w.rowptr)
+
+    def best_us(fn):
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        binding.csrk_profile_enable(args.iters)
+        for _ in range(args.iters):
+            fn()
+        torch.cuda.synchronize()
+        times = [ms for _, ms in binding.csrk_profile_collect(args.iters + 4)]
+        binding.csrk_profile_enable(0)
+        return min(times) * 1e3
+
+    lines = []
+    for n in (64, 128, 256, 512):
+        C = dev(inputs.uniform(0, inputs.STREAM_C, (K, n)))
+        O = torch.empty((M, n), dtype=torch.float32, device="cuda")
+        cells = []
+        for mode in ("1", "3"):             # automatic choice; LDS-tiled kernels off
+            os.environ["CSRK_KTILE"] = mode
+            plan = binding.csrk_plan_create(M, K, rp, ci)
+            cells += [best_us(lambda: binding.spmm_csr(M, K, n, rp, ci, v, C, O)),
+                      best_us(lambda: binding.spmm_csr_plan(plan, n, v, C, O)),
+                      best_us(lambda: binding.fusedmm_csr(M, K, D, n, rp, ci, v, A, B, C, O)),
+                      best_us(lambda: binding.fusedmm_csr_plan(plan, D, n, v, A, B, C, O))]
+            binding.csrk_plan_destroy(plan)
+        os.environ.pop("CSRK_KTILE", None)
+        lines.append((n, cells))
+        print(n, " ".join(f"{c:8.1f}" for c in cells), flush=True)
+    os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+    with open(args.out, "w") as fo:
+        fo.write(f"8192 x 8192, nnz = {w.nnz}, row lengths log-normal (mean {lens.mean():.0f}, longest {lens.max()}), D = 64; "
+                 f"microseconds per call, minimum over {args.iters} runs.\n\n")
+        fo.write("| N | SPMM | SPMM planned | FusedMM | FusedMM planned | equal shares only: SPMM | SPMM planned | FusedMM | FusedMM planned |\n")
+        fo.write("|---|---|---|---|---|---|---|---|---|\n")
+        for n, cells in lines:
+            fo.write(f"| {n} | " + " | ".join(f"{c:.1f}" for c in cells) + " |\n")
+    print(f"wrote {args.out}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="sweep72.md")
@@ -44,6 +100,7 @@ def main():
     ap.add_argument("--limit", type=int, default=0, help="only the first LIMIT grid points (debug)")
     ap.add_argument("--bf16", action="store_true",
                     help="dense operands rounded to bfloat16 and the *_csr_bf16 entry points instead of the FP32 ones")
+    ap.add_argument("--skew", action="store_true", help="uneven rows instead of the grid (see the module text)")
     ap.add_argument("--plan", action="store_true",
                     help="the pattern analysed once per shape (csrk_plan_create) and the *_csr_plan entry points: the "
                          "caller that reuses a pattern, and the paper's own protocol, which times kernels only")
@@ -58,6 +115,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("sweep needs a GPU")
     binding.load(build_if_missing=False)
+    if args.skew:
+        return skew_table(args, torch, binding, inputs)
     dev = lambda a: torch.from_numpy(a).cuda()
     bars = paper_bars()
     rows = []
