@@ -8,6 +8,7 @@ on the library's own scratch, on a plan's reserved workspace, and twice in a row
 import numpy as np
 import pytest
 
+import helpers
 import oracle
 from paper_2311_00368_amd import inputs
 from test_gpu_parity import check, csrk, dev  # noqa: F401  (csrk is a fixture)
@@ -134,3 +135,37 @@ def test_unplanned_calls_on_uneven_rows_with_wide_outputs(csrk, N):
         O = csrk.fusedmm_csr(M, K, D, N, d_rp, d_ci, d_v, dev(A), dev(B), dev(C))
         want, a = oracle.fusedmm(M, K, D, N, rp, ci, v, A, B, C)
         check(O.cpu().numpy(), want, a, f"unplanned fusedmm N={N}, {name}")
+
+
+@pytest.mark.parametrize("N", [64, 256])
+def test_scheduled_calls_on_adversarial_patterns(csrk, env, N):
+    # The degenerate cases of the row loop (empty rows in front, at the end and in runs; rows of length one; one row
+    # that holds every column among empty ones; lengths around the 64-entry chunks), each padded with empty rows to
+    # the 256 rows a schedule is made from, and one pattern in which a single row holds most of the entries.
+    env(CSRK_KTILE="2")
+    rng = np.random.default_rng(17)
+    K, D = 1024, 32
+    A0 = rng.normal(size=(4096, D)).astype(np.float32)
+    B = rng.normal(size=(K, D)).astype(np.float32)
+    C = rng.normal(size=(K, N)).astype(np.float32)
+    full = list(range(K))
+    lens = [0, 1, 63, 64, 65, 127, 128, 129, 255, 256, 257, 1000]
+    cases = {
+        "one full row among empty ones": [[]] * 100 + [full] + [[]] * 199,
+        "empty first and last, rows of length one and two long rows between":
+            [[]] * 3 + [[int(rng.integers(K))] for _ in range(150)] + [full[:500], full[300:]] + [[int(rng.integers(K))] for _ in range(150)] + [[]] * 3,
+        "ragged lengths": [sorted(rng.permutation(K)[:n].tolist()) for n in lens] * 22,
+        "one row with most of the entries": [sorted(rng.permutation(K)[:int(rng.integers(0, 6))].tolist()) for _ in range(299)] + [full],
+    }
+    for name, rows in cases.items():
+        M = len(rows)
+        rp, ci = helpers.csr_from_rows(rows, K)
+        lens_ = np.diff(rp)
+        assert M >= 256 and lens_.max() > 2 * lens_.mean() + 64, name
+        p = Planned(csrk, M, K, rp, ci)
+        _, sorted_, even = csrk.csrk_plan_info(p.plan)
+        assert sorted_ and not even, name
+        v = rng.uniform(-1, 1, len(ci)).astype(np.float32)
+        p.spmm(N, v, C)
+        p.fused(D, N, v, A0[:M], B, C)
+        p.close()
