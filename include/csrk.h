@@ -183,6 +183,26 @@ csrk_status fusedmm_csr_ws(int M, int K, int D, int N,
                            void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * Which kernel family a call would take (the paper chooses NT and nchunks from the
+ * shape, sections "SDDMM" and "SPMM"; here the choice is between kernel families).
+ * Host-only: no device is touched, the number of compute units `cus` is given.  The
+ * pattern is described by its number of stored entries and its longest row; columns
+ * are taken to ascend strictly in every row, operands to be 16-byte aligned and
+ * outputs not to alias inputs.  planned != 0: the choice of the *_plan calls.
+ * *family (host pointer) receives one of CSRK_FAMILY_*.  Used by the regression test
+ * that replays the choice against a recorded sweep of forced families.
+ */
+#define CSRK_FAMILY_GENERAL_SHARES 0  /* equal shares of the stored entries */
+#define CSRK_FAMILY_GENERAL_ROWS   1  /* the same kernels dealing out whole rows (rows found even) */
+#define CSRK_FAMILY_ROWS           2  /* whole-row kernels chosen by the host (small S) */
+#define CSRK_FAMILY_TILED_NARROW   3  /* LDS-tiled, outputs of up to 128 columns (per launch) */
+#define CSRK_FAMILY_TILED_WIDE     4  /* LDS-tiled, wider outputs */
+#define CSRK_FAMILY_TILED_SDDMM    5  /* LDS-tiled SDDMM */
+#define CSRK_FAMILY_SCHEDULE       6  /* a plan's schedule for uneven rows */
+csrk_status csrk_explain_choice(int op, int cus, int M, int K, int N, int D, long long nnz,
+                                int longest_row, int planned, int *family);
+
+/*
  * Plans: the sparsity pattern analysed once, for callers that use one pattern many
  * times (training loops; the paper's row analysis - nnzr, NT, nchunks of sections
  * "SDDMM" and "SPMM" - depends on the pattern alone).  The calls above look at the

@@ -169,6 +169,19 @@ def fusedmm_csr(M: int, K: int, D: int, N: int, rowptr, colidx, vals, A, B, C, O
 CSRK_OP_SPMM, CSRK_OP_SDDMM, CSRK_OP_FUSEDMM = 1, 2, 3
 
 
+FAMILY_NAMES = {0: "general, equal shares", 1: "general, whole rows", 2: "whole-row kernels", 3: "tiled narrow",
+                4: "tiled wide", 5: "tiled SDDMM", 6: "schedule"}
+
+
+def csrk_explain_choice(op: int, cus: int, M: int, K: int, N: int, D: int, nnz: int, longest_row: int,
+                        planned: bool = False) -> int:
+    """Which kernel family (CSRK_FAMILY_*, see FAMILY_NAMES) a call of this shape would take; host-only."""
+    fam = ctypes.c_int(-1)
+    _check(load().csrk_explain_choice(op, cus, M, K, N, D, ctypes.c_longlong(nnz), longest_row, 1 if planned else 0,
+                                      ctypes.byref(fam)))
+    return int(fam.value)
+
+
 def csrk_workspace_bytes(op: int, M: int, K: int, N: int, D: int = 0) -> int:
     """Bytes of workspace that a *_csr_ws call of this operation (CSRK_OP_*) and shape may need on the current device."""
     out = ctypes.c_size_t(0)

@@ -1238,11 +1238,143 @@ csrk_status static_scratch_ptr(void **out) {
     return CSRK_OK;
 }
 
+// --- which kernel family takes a call -------------------------------------------------------------------------
+// The host's part of the choice, from sizes, alignment and (planned calls) what the plan knows: one chain of
+// questions per operation, asked here and nowhere else.  A family with `gated` set is an ATTEMPT: the device's row
+// analysis (or the plan's facts) still has to find S dense enough (`min_density`) and its rows even enough.
+enum Family : int {
+    kFamGeneral = 0,    // equal shares of the stored entries, or whole rows where the rows are found even
+    kFamRows,           // whole-row kernels, chosen by the host alone (small S)
+    kFamNarrow,         // LDS-tiled, outputs of up to 128 columns
+    kFamWide,           // LDS-tiled, 132 to 2048 columns (beyond 512 in slabs)
+    kFamNarrowSlabs,    // FusedMM with dot products of 65-128 floats and a wide output: the narrow kernel per 128 columns
+    kFamSddmmTile,      // LDS-tiled SDDMM, dot products of up to 128 floats
+    kFamSddmmPieces,    // ... longer dot products, 128 floats at a time
+    kFamSchedule,       // a plan's schedule for uneven rows
+};
+struct Choice {
+    Family family = kFamGeneral;
+    float min_density = 0.f;
+    bool gated = false;
+};
+
+Choice choose_spmm(const DeviceState &d, const csrk_plan_s *plan, int M, int K, int N, bool vec4) {
+    if (!vec4) return Choice{};
+    if (sched_usable(d, plan, K, N, 0, false)) return Choice{kFamSchedule};
+    if (plan_small_tiled(d, plan, M, K, N, 0)) return Choice{kFamNarrow};
+    if (rows_mode_ok(M, K, N)) return Choice{kFamRows};
+    if (narrow_shape_ok(d, M, K, N, false)) {
+        const bool filled = tile_grid_for(d, M, K, N > 64 ? narrow_kt<2>() : narrow_kt<4>(), kTileWaves * 4).fill >= kWellFilled;
+        return Choice{kFamNarrow, narrow_min_density(M, K, N, false, filled), true};
+    }
+    if (ktile_shape_ok(d, M, K, N)) {
+        // (row analysis, then the LDS-tiled kernel; the general kernels behind it stand down unless S turns out
+        // unsuitable: unsorted columns, too sparse, rows too uneven)
+        const bool filled = tile_grid_for(d, M, K, N <= 256 ? 128 : 64, kTileWaves * 4).fill >= kWellFilled;
+        return Choice{kFamWide, uneven_ok(wide_min_density(M, K, N, false, filled)), true};
+    }
+    return Choice{};
+}
+
+Choice choose_sddmm(const DeviceState &d, const csrk_plan_s *plan, int M, int K, int D, bool vec4, bool in_place) {
+    if (!vec4) return Choice{};
+    if (plan_small_tiled(d, plan, M, K, D, 1)) return Choice{kFamSddmmTile};
+    if (dot_width_cfg(D, vec4).t == 1 && rows_mode_ok(M, K, D, plan == nullptr)) return Choice{kFamRows};
+    // In place (P aliases vals) a tiled kernel that meets unsorted columns has already overwritten values which the
+    // general kernel would need to redo the call: without a plan to vouch for the order, such calls skip the attempt.
+    const bool may_attempt = plan != nullptr || !in_place;
+    if (may_attempt && sddmm_tile_shape_ok(d, M, K, D)) return Choice{kFamSddmmTile, sddmm_min_density(M, K, D), true};
+    // Dot products longer than the 128 floats a row of the tile holds: 128 floats at a time, one launch of the
+    // tiled kernel per piece, the second and later pieces adding to P (each reads vals again, so not when P
+    // aliases vals).  16384^2 / 20 %, D = 256: 5.6 ms in the general kernel, whose gathers outgrow L2.
+    if (D > 128 && D <= kSddmmMaxD && !in_place && sddmm_tile_shape_ok(d, M, K, 128))
+        return Choice{kFamSddmmPieces, sddmm_min_density(M, K, 128), true};
+    return Choice{};
+}
+
+Choice choose_fused(const DeviceState &d, const csrk_plan_s *plan, int M, int K, int D, int N, bool nvec4, bool dvec4) {
+    if (!nvec4 || !dvec4) return Choice{};
+    if (D >= 4 && sched_usable(d, plan, K, N, D, true)) return Choice{kFamSchedule};
+    if (D > 128) return Choice{};
+    if (plan_small_tiled(d, plan, M, K, N, 2)) return Choice{kFamNarrow};
+    if (N <= 512 && rows_mode_ok(M, K, N)) return Choice{kFamRows};
+    if (narrow_shape_ok(d, M, K, N, true)) {
+        const int kt = D > 64 ? 128 : (N > 64 ? fused_narrow_kt<2, 64>() : fused_narrow_kt<4, 64>());
+        const bool filled = tile_grid_for(d, M, K, kt, kTileWaves * 4, fused_three_rows(d, M, N)).fill >= kWellFilled;
+        return Choice{kFamNarrow, narrow_min_density(M, K, N, true, filled), true};
+    }
+    if (D <= 64 && ktile_shape_ok(d, M, K, N)) {
+        const bool filled =
+            tile_grid_for(d, M, K, N <= 256 ? 96 : 64, kTileWaves * 4, fused_three_rows(d, M, N)).fill >= kWellFilled;
+        return Choice{kFamWide, uneven_ok(wide_min_density(M, K, N, true, filled)), true};
+    }
+    if (D > 64 && ktile_shape_ok(d, M, K, N)) {
+        // Dot products of 65 to 128 floats with a wide output: the wide kernel has no room for such rows of B beside
+        // its tile of C, so the narrow kernel takes the output 128 columns at a time, one launch per slab, each
+        // computing the scores again (half of a slab's work).  Measured on 16384^2 / 20 %, D = 128: N = 512
+        // 11.4 -> 4.9 ms, N = 256 5.6 -> 2.5 ms; level with the general kernels at 5 % (8192^2).
+        const float min_density =
+            env_int("CSRK_KTILE", 1) == 2 ? -1.f : ((long long)K * N * 4 >= (16ll << 20) ? 0.06f : 0.10f);
+        return Choice{kFamNarrowSlabs, min_density, true};
+    }
+    return Choice{};
+}
+
 }  // namespace
 
 extern "C" {
 
 const char *csrk_last_error(void) { return g_err; }
+
+csrk_status csrk_explain_choice(int op, int cus, int M, int K, int N, int D, long long nnz, int longest_row,
+                                int planned, int *family) {
+    if (!family) return fail(CSRK_INVALID_ARG, "csrk_explain_choice: family must not be NULL");
+    if (cus <= 0 || M <= 0 || K <= 0 || nnz < 0 || longest_row < 0)
+        return fail(CSRK_INVALID_ARG, "csrk_explain_choice: sizes must be positive");
+    DeviceState d;
+    d.cus = cus;
+    d.workers = (cus * 32 + kWavesPerBlock - 1) / kWavesPerBlock * kWavesPerBlock;
+    const double mean = (double)nnz / (double)M;
+    const bool even = (double)longest_row <= 2.0 * mean + 64.0;
+    csrk_plan_s facts{0, M, K, nnz, nullptr, nullptr, true, even, nullptr, nullptr, 0};
+    facts.has_sched = !even && M >= 256 && K >= 2 * kSchedMinSegment && nnz > 0;     // as csrk_plan_create decides
+    const csrk_plan_s *plan = planned ? &facts : nullptr;
+    Choice ch;
+    bool fused = false;
+    switch (op) {
+        case CSRK_OP_SPMM: ch = choose_spmm(d, plan, M, K, N, N % 4 == 0); break;
+        case CSRK_OP_SDDMM: ch = choose_sddmm(d, plan, M, K, D, D % 4 == 0 && D > 0, false); break;
+        case CSRK_OP_FUSEDMM:
+            ch = choose_fused(d, plan, M, K, D, N, N % 4 == 0, D % 4 == 0 && D > 0);
+            fused = true;
+            break;
+        default: return fail(CSRK_INVALID_ARG, "csrk_explain_choice: unknown operation %d", op);
+    }
+    bool attempted = false;
+    if (ch.gated) {     // what the row analysis (row_analysis in kernels_ktile.hpp) or the plan's facts would say
+        attempted = true;
+        const bool wide = ch.min_density >= kUnevenOk;
+        const double threshold = wide ? (double)(ch.min_density - kUnevenOk) : (double)ch.min_density;
+        const bool dense = (double)nnz >= threshold * (double)M * (double)K;
+        const bool suits = planned ? even : (even || (wide && (double)longest_row <= 16.0 * mean + 64.0));
+        if (!(ch.min_density < 0.f || (dense && suits))) ch.family = kFamGeneral;
+    }
+    switch (ch.family) {
+        case kFamRows: *family = CSRK_FAMILY_ROWS; break;
+        case kFamNarrow:
+        case kFamNarrowSlabs: *family = CSRK_FAMILY_TILED_NARROW; break;
+        case kFamWide: *family = CSRK_FAMILY_TILED_WIDE; break;
+        case kFamSddmmTile:
+        case kFamSddmmPieces: *family = CSRK_FAMILY_TILED_SDDMM; break;
+        case kFamSchedule: *family = CSRK_FAMILY_SCHEDULE; break;
+        default: {
+            // the general kernels deal out whole rows where they know the rows to be even
+            const bool asked = planned || attempted || (op != CSRK_OP_SDDMM && even_rows_worth_asking(d, M, K, fused));
+            *family = asked && even ? CSRK_FAMILY_GENERAL_ROWS : CSRK_FAMILY_GENERAL_SHARES;
+        }
+    }
+    return CSRK_OK;
+}
 
 const char *csrk_version(void) { return "csrk 0.1 gfx950"; }
 
@@ -1267,13 +1399,13 @@ static csrk_status spmm_run(const csrk_plan_s *plan, const ScratchSource &scratc
     const int32_t *gate = nullptr;
     CallRecord rec(1, stream);
     rec.begin();
-    if (vec4 && sched_usable(*d, plan, K, N, 0, false)) {      // uneven rows, planned: the plan's schedule for the tiled kernels
+    const Choice ch = choose_spmm(*d, plan, M, K, N, vec4);
+    if (ch.family == kFamSchedule) {
         const csrk_status s = sched_spmm(*d, plan, stream, N, vals, B, O);
         rec.end();
         return s;
     }
-    const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, N, 0);
-    if (!small_tiled && vec4 && rows_mode_ok(M, K, N)) {
+    if (ch.family == kFamRows) {
         const int wpr = rows_wpr(M, N);
         const dim3 rgrid = rows_grid(M, wpr, (N + tile - 1) / tile);
 #define CSRK_SPMM_ROWS_CASE(V, L, T)                                                                              \
@@ -1290,25 +1422,14 @@ static csrk_status spmm_run(const csrk_plan_s *plan, const ScratchSource &scratc
         CSRK_HIP(hipGetLastError());
         return CSRK_OK;
     }
-    bool go = false;
-    if (small_tiled) {
-        gate = tile_flags(*d);
-        if (csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O)) return s;
-    } else if (vec4 && narrow_shape_ok(*d, M, K, N, false)) {
-        const bool filled = tile_grid_for(*d, M, K, N > 64 ? narrow_kt<2>() : narrow_kt<4>(), kTileWaves * 4).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, false, filled), &go))
-            return s;
-        if (go) {
+    if (ch.family == kFamNarrow || ch.family == kFamWide) {
+        bool go = !ch.gated;
+        if (ch.gated)
+            if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, ch.min_density, &go)) return s;
+        if (go && ch.family == kFamNarrow) {
             gate = tile_flags(*d);
             if (csrk_status s = launch_narrow(*d, stream, M, K, N, rowptr, colidx, vals, B, O)) return s;
-        }
-    } else if (vec4 && ktile_shape_ok(*d, M, K, N)) {
-        // row analysis, then the LDS-tiled kernel; the general kernels below then stand down
-        // unless S turns out unsuitable (unsorted columns, too sparse, skewed rows)
-        const bool filled = tile_grid_for(*d, M, K, N <= 256 ? 128 : 64, kTileWaves * 4).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, uneven_ok(wide_min_density(M, K, N, false, filled)), &go))
-            return s;
-        if (go) {
+        } else if (go) {
             gate = tile_flags(*d);
             if (N <= kWideSlab) {
                 csrk_status s = N <= 256 ? launch_ktile<1, 128>(*d, stream, M, K, N, N, 0, rowptr, colidx, vals, B, O)
@@ -1379,8 +1500,8 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, const ScratchSource &scrat
     const int32_t *gate = nullptr;
     CallRecord rec(2, stream);
     rec.begin();
-    const bool small_tiled = vec4 && plan_small_tiled(*d, plan, M, K, D, 1);
-    if (!small_tiled && vec4 && c.t == 1 && rows_mode_ok(M, K, D, plan == nullptr)) {
+    const Choice ch = choose_sddmm(*d, plan, M, K, D, vec4, P == vals);
+    if (ch.family == kFamRows) {
         const int wpr = rows_wpr(M, D);
         const dim3 rgrid = rows_grid(M, wpr, 1);
 #define CSRK_SDDMM_ROWS_CASE(V, L, T)                                                                               \
@@ -1396,29 +1517,18 @@ static csrk_status sddmm_run(const csrk_plan_s *plan, const ScratchSource &scrat
         CSRK_HIP(hipGetLastError());
         return CSRK_OK;
     }
-    // In place (P aliases vals) a tiled kernel that meets unsorted columns has already overwritten values which the
-    // general kernel would need to redo the call: without a plan to vouch for the order, such calls skip the attempt.
-    const bool may_attempt = plan != nullptr || P != vals;
-    if (small_tiled || (vec4 && may_attempt && sddmm_tile_shape_ok(*d, M, K, D))) {
+    if (ch.family == kFamSddmmTile || ch.family == kFamSddmmPieces) {
         if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        bool go = small_tiled;
-        if (!go)
-            if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, sddmm_min_density(M, K, D), &go)) return s;
-        if (go) {
+        bool go = !ch.gated;
+        if (ch.gated)
+            if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, ch.min_density, &go)) return s;
+        if (go && ch.family == kFamSddmmTile) {
             gate = tile_flags(*d);
             csrk_status s = D <= 32   ? launch_sddmm_ktile_rows<32>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                             : D <= 64 ? launch_sddmm_ktile_rows<64>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P)
                                       : launch_sddmm_ktile_rows<128>(*d, stream, M, K, D, rowptr, colidx, vals, A, B, P);
             if (s) return s;
-        }
-    } else if (vec4 && D > 128 && D <= kSddmmMaxD && P != vals && sddmm_tile_shape_ok(*d, M, K, 128)) {
-        // Dot products longer than the 128 floats a row of the tile holds: 128 floats at a time, one launch of the
-        // tiled kernel per piece, the second and later pieces adding to P (each reads vals again, so not when P
-        // aliases vals).  16384^2 / 20 %, D = 256: 5.6 ms in the general kernel, whose gathers outgrow L2.
-        if (csrk_status s = ensure_scratch(*d, 1)) return s;
-        bool go = false;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, sddmm_min_density(M, K, 128), &go)) return s;
-        if (go) {
+        } else if (go) {
             gate = tile_flags(*d);
             for (int c0 = 0; c0 < D; c0 += 128)
                 if (csrk_status s = launch_sddmm_ktile_rows<128>(*d, stream, M, K, D - c0 < 128 ? D - c0 : 128, rowptr, colidx,
@@ -1473,13 +1583,13 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scr
     const int32_t *gate = nullptr;
     CallRecord rec(3, stream);
     rec.begin();
-    if (nvec4 && dvec4 && D >= 4 && sched_usable(*d, plan, K, N, D, true)) {      // uneven rows, planned: the plan's schedule
+    const Choice ch = choose_fused(*d, plan, M, K, D, N, nvec4, dvec4);
+    if (ch.family == kFamSchedule) {
         const csrk_status s = sched_fused(*d, plan, stream, D, N, vals, A, B, C, O);
         rec.end();
         return s;
     }
-    const bool small_tiled = nvec4 && dvec4 && D <= 128 && plan_small_tiled(*d, plan, M, K, N, 2);
-    if (!small_tiled && nvec4 && dvec4 && D <= 128 && N <= 512 && rows_mode_ok(M, K, N)) {
+    if (ch.family == kFamRows) {
         bool launched = false;
         if (dc.lg == 8) launched = launch_fused_rows_n<4, 8, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
         if (dc.lg == 16) launched = launch_fused_rows_n<4, 16, 1>(nc, stream, M, D, N, rowptr, colidx, vals, A, B, C, O);
@@ -1489,27 +1599,14 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scr
             CSRK_HIP(hipGetLastError());
             return CSRK_OK;
         }
-    }
-    bool go = false;
-    if (small_tiled) {
-        gate = tile_flags(*d);
-        if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
-    } else if (nvec4 && dvec4 && D <= 128 && narrow_shape_ok(*d, M, K, N, true)) {
-        const int kt = D > 64 ? 128 : (N > 64 ? fused_narrow_kt<2, 64>() : fused_narrow_kt<4, 64>());
-        const bool filled = tile_grid_for(*d, M, K, kt, kTileWaves * 4, fused_three_rows(*d, M, N)).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, narrow_min_density(M, K, N, true, filled), &go))
-            return s;
-        if (go) {
-            gate = tile_flags(*d);
+    } else if (ch.family != kFamGeneral) {
+        bool go = !ch.gated;
+        if (ch.gated)
+            if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, ch.min_density, &go)) return s;
+        if (go) gate = tile_flags(*d);
+        if (go && ch.family == kFamNarrow) {
             if (csrk_status s = launch_fused_narrow(*d, stream, M, K, D, N, rowptr, colidx, vals, A, B, C, O)) return s;
-        }
-    } else if (nvec4 && dvec4 && D <= 64 && ktile_shape_ok(*d, M, K, N)) {
-        const bool filled =
-            tile_grid_for(*d, M, K, N <= 256 ? 96 : 64, kTileWaves * 4, fused_three_rows(*d, M, N)).fill >= kWellFilled;
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, uneven_ok(wide_min_density(M, K, N, true, filled)), &go))
-            return s;
-        if (go) {
-            gate = tile_flags(*d);
+        } else if (go && ch.family == kFamWide) {
             if (N <= kWideSlab) {
                 csrk_status s =
                     N <= 256 ? launch_fused_ktile<1, 96, 64>(*d, stream, M, K, D, N, N, 0, rowptr, colidx, vals, A, B, C, O)
@@ -1526,20 +1623,9 @@ static csrk_status fusedmm_run(const csrk_plan_s *plan, const ScratchSource &scr
                     if (s) return s;
                 }
             }
-        }
-    } else if (nvec4 && dvec4 && D > 64 && D <= 128 && ktile_shape_ok(*d, M, K, N)) {
-        // Dot products of 65 to 128 floats with a wide output: the wide kernel has no room for such rows of B beside
-        // its tile of C, so the narrow kernel takes the output 128 columns at a time, one launch per slab, each
-        // computing the scores again (half of a slab's work).  Measured on 16384^2 / 20 %, D = 128: N = 512
-        // 11.4 -> 4.9 ms, N = 256 5.6 -> 2.5 ms; level with the general kernels at 5 % (8192^2).
-        constexpr int kSlab = 128;
-        const bool three = fused_three_rows(*d, M, kSlab);
-        const float min_density =
-            env_int("CSRK_KTILE", 1) == 2 ? -1.f : ((long long)K * N * 4 >= (16ll << 20) ? 0.06f : 0.10f);
-        if (csrk_status s = tiled_attempt(*d, plan, stream, M, K, rowptr, min_density, &go)) return s;
-        if (go) {
-            gate = tile_flags(*d);
-            const int S = ksplit_for(*d, M, K, fused_narrow_kt<2, 128>(), kTileWaves * 4, three);
+        } else if (go) {        // kFamNarrowSlabs
+            constexpr int kSlab = 128;
+            const int S = ksplit_for(*d, M, K, fused_narrow_kt<2, 128>(), kTileWaves * 4, fused_three_rows(*d, M, kSlab));
             for (int c0 = 0; c0 < N; c0 += kSlab) {
                 const int w = N - c0 < kSlab ? N - c0 : kSlab;
                 if (csrk_status s = launch_fused_narrow_g<2, 128>(*d, stream, M, K, D, w, rowptr, colidx, vals, A, B, C, O,

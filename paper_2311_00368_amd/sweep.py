@@ -2,6 +2,7 @@
 
     python -m paper_2311_00368_amd.sweep [--out sweep72.md] [--iters 10] [--bf16 | --plan]
     python -m paper_2311_00368_amd.sweep --skew [--out skew.md] [--iters 10]
+    python -m paper_2311_00368_amd.sweep --three-way [--out threeway.md] [--iters 10]
 
 The grid is the one on the x axes of the paper's benchmark figures: 12 (M, K) pairs x sparsity
 70 / 80 / 90 % x N in {32, 128}, with D = N as in the paper.  The paper's own matrices (the
@@ -18,6 +19,11 @@ one stack; other hardware, context only; `paper_grid_bars.txt`) are put next to 
 log-normal with mean 10 % of K and sigma 1) with D = 64 and N in {64, 128, 256, 512}; SPMM and FusedMM, unplanned
 and planned, microseconds per call (minimum), and the same calls with the LDS-tiled kernels switched off
 (CSRK_KTILE=3: the equal-share kernels only) for comparison.
+
+--three-way: every grid point and operation timed five times - automatic choice, the LDS-tiled kernels forced
+(CSRK_KTILE=2), the whole-row kernels forced (CSRK_KTILE=3 CSRK_ROWS=2), equal shares forced (CSRK_KTILE=3
+CSRK_ROWS=3), and a planned call - in microseconds per call (minimum), with the longest row of the pattern and the
+families that csrk_explain_choice names for the point (unplanned and planned).  The table is what tests/test_dispatch_choice.py replays the choice against.
 """
 from __future__ import annotations
 
@@ -93,6 +99,69 @@ def skew_table(args, torch, binding, inputs):
     print(f"wrote {args.out}")
 
 
+def three_way_table(args, torch, binding, inputs):
+    """Automatic choice against each forced family: see the module text."""
+    import numpy as np
+    dev = lambda a: torch.from_numpy(a).cuda()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    modes = (("auto", {}), ("tiled", {"CSRK_KTILE": "2"}), ("rows", {"CSRK_KTILE": "3", "CSRK_ROWS": "2"}),
+             ("shares", {"CSRK_KTILE": "3", "CSRK_ROWS": "3"}))
+    points = [(mk, sp, n) for mk in MK for sp in SPARSITY for n in WIDTHS]
+    if args.limit:
+        points = points[: args.limit]
+    lines = []
+    for (mk, kk), sp, n in points:
+        M, K, D = mk * 1024, kk * 1024, n
+        w = inputs.custom_workload(M, K, 1.0 - sp / 100.0, n, D)
+        nnz, longest = w.nnz, int(np.diff(w.rowptr).max())
+        rp, ci, v = dev(w.rowptr), dev(w.colidx), dev(w.vals)
+        A, B, C = dev(w.ops["fusedmm"]["A"]), dev(w.ops["fusedmm"]["B"]), dev(w.ops["fusedmm"]["C"])
+        O = torch.empty((M, n), dtype=torch.float32, device="cuda")
+        P = torch.empty((nnz,), dtype=torch.float32, device="cuda")
+        calls = (("spmm", binding.CSRK_OP_SPMM, lambda: binding.spmm_csr(M, K, n, rp, ci, v, C, O)),
+                 ("sddmm", binding.CSRK_OP_SDDMM, lambda: binding.sddmm_csr(M, K, D, rp, ci, v, A, B, P)),
+                 ("fusedmm", binding.CSRK_OP_FUSEDMM, lambda: binding.fusedmm_csr(M, K, D, n, rp, ci, v, A, B, C, O)))
+        plan = binding.csrk_plan_create(M, K, rp, ci)
+        planned_calls = {"spmm": lambda: binding.spmm_csr_plan(plan, n, v, C, O),
+                         "sddmm": lambda: binding.sddmm_csr_plan(plan, D, v, A, B, P),
+                         "fusedmm": lambda: binding.fusedmm_csr_plan(plan, D, n, v, A, B, C, O)}
+        for name, op, fn in calls:
+            us = {}
+            for mode, env in modes + (("planned", {}),):
+                if mode == "planned":
+                    fn = planned_calls[name]
+                for k in ("CSRK_KTILE", "CSRK_ROWS"):
+                    os.environ.pop(k, None)
+                os.environ.update(env)
+                fn()
+                fn()
+                torch.cuda.synchronize()
+                binding.csrk_profile_enable(args.iters)
+                for _ in range(args.iters):
+                    fn()
+                torch.cuda.synchronize()
+                us[mode] = min(ms for _, ms in binding.csrk_profile_collect(args.iters + 4)) * 1e3
+                binding.csrk_profile_enable(0)
+            for k in ("CSRK_KTILE", "CSRK_ROWS"):
+                os.environ.pop(k, None)
+            fam = binding.csrk_explain_choice(op, cus, M, K, n, D, nnz, longest)
+            famp = binding.csrk_explain_choice(op, cus, M, K, n, D, nnz, longest, planned=True)
+            lines.append((f"{mk}k/{kk}k/{n}/{sp}%", M, K, n, nnz, longest, name, us, fam, famp))
+            print(lines[-1][0], name, " ".join(f"{m} {t:8.1f}" for m, t in us.items()), binding.FAMILY_NAMES[fam], "/",
+                  binding.FAMILY_NAMES[famp], flush=True)
+        binding.csrk_plan_destroy(plan)
+        del rp, ci, v, A, B, C, O, P
+    os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+    with open(args.out, "w") as f:
+        f.write(f"| shape | M | K | N = D | nnz | longest row | operation | automatic | tiled forced | whole rows forced | equal shares forced | planned | family named by csrk_explain_choice ({cus} CUs) | ... for a planned call |\n")
+        f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+        for shape, M, K, n, nnz, longest, name, us, fam, famp in lines:
+            f.write(f"| {shape} | {M} | {K} | {n} | {nnz} | {longest} | {name} | {us['auto']:.1f} | {us['tiled']:.1f} | {us['rows']:.1f} | "
+                    f"{us['shares']:.1f} | {us['planned']:.1f} | {binding.FAMILY_NAMES[fam]} | {binding.FAMILY_NAMES[famp]} |\n")
+        f.write(f"\nMicroseconds per call (HIP-event pair around all kernels of a call), minimum over {args.iters} runs.\n")
+    print(f"wrote {args.out}")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default="sweep72.md")
@@ -101,6 +170,7 @@ def main():
     ap.add_argument("--bf16", action="store_true",
                     help="dense operands rounded to bfloat16 and the *_csr_bf16 entry points instead of the FP32 ones")
     ap.add_argument("--skew", action="store_true", help="uneven rows instead of the grid (see the module text)")
+    ap.add_argument("--three-way", action="store_true", help="automatic choice against forced families (see the module text)")
     ap.add_argument("--plan", action="store_true",
                     help="the pattern analysed once per shape (csrk_plan_create) and the *_csr_plan entry points: the "
                          "caller that reuses a pattern, and the paper's own protocol, which times kernels only")
@@ -117,6 +187,8 @@ def main():
     binding.load(build_if_missing=False)
     if args.skew:
         return skew_table(args, torch, binding, inputs)
+    if args.three_way:
+        return three_way_table(args, torch, binding, inputs)
     dev = lambda a: torch.from_numpy(a).cuda()
     bars = paper_bars()
     rows = []
