@@ -11,7 +11,8 @@ workload is the 16384 x 16384, 20 %-dense configuration the benchmark spec's target is
   value        GFLOP/s of the whole step, flops = 2*nnz*N (SPMM) + 2*nnz*D (SDDMM)
                + 2*nnz*(D+N) (FusedMM)
   ops          per operation, from one HIP-event pair around all kernels of a call: GFLOP/s (mean, median, best), the
-               fractions of the published FP32 peak and HBM bandwidth (algorithmic bytes) and of the three machine
+               fractions of the published FP32 peak and HBM bandwidth (algorithmic bytes, and the bytes counted by
+               rocprofv3 in a recorded run of the same kernel: hbm_counter_*) and of the three machine
                rates measured in this run (frac_*_measured), the rate at which gathered dense rows reach the ALUs
                (nnz * width * 4 bytes / time), one cold run (caches flushed by writing a 1 GiB buffer) and the wall
                time of the very first call (workspace allocation included)
@@ -225,9 +226,15 @@ def main():
             "gflops_avg": round(flops[name] / avg / 1e6, 1), "gflops_best": round(flops[name] / mn / 1e6, 1),
             "frac_fp32_peak": round(tf / FP32_VECTOR_PEAK_TFLOPS, 4),
             "hbm_algorithmic_bytes": int(hbm_bytes[name]),
+            "hbm_GBps": round(hbm_bytes[name] / avg / 1e6, 1),
             "frac_hbm_peak": round(hbm_bytes[name] / avg / 1e6 / HBM_PEAK_GBS, 4),
             "gathered_TBps": round(gather_bytes[name] / avg / 1e9, 2),
         }
+        counted, _ = hbm_traffic_from_profiles(args.workload, name)
+        if counted:         # FETCH_SIZE + WRITE_SIZE of a recorded rocprofv3 --pmc run of the same kernel
+            op_report[name]["hbm_counter_bytes"] = int(counted)
+            op_report[name]["hbm_counter_GBps"] = round(counted / avg / 1e6, 1)
+            op_report[name]["frac_hbm_peak_counter"] = round(counted / avg / 1e6 / HBM_PEAK_GBS, 4)
         if peaks:
             op_report[name]["frac_fma_measured"] = round(tf / peaks["fma_f32_TFLOPs"], 4)
             op_report[name]["frac_hbm_copy_measured"] = round(hbm_bytes[name] / avg / 1e6 / peaks["hbm_copy_GBps"], 4)

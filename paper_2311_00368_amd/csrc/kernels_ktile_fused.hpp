@@ -154,10 +154,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
             if (my_bpad[i]) stageb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
-    auto commit = [&]() {
+    // registers -> LDS: loads number [I0, I1) of the C tile; the B tile
+    auto commit_c = [&](auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
         f32x4 *dst = reinterpret_cast<f32x4 *>(ct);
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        for (int i = I0; i < I1; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+    };
+    auto commit_b = [&]() {
         f32x4 *dstb = reinterpret_cast<f32x4 *>(bt);
 #pragma unroll
         for (int i = 0; i < kPerB; ++i) {
@@ -186,12 +190,22 @@ __global__ __launch_bounds__(kTileThreads) void fused_ktile_kernel(
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         clk.lap(kPhBarrier1);
-        if constexpr (!kAllAhead && !kTail) {   // what no register could be spared for during the previous tile's arithmetic
+        if constexpr (!kAllAhead && !kTail) {
+            // What was prefetched goes to LDS first, so that those writes drain while the rest - what no register
+            // could be spared for during the previous tile's arithmetic - is being requested (requests first: the
+            // 16 wavefronts' loads fill the vector-memory queue for about 1000 cycles before a single LDS write is
+            // issued; 1.96 -> 1.89 ms at 16384^2 / 20 %).  The fence keeps the compiler from moving the loads up.
+            commit_c(I0{}, IPF{});
+            __builtin_amdgcn_sched_barrier(0);
             issue(k0, IPF{}, IEND{});
             issue_b(k0);
             clk.lap(kPhIssue);
+            commit_c(IPF{}, IEND{});
+            commit_b();
+        } else {
+            commit_c(I0{}, IEND{});
+            commit_b();
         }
-        commit();
         if constexpr (TIMED) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         clk.lap(kPhCommit);
         __syncthreads();
@@ -581,10 +595,14 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
             if (e < KT * kD4 && k0 + kk < K && c4 < d4) stageb[i] = srcb[(size_t)(k0 + kk) * d4 + c4];
         }
     };
-    auto commit = [&]() {
+    // registers -> LDS: loads number [I0, I1) of the C tile; the B tile
+    auto commit_c = [&](auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
         float4 *dst = reinterpret_cast<float4 *>(ct);
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+        for (int i = I0; i < I1; ++i) dst[i * kTileThreads + threadIdx.x] = stage[i];
+    };
+    auto commit_b = [&]() {
         float4 *dstb = reinterpret_cast<float4 *>(bt);
 #pragma unroll
         for (int i = 0; i < kPerB; ++i) {
@@ -602,10 +620,17 @@ __global__ __launch_bounds__(kTileThreads) void fused_narrow_kernel(
     for (int k0 = ks.kb; k0 < ks.ke; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         if constexpr (!kAllAhead) {
+            // what was prefetched goes to LDS before the rest is requested (see fused_ktile_kernel)
+            commit_c(I0{}, IPF{});
+            __builtin_amdgcn_sched_barrier(0);
             issue(k0, IPF{}, IEND{});
             issue_b(k0);
+            commit_c(IPF{}, IEND{});
+            commit_b();
+        } else {
+            commit_c(I0{}, IEND{});
+            commit_b();
         }
-        commit();
         __syncthreads();
         if constexpr (PF > 0) {
             if (k0 + KT < ks.ke) {              // lands while this tile is being worked on
