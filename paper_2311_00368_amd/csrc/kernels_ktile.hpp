@@ -679,15 +679,17 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
     // piece and write zeros; rows past K in the last tile re-read row K-1 and are never used.
     const size_t my_off = (size_t)my_kk * ld4 + (my_col ? my_c : d4n - 1);
     const size_t step_off = (size_t)kRound * ld4;
-    auto issue = [&](int k0) {
+    // loads number [I0, I1) of this thread for the tile that starts at row k0
+    auto issue = [&](int k0, auto i0c, auto i1c) {
+        constexpr int I0 = decltype(i0c)::value, I1 = decltype(i1c)::value;
         const float4 *src = reinterpret_cast<const float4 *>(Bmat);
         if (k0 + KT <= K) {
             const float4 *tile = src + (size_t)k0 * ld4;   // uniform
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) stage[i] = tile[i * step_off + my_off];
+            for (int i = I0; i < I1; ++i) stage[i] = tile[i * step_off + my_off];
         } else {                                           // last, partial tile: clamp the row
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) {
+            for (int i = I0; i < I1; ++i) {
                 const int k = k0 + i * kRound + my_kk;
                 stage[i] = src[(size_t)(k < K ? k : K - 1) * ld4 + (my_col ? my_c : d4n - 1)];
             }
@@ -703,15 +705,21 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
         }
     };
 
-    issue(0);
+    issue(0, std::integral_constant<int, 0>{}, std::integral_constant<int, kPer>{});
     for (int k0 = 0; k0 < K; k0 += KT) {
         __syncthreads();                    // previous tile fully consumed
         commit();
         __syncthreads();
-        if (k0 + KT < K) issue(k0 + KT);    // lands while this tile is being worked on
+        // The next tile is requested while this one is worked on, a share of a thread's loads ahead of each of the
+        // wavefront's rows rather than all of them behind the barrier: 16 wavefronts issuing 9 loads of 1 KB each at
+        // the same moment fill the vector-memory queue (64 bytes a clock) and sit in their load instructions before
+        // their first chunk; after the first row the wavefronts are no longer in step and the shares interleave.
+        const bool more = k0 + KT < K;
         const int kend = k0 + KT;
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
+        static_for<0, ROWS>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+            if (more)
+                issue(k0 + KT, std::integral_constant<int, r * kPer / ROWS>{}, std::integral_constant<int, (r + 1) * kPer / ROWS>{});
             float a[H][4];                  // this lane's pieces of the row of A
 #pragma unroll
             for (int h = 0; h < H; ++h) load_vec<4>(arows + r * DMAX + (h * 16 + (i16 & (S - 1))) * 4, a[h]);
@@ -787,7 +795,7 @@ __global__ __launch_bounds__(kTileThreads) void sddmm_ktile_kernel(
                 kc2[r] = colidx[j2];
                 vc2[r] = vsrc[j2];
             }
-        }
+        });
     }
     if (bad != 0 && lane == 0) flags[0] = 1;   // the general kernel behind this one redoes the call
 }
