@@ -83,3 +83,12 @@ def test_choice_at_the_benchmark_shapes(planned):
     assert binding.FAMILY_NAMES[binding.csrk_explain_choice(OPS["fusedmm"], cus, M, M, 64, 64, nnz, longest, planned)] == "general, equal shares"
     wide = binding.FAMILY_NAMES[binding.csrk_explain_choice(OPS["fusedmm"], cus, M, M, 512, 64, nnz, longest, planned)]
     assert wide == ("schedule" if planned else "tiled wide")
+
+
+def test_choice_function_refuses_nonsense():
+    with pytest.raises(Exception):
+        binding.csrk_explain_choice(99, 256, 1024, 1024, 64, 64, 1000, 10)
+    with pytest.raises(Exception):
+        binding.csrk_explain_choice(OPS["spmm"], 0, 1024, 1024, 64, 64, 1000, 10)
+    with pytest.raises(Exception):
+        binding.csrk_explain_choice(OPS["spmm"], 256, 0, 1024, 64, 64, 1000, 10)
